@@ -1,0 +1,244 @@
+/*
+ * mllm_stage.h -- C ABI of the MI355X (gfx950) pipeline-stage library.
+ *
+ * One call = the forward (or backward) pass of ONE pipeline stage's transformer layers over
+ * ONE packed microbatch on ONE GPU: the unit of work that a 1F1B pipeline schedule repeats per
+ * microbatch and per stage (Background and Motivation, Fig. 1).  A stage is a run of ViT encoder
+ * layers over visual tokens, optionally a linear connector, optionally LLM decoder layers over
+ * visual + text tokens (MLLM Architecture, Section 2.1; Fig. 1 caption).  The microbatch is a
+ * set of items, each with a variable number of visual and text tokens (Table 1: E_seq_len,
+ * L_seq_len; Data Profiler, Section 3.2), concatenated along the sequence dimension with batch
+ * size 1 (Model Profiler, "Memory Profiling").  Attention handles every original instance
+ * separately and causally; linear operations run over the whole concatenated sequence (Model
+ * Profiler, "Throughput Profiling").
+ *
+ * General rules
+ *   - Plain C99 types only.  "device" pointers are HIP device memory of the current device,
+ *     "host" pointers are ordinary host memory.  All bf16 tensors are row-major, raw 16-bit
+ *     patterns; matrices are stored [in, out] so that Y = X.W.
+ *   - The caller owns every buffer and the stream.  The library owns only the opaque handle.
+ *     mllm_stage_fwd / mllm_stage_bwd / mllm_op_* allocate nothing on the device.
+ *   - Every call returns a status.  All argument validation happens before the first kernel is
+ *     enqueued: on a status other than MLLM_OK and MLLM_ERR_HIP nothing was launched and no
+ *     output was touched.  mllm_last_error() returns a thread-local message for the last failure.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and return without waiting.  Host arrays are consumed before the call returns.
+ *   - One handle must not be used from two threads at once.  Same inputs give bitwise-identical
+ *     outputs (no atomics in any reduction).
+ */
+#ifndef MLLM_STAGE_H
+#define MLLM_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mllm_stage mllm_stage_t; /* opaque, library-owned */
+
+typedef enum {
+  MLLM_OK = 0,
+  MLLM_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  MLLM_ERR_DESC = 2,        /* inconsistent layer / stage descriptor                       */
+  MLLM_ERR_SHAPE = 3,       /* sizes do not fit the descriptor or the kernels' limits      */
+  MLLM_ERR_CU_SEQLENS = 4,  /* cu_seqlens not starting at 0, decreasing, or wrong total    */
+  MLLM_ERR_MASK_KIND = 5,   /* mask kind outside {BIDIR, CAUSAL}                           */
+  MLLM_ERR_INDEX = 6,       /* img_to_seq_row out of range or not strictly increasing      */
+  MLLM_ERR_WORKSPACE = 7,   /* saved / workspace buffer smaller than mllm_stage_sizes says */
+  MLLM_ERR_UNSUPPORTED = 8, /* valid request that this build does not implement            */
+  MLLM_ERR_HIP = 9          /* a HIP call or kernel launch reported an error               */
+} mllm_status_t;
+
+enum { MLLM_MASK_BIDIR = 0, MLLM_MASK_CAUSAL = 1 };                       /* per segment */
+enum { MLLM_LAYER_VIT = 0, MLLM_LAYER_DECODER = 1, MLLM_LAYER_PROJECTOR = 2 };
+enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
+
+/*
+ * One layer.  The paper names layers only by model family (Evaluation, Table 4), so the layer
+ * arithmetic is the standard pre-norm transformer:
+ *   VIT:       n = LayerNorm(x); [q|k|v] = n.W_qkv + b; o = attention (mask per segment);
+ *              x1 = x + o.W_o + b_o; n2 = LayerNorm(x1); y = x1 + GELU(n2.W_1 + b_1).W_2 + b_2
+ *   DECODER:   n = RMSNorm(x); [q|k|v] = n.W_qkv; rotary positions on q, k (half-split pairs
+ *              (i, i + head_dim/2), angle pos * rope_base^(-2i/head_dim), pos restarting at 0 in
+ *              every segment); grouped-query attention (kv head = q head / (n_q/n_kv));
+ *              x1 = x + o.W_o; n2 = RMSNorm(x1); y = x1 + (SiLU(n2.W_g) * n2.W_u).W_d
+ *   PROJECTOR: p = x.W_p + b_p, row i written to row img_to_seq_row[i] of the packed sequence
+ *              (the learnable connector of Section 2.1).
+ * Parameter tensors per layer, in order (all bf16, matrices [in, out], vectors [n]):
+ *   VIT:       ln1_g, ln1_b, w_qkv [d, 3d], b_qkv, w_o [d, d], b_o, ln2_g, ln2_b,
+ *              w_1 [d, f], b_1, w_2 [f, d], b_2
+ *   DECODER:   rms1_g, w_qkv [d, (n_q + 2 n_kv) hd], w_o [n_q hd, d], rms2_g,
+ *              w_gu [d, 2f] = [W_gate | W_up], w_d [f, d]
+ *   PROJECTOR: w_p [d_model, d_out], b_p
+ * Limits: head_dim in {64, 128}; d_model == n_q_heads * head_dim for VIT / DECODER; every width
+ * a multiple of 64; n_q_heads a multiple of n_kv_heads; act GELU_* for VIT, SWIGLU for DECODER.
+ */
+typedef struct {
+  int32_t kind;       /* MLLM_LAYER_*                                   */
+  int32_t d_model;    /* input width                                    */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t d_ff;       /* MLP width f                                    */
+  int32_t d_out;      /* PROJECTOR only: output width                   */
+  int32_t act;        /* MLLM_ACT_*                                     */
+  int32_t has_bias;   /* must be 1 for VIT / PROJECTOR, 0 for DECODER   */
+  float norm_eps;
+  float rope_base;    /* DECODER only                                   */
+} mllm_layer_desc_t;
+
+/* Layers in execution order: zero or more VIT, then at most one PROJECTOR, then zero or more
+ * DECODER.  Widths of consecutive layers must chain. */
+typedef struct {
+  int32_t n_layers;
+  const mllm_layer_desc_t* layers; /* host */
+} mllm_stage_desc_t;
+
+/* A packed token space: segment s covers rows cu_seqlens[s] .. cu_seqlens[s+1]-1.  Zero-length
+ * segments are allowed.  max_seqlen must be >= the longest segment. */
+typedef struct {
+  int32_t total_tokens;
+  int32_t n_segments;
+  int32_t max_seqlen;
+  const int32_t* cu_seqlens_host; /* host [n_segments + 1] */
+  const uint8_t* mask_kind_host;  /* host [n_segments], MLLM_MASK_* */
+} mllm_pack_t;
+
+/* img: segments are images (used by VIT and PROJECTOR layers).  seq: segments are samples
+ * (used by PROJECTOR and DECODER layers).  img_to_seq_row: host [img.total_tokens], the row of
+ * the packed sequence that each projected image token lands on; strictly increasing. */
+typedef struct {
+  mllm_pack_t img;
+  mllm_pack_t seq;
+  const int32_t* img_to_seq_row_host;
+} mllm_batch_t;
+
+/* Create / destroy a stage handle.  The descriptor is copied. */
+mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** out);
+void mllm_stage_destroy(mllm_stage_t* stage);
+
+/* Number of parameter tensors of the stage, and name / shape of tensor i (layer-major, in the
+ * order listed above).  `name` points to static storage. */
+size_t mllm_stage_param_count(const mllm_stage_t* stage);
+mllm_status_t mllm_stage_param_info(const mllm_stage_t* stage, size_t i, const char** name,
+                                    int32_t* layer, int64_t* rows, int64_t* cols);
+
+/* Bytes of the `saved` buffer (activations kept from forward to backward) and of the scratch
+ * `workspace` that fwd and bwd need for this microbatch. */
+mllm_status_t mllm_stage_sizes(const mllm_stage_t* stage, const mllm_batch_t* batch,
+                               size_t* saved_bytes, size_t* workspace_bytes);
+
+/*
+ * Forward pass of the stage.
+ *   params   host array of mllm_stage_param_count() device pointers (bf16)
+ *   x_img    device bf16 [img.total_tokens, d_model of the first layer]; required when the first
+ *            layer is VIT or PROJECTOR, ignored otherwise
+ *   x_seq    device bf16 [seq.total_tokens, d_llm]; required when the stage has a PROJECTOR or a
+ *            DECODER layer.  With a PROJECTOR the rows named by img_to_seq_row are ignored and
+ *            replaced by the projected image tokens; the buffer itself is not modified
+ *   y        device bf16 output: [img.total_tokens, d] when the last layer is VIT, else
+ *            [seq.total_tokens, d_llm]
+ *   saved    device buffer (256-byte aligned) that mllm_stage_bwd reads back
+ *   workspace device scratch (256-byte aligned); contents are undefined afterwards
+ */
+mllm_status_t mllm_stage_fwd(mllm_stage_t* stage, const mllm_batch_t* batch,
+                             const void* const* params, const void* x_img, const void* x_seq,
+                             void* y, void* saved, size_t saved_bytes, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward pass for the microbatch that the preceding mllm_stage_fwd call with the same `saved`
+ * buffer processed.
+ *   dy       device bf16, same shape as y
+ *   dx_img   device bf16 like x_img, or NULL if not wanted / not applicable
+ *   dx_seq   device bf16 like x_seq, or NULL; rows named by img_to_seq_row are written as 0
+ *   dparams  host array of device pointers, fp32, same shapes as params
+ *   accumulate  0: dparams are overwritten; non-zero: dparams += gradient (microbatches of one
+ *            optimizer step accumulate, cf. the N_mb microbatches of the Problem Formulation)
+ */
+mllm_status_t mllm_stage_bwd(mllm_stage_t* stage, const mllm_batch_t* batch,
+                             const void* const* params, const void* dy, const void* saved,
+                             size_t saved_bytes, void* dx_img, void* dx_seq, void* const* dparams,
+                             int accumulate, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* Thread-local description of the last error on this thread; never NULL, never freed. */
+const char* mllm_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Single operations of the path, exported so that each kernel can be checked on its own.
+ * They are the same kernels the stage calls.  All pointers are device pointers unless named
+ * *_host.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Dense contraction of the linear layers ("linear operations ... applied to the entire
+ * concatenated sequence at once", Model Profiler): C[M,N] = op(A).op(B) (+ bias) (+ residual).
+ *   a_layout 0: A stored [M,K] row-major; 1: A stored [K,M] row-major (contraction over rows)
+ *   b_layout 0: B stored [K,N] row-major; 1: B stored [N,K] row-major
+ *   out_fp32 0: C is bf16 [M,N]; 1: C is fp32 [M,N]; accumulate != 0 (fp32 only): C += product
+ *   bias bf16 [N] or NULL; residual bf16 [M,N] or NULL (bf16 output only)
+ * Contiguous dimensions must be multiples of 8. */
+mllm_status_t mllm_op_gemm(const void* a, const void* b, void* c, int64_t m, int64_t n, int64_t k,
+                           int a_layout, int b_layout, int out_fp32, int accumulate,
+                           const void* bias, const void* residual, void* hip_stream);
+
+/* Per-instance attention over a packed sequence (Model Profiler, "Throughput Profiling").
+ *   q [T, n_q, hd], k, v [T, n_kv, hd] bf16 with row strides (in elements) q_stride / kv_stride,
+ *   o [T, n_q, hd] bf16 (row stride o_stride), lse fp32 [n_q, T] (natural log-sum-exp of the
+ *   scaled scores), scale = 1/sqrt(hd) applied inside.
+ *   workspace: device scratch of at least mllm_op_attn_workspace_bytes(n_segments, T) bytes. */
+size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens);
+mllm_status_t mllm_op_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                               const mllm_pack_t* pack, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t head_dim, int64_t q_stride, int64_t kv_stride,
+                               int64_t o_stride, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+/* Backward of the above from (q, k, v, o, lse, do): dq, dk, dv bf16 with the strides of q / k / v.
+ * delta: fp32 scratch [n_q, T] (rowsum(dO * O)), overwritten. */
+mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, const void* o,
+                               const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                               float* delta, const mllm_pack_t* pack, int32_t n_q_heads,
+                               int32_t n_kv_heads, int32_t head_dim, int64_t q_stride,
+                               int64_t kv_stride, int64_t o_stride, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
+
+/* Row normalisation.  kind 0: LayerNorm (gamma, beta), 1: RMSNorm (gamma).  x, y bf16 [T, d];
+ * stats fp32 [2, T]: row 0 = 1/sqrt(var+eps) (or 1/sqrt(mean sq+eps)), row 1 = mean (LayerNorm). */
+mllm_status_t mllm_op_norm_fwd(int kind, const void* x, const void* gamma, const void* beta,
+                               void* y, float* stats, int64_t t, int64_t d, float eps,
+                               void* hip_stream);
+/* dx = norm backward of dy (bf16), plus `dres` (bf16 [T,d] or NULL) added to it; dgamma / dbeta
+ * fp32 [d] (accumulate != 0: +=).  partial: fp32 scratch of mllm_op_norm_bwd_partial_bytes. */
+size_t mllm_op_norm_bwd_partial_bytes(int64_t t, int64_t d);
+mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
+                               const float* stats, const void* dres, void* dx, float* dgamma,
+                               float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
+                               void* hip_stream);
+
+/* Rotary positions applied in place to the q and k column blocks of a packed [T, row_stride]
+ * bf16 buffer (n_heads heads of head_dim starting at column col0).  pos: device int32 [T];
+ * inverse != 0 rotates by the negative angle (the backward pass). */
+mllm_status_t mllm_op_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride,
+                           int64_t col0, int32_t n_heads, int32_t head_dim, float rope_base,
+                           int inverse, void* hip_stream);
+
+/* Activations.  act GELU_*: a = GELU(h), h [T, f].  act SWIGLU: a = SiLU(g) * u with
+ * gu = [g | u] of shape [T, 2f].  Backward writes dh [T, f] or dgu [T, 2f] from da and the
+ * saved pre-activation. */
+mllm_status_t mllm_op_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f,
+                              void* hip_stream);
+mllm_status_t mllm_op_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t,
+                              int64_t f, void* hip_stream);
+
+/* Column sums of a bf16 [T, n] matrix into fp32 [n] (bias gradients); accumulate != 0: +=.
+ * partial: fp32 scratch of mllm_op_colsum_partial_bytes(t, n). */
+size_t mllm_op_colsum_partial_bytes(int64_t t, int64_t n);
+mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* partial, int64_t t,
+                             int64_t n, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLLM_STAGE_H */

@@ -1,0 +1,290 @@
+"""ctypes binding of libmllm_stage.so: same names as the C ABI, argument marshalling only.
+
+Tensors are anything with `.data_ptr()` (PyTorch device tensors: PyTorch only provides device
+memory and the stream) or plain integer device addresses.  Every step of the path runs inside
+the library's kernels; there is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmllm_stage.so")
+
+MLLM_OK = 0
+STATUS_NAMES = ["MLLM_OK", "MLLM_ERR_NULL", "MLLM_ERR_DESC", "MLLM_ERR_SHAPE", "MLLM_ERR_CU_SEQLENS",
+                "MLLM_ERR_MASK_KIND", "MLLM_ERR_INDEX", "MLLM_ERR_WORKSPACE", "MLLM_ERR_UNSUPPORTED",
+                "MLLM_ERR_HIP"]
+
+EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", "mllm_stage_param_info",
+           "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
+           "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
+           "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
+           "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum"]
+
+
+class MllmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status, message))
+        self.status = status
+
+
+class LayerDescC(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
+                ("d_out", C.c_int32), ("act", C.c_int32), ("has_bias", C.c_int32),
+                ("norm_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class StageDescC(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerDescC))]
+
+
+class PackC(C.Structure):
+    _fields_ = [("total_tokens", C.c_int32), ("n_segments", C.c_int32), ("max_seqlen", C.c_int32),
+                ("cu_seqlens_host", C.POINTER(C.c_int32)), ("mask_kind_host", C.POINTER(C.c_uint8))]
+
+
+class BatchC(C.Structure):
+    _fields_ = [("img", PackC), ("seq", PackC), ("img_to_seq_row_host", C.POINTER(C.c_int32))]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library; raise if it was not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_2603_25120_amd.build`" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.mllm_last_error.restype = C.c_char_p
+    L.mllm_stage_create.argtypes = [C.POINTER(StageDescC), C.POINTER(vp)]
+    L.mllm_stage_destroy.argtypes = [vp]
+    L.mllm_stage_destroy.restype = None
+    L.mllm_stage_param_count.argtypes = [vp]
+    L.mllm_stage_param_count.restype = sz
+    L.mllm_stage_param_info.argtypes = [vp, sz, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
+    L.mllm_stage_sizes.argtypes = [vp, C.POINTER(BatchC), C.POINTER(sz), C.POINTER(sz)]
+    L.mllm_stage_fwd.argtypes = [vp, C.POINTER(BatchC), C.POINTER(vp), vp, vp, vp, vp, sz, vp, sz, vp]
+    L.mllm_stage_bwd.argtypes = [vp, C.POINTER(BatchC), C.POINTER(vp), vp, vp, sz, vp, vp, C.POINTER(vp), C.c_int, vp, sz, vp]
+    L.mllm_op_gemm.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
+    L.mllm_op_attn_workspace_bytes.argtypes = [i32, i32]
+    L.mllm_op_attn_workspace_bytes.restype = sz
+    L.mllm_op_attn_fwd.argtypes = [vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, sz, vp]
+    L.mllm_op_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, sz, vp]
+    L.mllm_op_norm_fwd.argtypes = [C.c_int, vp, vp, vp, vp, vp, i64, i64, C.c_float, vp]
+    L.mllm_op_norm_bwd_partial_bytes.argtypes = [i64, i64]
+    L.mllm_op_norm_bwd_partial_bytes.restype = sz
+    L.mllm_op_norm_bwd.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, i64, i64, vp]
+    L.mllm_op_rope.argtypes = [vp, vp, i64, i64, i64, i32, i32, C.c_float, C.c_int, vp]
+    L.mllm_op_act_fwd.argtypes = [C.c_int, vp, vp, i64, i64, vp]
+    L.mllm_op_act_bwd.argtypes = [C.c_int, vp, vp, vp, i64, i64, vp]
+    L.mllm_op_colsum_partial_bytes.argtypes = [i64, i64]
+    L.mllm_op_colsum_partial_bytes.restype = sz
+    L.mllm_op_colsum.argtypes = [vp, vp, C.c_int, vp, i64, i64, vp]
+    for name in EXPORTS:
+        fn = getattr(L, name)
+        if fn.restype is C.c_int and name not in ("mllm_last_error",):
+            fn.restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != MLLM_OK:
+        raise MllmError(status, lib().mllm_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    return int(t.numel() * t.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+class _PackKeep:
+    """ctypes view of a packed token space; keeps the NumPy arrays alive."""
+
+    def __init__(self, pack):
+        self.c = PackC()
+        if pack is None:
+            self.cu = np.zeros(1, dtype=np.int32)
+            self.mk = np.zeros(0, dtype=np.uint8)
+            n_seg, total, longest = 0, 0, 0
+        else:
+            self.cu = np.ascontiguousarray(pack.cu_seqlens, dtype=np.int32)
+            self.mk = np.ascontiguousarray(pack.mask_kind, dtype=np.uint8)
+            n_seg = len(self.mk)
+            total = int(getattr(pack, "total_tokens_override", self.cu[-1]))
+            longest = getattr(pack, "max_seqlen_override", None)
+            if longest is None:
+                longest = int(np.max(np.diff(self.cu))) if n_seg else 0
+        self.c.total_tokens, self.c.n_segments, self.c.max_seqlen = total, n_seg, int(longest)
+        self.c.cu_seqlens_host = self.cu.ctypes.data_as(C.POINTER(C.c_int32))
+        self.c.mask_kind_host = self.mk.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+class _BatchKeep:
+    def __init__(self, batch):
+        self.img = _PackKeep(getattr(batch, "img", None))
+        self.seq = _PackKeep(getattr(batch, "seq", None))
+        self.c = BatchC()
+        self.c.img, self.c.seq = self.img.c, self.seq.c
+        rows = getattr(batch, "img_to_seq_row", None)
+        if rows is not None:
+            self.rows = np.ascontiguousarray(rows, dtype=np.int32)
+            self.c.img_to_seq_row_host = self.rows.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _ptr_array(tensors: Sequence):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+# -------------------------------------------------------------------------------------------
+# stage entry points
+# -------------------------------------------------------------------------------------------
+def mllm_stage_create(layers: Sequence) -> int:
+    """layers: objects with the fields of mllm_layer_desc_t.  Returns the opaque handle."""
+    arr = (LayerDescC * len(layers))()
+    for i, l in enumerate(layers):
+        for f, _ in LayerDescC._fields_:
+            setattr(arr[i], f, getattr(l, f))
+    desc = StageDescC(len(layers), arr)
+    out = C.c_void_p()
+    _check(lib().mllm_stage_create(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def mllm_stage_destroy(handle: int) -> None:
+    lib().mllm_stage_destroy(handle)
+
+
+def mllm_stage_param_count(handle: int) -> int:
+    return int(lib().mllm_stage_param_count(handle))
+
+
+def mllm_stage_param_info(handle: int, i: int):
+    name, layer, rows, cols = C.c_char_p(), C.c_int32(), C.c_int64(), C.c_int64()
+    _check(lib().mllm_stage_param_info(handle, i, C.byref(name), C.byref(layer), C.byref(rows), C.byref(cols)))
+    return name.value.decode(), layer.value, rows.value, cols.value
+
+
+def mllm_stage_sizes(handle: int, batch):
+    bk = _BatchKeep(batch)
+    a, b = C.c_size_t(), C.c_size_t()
+    _check(lib().mllm_stage_sizes(handle, C.byref(bk.c), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def mllm_stage_fwd(handle, batch, params, x_img, x_seq, y, saved, workspace, stream=None,
+                   saved_bytes=None, workspace_bytes=None) -> None:
+    bk = _BatchKeep(batch)
+    _check(lib().mllm_stage_fwd(handle, C.byref(bk.c), _ptr_array(params), _ptr(x_img), _ptr(x_seq), _ptr(y),
+                                _ptr(saved), _nbytes(saved) if saved_bytes is None else saved_bytes,
+                                _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes,
+                                _stream(stream)))
+
+
+def mllm_stage_bwd(handle, batch, params, dy, saved, dx_img, dx_seq, dparams, accumulate, workspace,
+                   stream=None, saved_bytes=None, workspace_bytes=None) -> None:
+    bk = _BatchKeep(batch)
+    _check(lib().mllm_stage_bwd(handle, C.byref(bk.c), _ptr_array(params), _ptr(dy), _ptr(saved),
+                                _nbytes(saved) if saved_bytes is None else saved_bytes, _ptr(dx_img), _ptr(dx_seq),
+                                _ptr_array(dparams), int(accumulate), _ptr(workspace),
+                                _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream)))
+
+
+def mllm_last_error() -> str:
+    return lib().mllm_last_error().decode()
+
+
+# -------------------------------------------------------------------------------------------
+# single operations
+# -------------------------------------------------------------------------------------------
+def mllm_op_gemm(a, b, c, m, n, k, a_layout=0, b_layout=0, out_fp32=0, accumulate=0, bias=None,
+                 residual=None, stream=None) -> None:
+    _check(lib().mllm_op_gemm(_ptr(a), _ptr(b), _ptr(c), m, n, k, a_layout, b_layout, out_fp32, accumulate,
+                              _ptr(bias), _ptr(residual), _stream(stream)))
+
+
+def mllm_op_attn_workspace_bytes(n_segments: int, total_tokens: int) -> int:
+    return int(lib().mllm_op_attn_workspace_bytes(n_segments, total_tokens))
+
+
+def mllm_op_attn_fwd(q, k, v, o, lse, pack, n_q_heads, n_kv_heads, head_dim, q_stride, kv_stride, o_stride,
+                     workspace, stream=None) -> None:
+    pk = _PackKeep(pack)
+    _check(lib().mllm_op_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), C.byref(pk.c), n_q_heads,
+                                  n_kv_heads, head_dim, q_stride, kv_stride, o_stride, _ptr(workspace),
+                                  _nbytes(workspace), _stream(stream)))
+
+
+def mllm_op_attn_bwd(q, k, v, o, lse, d_o, dq, dk, dv, delta, pack, n_q_heads, n_kv_heads, head_dim, q_stride,
+                     kv_stride, o_stride, workspace, stream=None) -> None:
+    pk = _PackKeep(pack)
+    _check(lib().mllm_op_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk),
+                                  _ptr(dv), _ptr(delta), C.byref(pk.c), n_q_heads, n_kv_heads, head_dim,
+                                  q_stride, kv_stride, o_stride, _ptr(workspace), _nbytes(workspace),
+                                  _stream(stream)))
+
+
+def mllm_op_norm_fwd(kind, x, gamma, beta, y, stats, t, d, eps, stream=None) -> None:
+    _check(lib().mllm_op_norm_fwd(kind, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(stats), t, d, eps,
+                                  _stream(stream)))
+
+
+def mllm_op_norm_bwd_partial_bytes(t: int, d: int) -> int:
+    return int(lib().mllm_op_norm_bwd_partial_bytes(t, d))
+
+
+def mllm_op_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d,
+                     stream=None) -> None:
+    _check(lib().mllm_op_norm_bwd(kind, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(stats), _ptr(dres), _ptr(dx),
+                                  _ptr(dgamma), _ptr(dbeta), int(accumulate), _ptr(partial), t, d,
+                                  _stream(stream)))
+
+
+def mllm_op_rope(qk, pos, t, row_stride, col0, n_heads, head_dim, rope_base, inverse=0, stream=None) -> None:
+    _check(lib().mllm_op_rope(_ptr(qk), _ptr(pos), t, row_stride, col0, n_heads, head_dim, rope_base,
+                              int(inverse), _stream(stream)))
+
+
+def mllm_op_act_fwd(act, pre, a, t, f, stream=None) -> None:
+    _check(lib().mllm_op_act_fwd(act, _ptr(pre), _ptr(a), t, f, _stream(stream)))
+
+
+def mllm_op_act_bwd(act, da, pre, dpre, t, f, stream=None) -> None:
+    _check(lib().mllm_op_act_bwd(act, _ptr(da), _ptr(pre), _ptr(dpre), t, f, _stream(stream)))
+
+
+def mllm_op_colsum_partial_bytes(t: int, n: int) -> int:
+    return int(lib().mllm_op_colsum_partial_bytes(t, n))
+
+
+def mllm_op_colsum(x, out, accumulate, partial, t, n, stream=None) -> None:
+    _check(lib().mllm_op_colsum(_ptr(x), _ptr(out), int(accumulate), _ptr(partial), t, n, _stream(stream)))

@@ -1,0 +1,480 @@
+// Varlen block-diagonal flash attention for gfx950, forward and backward.
+//
+// "Attention operations are dependent on individual sequence lengths and must process each
+// original instance separately to maintain causal integrity" (Model Profiler, "Throughput
+// Profiling"): a packed [T, heads, hd] sequence is cut into segments by cu_seqlens; each segment
+// attends only to itself, bidirectionally (an image inside the ViT) or causally (a sample inside
+// the LLM).  The host turns the segments into a list of tiles, longest first.
+//
+// All three kernels compute score blocks TRANSPOSED so that a lane owns one query (or one key)
+// column of the 32x32 MFMA result: row statistics are then per-lane scalars plus one exchange
+// between the two half-wavefronts, and the probability block can be fed straight back as the
+// B operand of the next MFMA without leaving registers (the contraction-slot order of that
+// operand is a fixed permutation of the key/query rows, applied identically to the A operand,
+// which is fetched from LDS with the transposing read).
+//
+//   forward:  S^T = K.Q^T, online softmax, O^T += V^T.P^T
+//   dQ pass:  S^T, dP^T = V.dO^T, dS^T = P^T*(dP^T - delta), dQ^T += K^T.dS^T
+//   dK/dV:    S = Q.K^T, dP = dO.V^T, dV^T += dO^T.P, dK^T += Q^T.dS, looping the query tiles
+//             and the query heads of the GQA group, so dK/dV need no atomics.
+#include "common.h"
+#include "kernels.h"
+
+namespace mllm {
+
+namespace {
+
+constexpr int BKV = 64;   // key rows staged per step (forward, dQ)
+constexpr int BQ = 64;    // query rows staged per step (dK/dV)
+constexpr int APAD = 8;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// v_exp_f32: flushes tiny results to zero, which is what a masked or negligible probability wants.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+struct AttnParams {
+  const bf16_t* q; const bf16_t* k; const bf16_t* v; bf16_t* o; float* lse;
+  const bf16_t* d_o; bf16_t* dq; bf16_t* dk; bf16_t* dv; float* delta;
+  int64_t q_stride, kv_stride, o_stride;
+  int32_t T, Hq, Hkv;
+  const AttnTile* tiles;
+  float scale_log2e, scale;
+};
+
+// Stage ROWS x HD bf16 rows [row0, row0+ROWS) of a segment into LDS (zero beyond seg_len).
+template <int ROWS, int HD>
+struct RowTile {
+  static constexpr int NVEC = ROWS * HD / 8, PER_THREAD = NVEC / 256, VPR = HD / 8;
+  uint4 r[PER_THREAD];
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int64_t stride, int row0,
+                                       int seg_len, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; i++) {
+      int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
+      r[i] = (row0 + rr < seg_len)
+                 ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + rr) * stride + cc)
+                 : make_uint4(0, 0, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; i++) {
+      int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
+      *reinterpret_cast<uint4*>(lds + rr * (HD + APAD) + cc) = r[i];
+    }
+  }
+};
+
+// Natural-layout operand: row (r0 + lane%32), contraction values 16c + 8*(lane/32) .. +7.
+template <int STRIDE>
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int r0, int c, int lane) {
+  Frag8 f;
+  f.u = *reinterpret_cast<const uint4*>(tile + (r0 + (lane & 31)) * STRIDE + 16 * c + 8 * (lane >> 5));
+  return f.v;
+}
+// Transposed operand for the register-resident B operand built from a 32x32 accumulator:
+// output row (n0 + lane%32) of the tile's columns, contraction slots e = 0..7 standing for tile
+// rows k16 + 8*(e/4) + 4*(lane/32) + e%4.
+template <int STRIDE>
+__device__ __forceinline__ bf16x8 frag_cols_permuted(const bf16_t* tile, int k16, int n0, int lane) {
+  Frag8 f;
+  const int h = lane >> 5, nn = n0 + 16 * ((lane >> 4) & 1);
+  f.h[0] = lds_read_tr4(tile, STRIDE, k16 + 4 * h, nn, lane & 15);
+  f.h[1] = lds_read_tr4(tile, STRIDE, k16 + 8 + 4 * h, nn, lane & 15);
+  return f.v;
+}
+// Accumulator values 8*cc .. 8*cc+7 of a 32x32 block as a bf16 B operand.
+__device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int cc) {
+  Frag8 f;
+#pragma unroll
+  for (int e = 0; e < 4; e++) f.w[e] = pack_bf16x2(a[8 * cc + 2 * e], a[8 * cc + 2 * e + 1]);
+  return f.v;
+}
+__device__ __forceinline__ bf16x8 global_frag(const bf16_t* p, bool ok) {
+  Frag8 f;
+  f.u = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+  return f.v;
+}
+// Row index inside a 32x32 accumulator block held at position v by a lane of half h.
+__device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+
+// ---------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnParams p) {
+  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
+  const AttnTile t = p.tiles[blockIdx.y];
+  const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int qrow = t.tile0 + 32 * wave + (lane & 31);
+  const bool qok = qrow < t.seg_len;
+  const bf16_t* qp = p.q + (int64_t)(t.seg_start + qrow) * p.q_stride + head * HD + 8 * h;
+  bf16x8 qf[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) qf[c] = global_frag(qp + 16 * c, qok);
+
+  const bf16_t* kbase = p.k + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
+  const bf16_t* vbase = p.v + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
+  const int kv_end = t.causal ? min(t.seg_len, t.tile0 + ATTN_FWD_Q_TILE) : t.seg_len;
+  const int wave_last_q = t.tile0 + 32 * wave + 31;
+
+  f32x16 oacc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) oacc[d][v] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  RowTile<BKV, HD> lk, lv;
+  lk.load(kbase, p.kv_stride, 0, t.seg_len, tid);
+  lv.load(vbase, p.kv_stride, 0, t.seg_len, tid);
+  for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
+    __syncthreads();  // previous step's readers are done
+    lk.store(Ks, tid);
+    lv.store(Vs, tid);
+    __syncthreads();
+    if (kv0 + BKV < kv_end) {
+      lk.load(kbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
+      lv.load(vbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
+    }
+    if (t.causal && kv0 > wave_last_q) continue;  // wavefront-uniform
+    f32x16 s[BKV / 32];
+#pragma unroll
+    for (int b = 0; b < BKV / 32; b++) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) s[b][v] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; c++)
+        s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s[b], 0, 0, 0);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < BKV / 32; b++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int kv = kv0 + 32 * b + acc_row(v, h);
+        const bool vis = kv < t.seg_len && (!t.causal || kv <= qrow);
+        s[b][v] = vis ? s[b][v] * p.scale_log2e : -INFINITY;
+        mx = fmaxf(mx, s[b][v]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m - m_use);
+    float rs = 0.f;
+#pragma unroll
+    for (int b = 0; b < BKV / 32; b++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        s[b][v] = fast_exp2(s[b][v] - m_use);
+        rs += s[b][v];
+      }
+    l = l * alpha + rs;
+    m = m_new;
+#pragma unroll
+    for (int d = 0; d < ND; d++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) oacc[d][v] *= alpha;
+#pragma unroll
+    for (int b = 0; b < BKV / 32; b++)
+#pragma unroll
+      for (int cc = 0; cc < 2; cc++) {
+        const bf16x8 pf = acc_to_frag(s[b], cc);
+#pragma unroll
+        for (int d = 0; d < ND; d++)
+          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_permuted<STRIDE>(Vs, 32 * b + 16 * cc, 32 * d, lane), pf, oacc[d], 0, 0, 0);
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (!qok) return;
+  const float inv = 1.f / l;
+  bf16_t* op = p.o + (int64_t)(t.seg_start + qrow) * p.o_stride + head * HD;
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      uint2 w;
+      w.x = pack_bf16x2(oacc[d][4 * g4] * inv, oacc[d][4 * g4 + 1] * inv);
+      w.y = pack_bf16x2(oacc[d][4 * g4 + 2] * inv, oacc[d][4 * g4 + 3] * inv);
+      *reinterpret_cast<uint2*>(op + 32 * d + 8 * g4 + 4 * h) = w;
+    }
+  if (h == 0) p.lse[(int64_t)head * p.T + t.seg_start + qrow] = (m + log2f(l)) * LN2;
+}
+
+// ---------------------------------------------------------------------------------------------
+// delta[h][t] = sum_d dO[t,h,d] * O[t,h,d]
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                  float* __restrict__ delta, int64_t T, int Hq, int64_t o_stride) {
+  constexpr int G = HD / 8;  // lanes per (token, head)
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t pair = gid / G;
+  const int sub = (int)(gid % G);
+  float s = 0.f;
+  const bool ok = pair < T * Hq;
+  const int64_t tok = ok ? pair / Hq : 0;
+  const int hh = ok ? (int)(pair % Hq) : 0;
+  if (ok) {
+    const int64_t off = tok * o_stride + hh * HD + 8 * sub;
+    uint4 a = *reinterpret_cast<const uint4*>(o + off), b = *reinterpret_cast<const uint4*>(d_o + off);
+    s = bf16lo(a.x) * bf16lo(b.x) + bf16hi(a.x) * bf16hi(b.x) + bf16lo(a.y) * bf16lo(b.y) +
+        bf16hi(a.y) * bf16hi(b.y) + bf16lo(a.z) * bf16lo(b.z) + bf16hi(a.z) * bf16hi(b.z) +
+        bf16lo(a.w) * bf16lo(b.w) + bf16hi(a.w) * bf16hi(b.w);
+  }
+#pragma unroll
+  for (int off = G / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (ok && sub == 0) delta[(int64_t)hh * T + tok] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ pass: one workgroup per (query tile of 128, head), looping over key tiles.
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnParams p) {
+  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
+  const AttnTile t = p.tiles[blockIdx.y];
+  const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int qrow = t.tile0 + 32 * wave + (lane & 31);
+  const bool qok = qrow < t.seg_len;
+  const int64_t grow = t.seg_start + (qok ? qrow : 0);
+  const bf16_t* qp = p.q + grow * p.q_stride + head * HD + 8 * h;
+  const bf16_t* dop = p.d_o + grow * p.o_stride + head * HD + 8 * h;
+  bf16x8 qf[NC], dof[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) {
+    qf[c] = global_frag(qp + 16 * c, qok);
+    dof[c] = global_frag(dop + 16 * c, qok);
+  }
+  const float lse2 = qok ? p.lse[(int64_t)head * p.T + grow] * LOG2E : 0.f;
+  const float delta = qok ? p.delta[(int64_t)head * p.T + grow] : 0.f;
+
+  const bf16_t* kbase = p.k + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
+  const bf16_t* vbase = p.v + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
+  const int kv_end = t.causal ? min(t.seg_len, t.tile0 + ATTN_FWD_Q_TILE) : t.seg_len;
+  const int wave_last_q = t.tile0 + 32 * wave + 31;
+
+  f32x16 dqacc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) dqacc[d][v] = 0.f;
+
+  RowTile<BKV, HD> lk, lv;
+  lk.load(kbase, p.kv_stride, 0, t.seg_len, tid);
+  lv.load(vbase, p.kv_stride, 0, t.seg_len, tid);
+  for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
+    __syncthreads();
+    lk.store(Ks, tid);
+    lv.store(Vs, tid);
+    __syncthreads();
+    if (kv0 + BKV < kv_end) {
+      lk.load(kbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
+      lv.load(vbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
+    }
+    if (t.causal && kv0 > wave_last_q) continue;
+#pragma unroll
+    for (int b = 0; b < BKV / 32; b++) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < NC; c++) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Vs, 32 * b, c, lane), dof[c], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int kv = kv0 + 32 * b + acc_row(v, h);
+        const bool vis = qok && kv < t.seg_len && (!t.causal || kv <= qrow);
+        const float pr = vis ? fast_exp2(s[v] * p.scale_log2e - lse2) : 0.f;
+        s[v] = pr * (dp[v] - delta);   // dS^T
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; cc++) {
+        const bf16x8 dsf = acc_to_frag(s, cc);
+#pragma unroll
+        for (int d = 0; d < ND; d++)
+          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_permuted<STRIDE>(Ks, 32 * b + 16 * cc, 32 * d, lane), dsf, dqacc[d], 0, 0, 0);
+      }
+    }
+  }
+  if (!qok) return;
+  bf16_t* dqp = p.dq + grow * p.q_stride + head * HD;
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      uint2 w;
+      w.x = pack_bf16x2(dqacc[d][4 * g4] * p.scale, dqacc[d][4 * g4 + 1] * p.scale);
+      w.y = pack_bf16x2(dqacc[d][4 * g4 + 2] * p.scale, dqacc[d][4 * g4 + 3] * p.scale);
+      *reinterpret_cast<uint2*>(dqp + 32 * d + 8 * g4 + 4 * h) = w;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK/dV pass: one workgroup per (key tile of 128, kv head); each wavefront owns 32 key rows and
+// loops over the query heads of the group and the query tiles that can see its keys.
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
+  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * STRIDE];
+  __shared__ float lse_s[BQ], delta_s[BQ];
+  const AttnTile t = p.tiles[blockIdx.y];
+  const int kvh = blockIdx.x, grp = p.Hq / p.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int krow = t.tile0 + 32 * wave + (lane & 31);
+  const bool kok = krow < t.seg_len;
+  const int64_t gkrow = t.seg_start + (kok ? krow : 0);
+  const bf16_t* kp = p.k + gkrow * p.kv_stride + kvh * HD + 8 * h;
+  const bf16_t* vp = p.v + gkrow * p.kv_stride + kvh * HD + 8 * h;
+  bf16x8 kf[NC], vf[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) {
+    kf[c] = global_frag(kp + 16 * c, kok);
+    vf[c] = global_frag(vp + 16 * c, kok);
+  }
+  f32x16 dkacc[ND], dvacc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) { dkacc[d][v] = 0.f; dvacc[d][v] = 0.f; }
+
+  const int q_begin = t.causal ? (t.tile0 / BQ) * BQ : 0;
+  const int wave_first_k = t.tile0 + 32 * wave;
+  RowTile<BQ, HD> lq, ldo;
+  for (int j = 0; j < grp; j++) {
+    const int head = kvh * grp + j;
+    const bf16_t* qbase = p.q + (int64_t)t.seg_start * p.q_stride + head * HD;
+    const bf16_t* dobase = p.d_o + (int64_t)t.seg_start * p.o_stride + head * HD;
+    const float* lse_h = p.lse + (int64_t)head * p.T + t.seg_start;
+    const float* delta_h = p.delta + (int64_t)head * p.T + t.seg_start;
+    for (int q0 = q_begin; q0 < t.seg_len; q0 += BQ) {
+      lq.load(qbase, p.q_stride, q0, t.seg_len, tid);
+      ldo.load(dobase, p.o_stride, q0, t.seg_len, tid);
+      float my_lse = 0.f, my_delta = 0.f;
+      if (tid < BQ && q0 + tid < t.seg_len) {
+        my_lse = lse_h[q0 + tid] * LOG2E;
+        my_delta = delta_h[q0 + tid];
+      }
+      __syncthreads();  // previous step's readers are done
+      lq.store(Qs, tid);
+      ldo.store(dOs, tid);
+      if (tid < BQ) { lse_s[tid] = my_lse; delta_s[tid] = my_delta; }
+      __syncthreads();
+      if (t.causal && q0 + BQ - 1 < wave_first_k) continue;  // no query here sees this wave's keys
+#pragma unroll
+      for (int b = 0; b < BQ / 32; b++) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
+        }
+        f32x16 pr;
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int qi = 32 * b + acc_row(v, h);
+          const int qrow = q0 + qi;
+          const bool vis = kok && qrow < t.seg_len && (!t.causal || krow <= qrow);
+          pr[v] = vis ? fast_exp2(s[v] * p.scale_log2e - lse_s[qi]) : 0.f;
+          s[v] = pr[v] * (dp[v] - delta_s[qi]);   // dS
+        }
+#pragma unroll
+        for (int cc = 0; cc < 2; cc++) {
+          const bf16x8 pf = acc_to_frag(pr, cc), dsf = acc_to_frag(s, cc);
+#pragma unroll
+          for (int d = 0; d < ND; d++) {
+            dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols_permuted<STRIDE>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
+            dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols_permuted<STRIDE>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (!kok) return;
+  bf16_t* dkp = p.dk + gkrow * p.kv_stride + kvh * HD;
+  bf16_t* dvp = p.dv + gkrow * p.kv_stride + kvh * HD;
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      uint2 w;
+      w.x = pack_bf16x2(dkacc[d][4 * g4] * p.scale, dkacc[d][4 * g4 + 1] * p.scale);
+      w.y = pack_bf16x2(dkacc[d][4 * g4 + 2] * p.scale, dkacc[d][4 * g4 + 3] * p.scale);
+      *reinterpret_cast<uint2*>(dkp + 32 * d + 8 * g4 + 4 * h) = w;
+      w.x = pack_bf16x2(dvacc[d][4 * g4], dvacc[d][4 * g4 + 1]);
+      w.y = pack_bf16x2(dvacc[d][4 * g4 + 2], dvacc[d][4 * g4 + 3]);
+      *reinterpret_cast<uint2*>(dvp + 32 * d + 8 * g4 + 4 * h) = w;
+    }
+}
+
+AttnParams make_params(const AttnArgs& a) {
+  AttnParams p;
+  p.q = (const bf16_t*)a.q; p.k = (const bf16_t*)a.k; p.v = (const bf16_t*)a.v;
+  p.o = (bf16_t*)a.o; p.lse = a.lse; p.d_o = (const bf16_t*)a.d_o;
+  p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv; p.delta = a.delta;
+  p.q_stride = a.q_stride; p.kv_stride = a.kv_stride; p.o_stride = a.o_stride;
+  p.T = a.total_tokens; p.Hq = a.n_q_heads; p.Hkv = a.n_kv_heads;
+  p.tiles = nullptr;
+  p.scale = 1.0f / sqrtf((float)a.head_dim);
+  p.scale_log2e = p.scale * LOG2E;
+  return p;
+}
+
+}  // namespace
+
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
+  if (a.n_q_tiles == 0) return hipSuccess;
+  AttnParams p = make_params(a);
+  p.tiles = a.q_tiles;
+  dim3 grid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles), block(256);  // heads fastest: heavy tiles first
+  if (a.head_dim == 128) hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, block, 0, s, p);
+  else if (a.head_dim == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, block, 0, s, p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
+  if (a.n_q_tiles == 0) return hipSuccess;
+  AttnParams p = make_params(a);
+  const int64_t n = (int64_t)a.total_tokens * a.n_q_heads * (a.head_dim / 8);
+  dim3 dgrid((unsigned)((n + 255) / 256)), block(256);
+  dim3 qgrid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles);
+  dim3 kgrid((unsigned)a.n_kv_heads, (unsigned)a.n_kv_tiles);
+  if (a.head_dim == 128) {
+    hipLaunchKernelGGL(attn_delta_kernel<128>, dgrid, block, 0, s, (const bf16_t*)a.o,
+                       (const bf16_t*)a.d_o, a.delta, (int64_t)a.total_tokens, a.n_q_heads, a.o_stride);
+    p.tiles = a.kv_tiles;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, kgrid, block, 0, s, p);
+    p.tiles = a.q_tiles;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, qgrid, block, 0, s, p);
+  } else if (a.head_dim == 64) {
+    hipLaunchKernelGGL(attn_delta_kernel<64>, dgrid, block, 0, s, (const bf16_t*)a.o,
+                       (const bf16_t*)a.d_o, a.delta, (int64_t)a.total_tokens, a.n_q_heads, a.o_stride);
+    p.tiles = a.kv_tiles;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, kgrid, block, 0, s, p);
+    p.tiles = a.q_tiles;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, qgrid, block, 0, s, p);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mllm

@@ -1,0 +1,56 @@
+// Shared device-side helpers for the gfx950 kernels: bf16 conversion, MFMA fragment types,
+// LDS transposing reads, wavefront reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mllm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef uint16_t bf16_t;  // raw storage type in global memory
+
+#define MLLM_LDS __attribute__((address_space(3)))
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+union Frag8 {  // eight bf16 = one MFMA A/B operand of the k=16 (32x32) or k=32 (16x16) shapes
+  bf16x8 v;
+  uint4 u;
+  uint32_t w[4];
+  s16x4 h[2];
+};
+
+// LDS transposing read.  Within each group of 16 lanes, lane i returns
+// tile[k0 + e][n0 + i] for e = 0..3 when the lane passes the address of
+// tile[k0 + i/4][n0 + 4*(i%4)] (tile rows are `stride` elements apart).
+__device__ __forceinline__ s16x4 lds_read_tr4(const bf16_t* tile, int stride, int k0, int n0,
+                                              int lane16) {
+  const bf16_t* p = tile + (k0 + (lane16 >> 2)) * stride + n0 + 4 * (lane16 & 3);
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)p);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace mllm

@@ -1,0 +1,484 @@
+// HBM-bound kernels of the stage: LayerNorm / RMSNorm forward and backward (one wavefront per
+// row, wavefront reductions), rotary positions, GELU / SwiGLU forward and backward, bias-gradient
+// column sums, row scatter / gather for the connector.  All math in fp32 on bf16 storage, 16-byte
+// accesses, no atomics: every cross-row reduction is two deterministic stages.
+#include "common.h"
+#include "kernels.h"
+
+namespace mllm {
+
+namespace {
+
+constexpr int ROWS_PER_BLOCK = 4;  // 4 wavefronts, one row each
+
+__device__ __forceinline__ void unpack8(const uint4& u, float* f) {
+  f[0] = bf16lo(u.x); f[1] = bf16hi(u.x); f[2] = bf16lo(u.y); f[3] = bf16hi(u.y);
+  f[4] = bf16lo(u.z); f[5] = bf16hi(u.z); f[6] = bf16lo(u.w); f[7] = bf16hi(u.w);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                    pack_bf16x2(f[6], f[7]));
+}
+
+// ---------------------------------------------------------------------------------------------
+// normalisation forward: y = (x - mean) * rstd * gamma + beta   (LayerNorm, KIND 0)
+//                        y = x * rstd * gamma                   (RMSNorm,   KIND 1)
+// NV = 16-byte vectors per lane; the row lives in registers between the passes.
+// ---------------------------------------------------------------------------------------------
+template <int KIND, int NV>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict__ x,
+                                                       const bf16_t* __restrict__ gamma,
+                                                       const bf16_t* __restrict__ beta,
+                                                       bf16_t* __restrict__ y, float* __restrict__ stats,
+                                                       int64_t T, int d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int nvec = d >> 3;
+  float v[NV][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int c = lane + 64 * j;
+    if (c < nvec) {
+      uint4 u = *reinterpret_cast<const uint4*>(x + row * d + 8 * c);
+      unpack8(u, v[j]);
+#pragma unroll
+      for (int e = 0; e < 8; e++) sum += v[j][e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[j][e] = 0.f;
+    }
+  }
+  float mean = 0.f;
+  if (KIND == 0) mean = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int c = lane + 64 * j;
+    if (c < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        float t = v[j][e] - mean;
+        sq += t * t;
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+  if (lane == 0) {
+    stats[row] = rstd;
+    stats[T + row] = mean;
+  }
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int c = lane + 64 * j;
+    if (c < nvec) {
+      float g[8], b[8], o[8];
+      unpack8(*reinterpret_cast<const uint4*>(gamma + 8 * c), g);
+      if (KIND == 0) unpack8(*reinterpret_cast<const uint4*>(beta + 8 * c), b);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        o[e] = (v[j][e] - mean) * rstd * g[e];
+        if (KIND == 0) o[e] += b[e];
+      }
+      *reinterpret_cast<uint4*>(y + row * d + 8 * c) = pack8(o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// normalisation backward.  With xhat = (x - mean) * rstd and dxh = dy * gamma:
+//   LayerNorm: dx = (dxh - mean(dxh) - xhat * mean(dxh * xhat)) * rstd
+//   RMSNorm:   dx = (dxh - xhat * mean(dxh * xhat)) * rstd
+// plus the residual branch's gradient dres.  Each wavefront walks rows w, w + W, ... and keeps
+// its column sums of dy * xhat (and of dy) in registers; they go to partial[w][*].
+// ---------------------------------------------------------------------------------------------
+template <int KIND, int NV>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(
+    const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+    const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
+    float* __restrict__ partial, int64_t T, int d) {
+  const int lane = threadIdx.x & 63;
+  const int W = gridDim.x * ROWS_PER_BLOCK;
+  const int w = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  const int nvec = d >> 3;
+  uint4 graw[NV];           // gamma, packed
+  float dg[NV][8], db[NV][8];
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int c = lane + 64 * j;
+    graw[j] = c < nvec ? *reinterpret_cast<const uint4*>(gamma + 8 * c) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; }
+  }
+  for (int64_t row = w; row < T; row += W) {
+    const float rstd = stats[row];
+    const float mean = KIND == 0 ? stats[T + row] : 0.f;
+    uint4 xraw[NV], dyraw[NV];  // the row stays packed between the two passes
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      int c = lane + 64 * j;
+      if (c < nvec) {
+        xraw[j] = *reinterpret_cast<const uint4*>(x + row * d + 8 * c);
+        dyraw[j] = *reinterpret_cast<const uint4*>(dy + row * d + 8 * c);
+        float xv[8], dv[8], g[8];
+        unpack8(xraw[j], xv);
+        unpack8(dyraw[j], dv);
+        unpack8(graw[j], g);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          float xh = (xv[e] - mean) * rstd;
+          float dxh = dv[e] * g[e];
+          s1 += dxh;
+          s2 += dxh * xh;
+          dg[j][e] += dv[e] * xh;
+          db[j][e] += dv[e];
+        }
+      }
+    }
+    const float m2 = wave_sum(s2) / (float)d;
+    const float m1 = KIND == 0 ? wave_sum(s1) / (float)d : 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      int c = lane + 64 * j;
+      if (c < nvec) {
+        float xv[8], dv[8], g[8], o[8], r[8];
+        unpack8(xraw[j], xv);
+        unpack8(dyraw[j], dv);
+        unpack8(graw[j], g);
+        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * d + 8 * c), r);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          float xh = (xv[e] - mean) * rstd;
+          o[e] = (dv[e] * g[e] - m1 - xh * m2) * rstd;
+          if (dres) o[e] += r[e];
+        }
+        *reinterpret_cast<uint4*>(dx + row * d + 8 * c) = pack8(o);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int c = lane + 64 * j;
+    if (c < nvec) {
+      float* pg = partial + (int64_t)w * d + 8 * c;
+      *reinterpret_cast<float4*>(pg) = make_float4(dg[j][0], dg[j][1], dg[j][2], dg[j][3]);
+      *reinterpret_cast<float4*>(pg + 4) = make_float4(dg[j][4], dg[j][5], dg[j][6], dg[j][7]);
+      if (KIND == 0) {
+        float* pb = partial + (int64_t)(W + w) * d + 8 * c;
+        *reinterpret_cast<float4*>(pb) = make_float4(db[j][0], db[j][1], db[j][2], db[j][3]);
+        *reinterpret_cast<float4*>(pb + 4) = make_float4(db[j][4], db[j][5], db[j][6], db[j][7]);
+      }
+    }
+  }
+}
+
+// out[c] (+)= sum_p partial[p][c], p ascending: fixed order, bitwise reproducible.
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                       int P, int64_t n, int accumulate) {
+  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < P; p++) s += partial[(int64_t)p * n + c];
+  out[c] = accumulate ? out[c] + s : s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// rotary positions, in place, half-split pairs (i, i + hd/2); angle = pos * base^(-2i/hd).
+// One thread: one token, eight consecutive i, all heads.  Angles in fp64 so that positions in
+// the ten-thousands keep full fp32-accurate sines.
+// ---------------------------------------------------------------------------------------------
+__global__ void rope_kernel(bf16_t* __restrict__ qk, const int32_t* __restrict__ pos, int64_t T,
+                            int64_t row_stride, int64_t col0, int n_heads, int hd, double log2_base,
+                            int inverse) {
+  const int per_tok = hd >> 4;  // threads per token
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t t = gid / per_tok;
+  if (t >= T) return;
+  const int i0 = (int)(gid % per_tok) * 8;
+  const double p = (double)pos[t];
+  float cs[8], sn[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    double inv = exp2(-2.0 * (double)(i0 + e) / (double)hd * log2_base);
+    double s, c;
+    sincos(p * inv, &s, &c);
+    cs[e] = (float)c;
+    sn[e] = inverse ? -(float)s : (float)s;
+  }
+  bf16_t* base = qk + t * row_stride + col0 + i0;
+  const int half = hd >> 1;
+  for (int h = 0; h < n_heads; h++) {
+    bf16_t* p1 = base + h * hd;
+    float a[8], b[8], oa[8], ob[8];
+    unpack8(*reinterpret_cast<const uint4*>(p1), a);
+    unpack8(*reinterpret_cast<const uint4*>(p1 + half), b);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      oa[e] = a[e] * cs[e] - b[e] * sn[e];
+      ob[e] = b[e] * cs[e] + a[e] * sn[e];
+    }
+    *reinterpret_cast<uint4*>(p1) = pack8(oa);
+    *reinterpret_cast<uint4*>(p1 + half) = pack8(ob);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// activations
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_f(int act, float z) {
+  if (act == 1) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    return 0.5f * z * (1.f + tanhf(u));
+  }
+  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_grad_f(int act, float z) {
+  if (act == 1) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    float t = tanhf(u);
+    return 0.5f * (1.f + t) +
+           0.5f * z * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * z * z);
+  }
+  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) +
+         z * expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+
+__global__ void gelu_fwd_kernel(int act, const bf16_t* __restrict__ h, bf16_t* __restrict__ a, int64_t nvec) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float z[8], o[8];
+  unpack8(reinterpret_cast<const uint4*>(h)[i], z);
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] = gelu_f(act, z[e]);
+  reinterpret_cast<uint4*>(a)[i] = pack8(o);
+}
+__global__ void gelu_bwd_kernel(int act, const bf16_t* __restrict__ da, const bf16_t* __restrict__ h,
+                                bf16_t* __restrict__ dh, int64_t nvec) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float z[8], g[8], o[8];
+  unpack8(reinterpret_cast<const uint4*>(h)[i], z);
+  unpack8(reinterpret_cast<const uint4*>(da)[i], g);
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] = g[e] * gelu_grad_f(act, z[e]);
+  reinterpret_cast<uint4*>(dh)[i] = pack8(o);
+}
+// gu = [g | u], [T, 2f];  a = g * sigmoid(g) * u
+__global__ void swiglu_fwd_kernel(const bf16_t* __restrict__ gu, bf16_t* __restrict__ a, int64_t T, int64_t f) {
+  const int64_t vec_per_row = f >> 3;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T * vec_per_row) return;
+  const int64_t t = i / vec_per_row, c = (i % vec_per_row) * 8;
+  float g[8], u[8], o[8];
+  unpack8(*reinterpret_cast<const uint4*>(gu + t * 2 * f + c), g);
+  unpack8(*reinterpret_cast<const uint4*>(gu + t * 2 * f + f + c), u);
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] = g[e] / (1.f + expf(-g[e])) * u[e];
+  *reinterpret_cast<uint4*>(a + t * f + c) = pack8(o);
+}
+__global__ void swiglu_bwd_kernel(const bf16_t* __restrict__ da, const bf16_t* __restrict__ gu,
+                                  bf16_t* __restrict__ dgu, int64_t T, int64_t f) {
+  const int64_t vec_per_row = f >> 3;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T * vec_per_row) return;
+  const int64_t t = i / vec_per_row, c = (i % vec_per_row) * 8;
+  float g[8], u[8], d[8], og[8], ou[8];
+  unpack8(*reinterpret_cast<const uint4*>(gu + t * 2 * f + c), g);
+  unpack8(*reinterpret_cast<const uint4*>(gu + t * 2 * f + f + c), u);
+  unpack8(*reinterpret_cast<const uint4*>(da + t * f + c), d);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    float s = 1.f / (1.f + expf(-g[e]));
+    og[e] = d[e] * u[e] * (s + g[e] * s * (1.f - s));
+    ou[e] = d[e] * g[e] * s;
+  }
+  *reinterpret_cast<uint4*>(dgu + t * 2 * f + c) = pack8(og);
+  *reinterpret_cast<uint4*>(dgu + t * 2 * f + f + c) = pack8(ou);
+}
+
+// ---------------------------------------------------------------------------------------------
+// column sums (bias gradients), stage 1: row chunk blockIdx.y, 8 columns per thread
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void colsum_partial_kernel(const bf16_t* __restrict__ x, int64_t ldx,
+                                                            float* __restrict__ partial, int64_t T,
+                                                            int64_t n) {
+  const int64_t c = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 8;
+  if (c >= n) return;
+  const int P = gridDim.y;
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int64_t r = blockIdx.y; r < T; r += P) {
+    float v[8];
+    unpack8(*reinterpret_cast<const uint4*>(x + r * ldx + c), v);
+#pragma unroll
+    for (int e = 0; e < 8; e++) s[e] += v[e];
+  }
+  float* p = partial + (int64_t)blockIdx.y * n + c;
+  *reinterpret_cast<float4*>(p) = make_float4(s[0], s[1], s[2], s[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(s[4], s[5], s[6], s[7]);
+}
+
+__global__ void scatter_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                    const int32_t* __restrict__ rows, int64_t n_rows, int64_t vec_per_row,
+                                    int gather) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_rows * vec_per_row) return;
+  const int64_t r = i / vec_per_row, c = i % vec_per_row;
+  const int64_t other = rows[r];
+  if (gather) reinterpret_cast<uint4*>(dst)[r * vec_per_row + c] = reinterpret_cast<const uint4*>(src)[other * vec_per_row + c];
+  else reinterpret_cast<uint4*>(dst)[other * vec_per_row + c] = reinterpret_cast<const uint4*>(src)[r * vec_per_row + c];
+}
+__global__ void zero_rows_kernel(bf16_t* __restrict__ dst, const int32_t* __restrict__ rows,
+                                 int64_t n_rows, int64_t vec_per_row) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_rows * vec_per_row) return;
+  const int64_t r = rows[i / vec_per_row], c = i % vec_per_row;
+  reinterpret_cast<uint4*>(dst)[r * vec_per_row + c] = make_uint4(0, 0, 0, 0);
+}
+__global__ void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t nvec) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nvec) dst[i] = src[i];
+}
+
+inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+}  // namespace
+
+#define MLLM_NV_DISPATCH(NVEC, CALL)          \
+  if ((NVEC) <= 64) { CALL(1) }               \
+  else if ((NVEC) <= 128) { CALL(2) }         \
+  else if ((NVEC) <= 256) { CALL(4) }         \
+  else if ((NVEC) <= 512) { CALL(8) }         \
+  else { CALL(16) }
+
+hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const void* beta, void* y,
+                           float* stats, int64_t t, int64_t d, float eps, hipStream_t s) {
+  if (t == 0) return hipSuccess;
+  if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
+  dim3 grid(blocks_for(t, ROWS_PER_BLOCK)), block(256);
+#define CALL(NV)                                                                                  \
+  if (kind == 0) hipLaunchKernelGGL((norm_fwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)x, \
+      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, eps);              \
+  else hipLaunchKernelGGL((norm_fwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)x,           \
+      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, eps);
+  MLLM_NV_DISPATCH(d / 8, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+int64_t norm_bwd_partial_rows(int64_t t) {
+  int64_t blocks = (t + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+  if (blocks > 256) blocks = 256;
+  if (blocks < 1) blocks = 1;
+  return blocks * ROWS_PER_BLOCK;
+}
+
+hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
+                           const float* stats, const void* dres, void* dx, float* dgamma,
+                           float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
+                           hipStream_t s) {
+  if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
+  const int64_t W = norm_bwd_partial_rows(t);
+  dim3 grid((unsigned)(W / ROWS_PER_BLOCK)), block(256);
+#define CALL(NV)                                                                                   \
+  if (kind == 0) hipLaunchKernelGGL((norm_bwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d); \
+  else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
+  MLLM_NV_DISPATCH(d / 8, CALL)
+#undef CALL
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s, partial,
+                     dgamma, (int)W, d, accumulate);
+  if (kind == 0)
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s,
+                       partial + W * d, dbeta, (int)W, d, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride, int64_t col0,
+                       int32_t n_heads, int32_t head_dim, float rope_base, int inverse,
+                       hipStream_t s) {
+  if (t == 0 || n_heads == 0) return hipSuccess;
+  if (head_dim % 16 != 0 || row_stride % 8 != 0 || col0 % 8 != 0) return hipErrorInvalidValue;
+  const int64_t n = t * (head_dim / 16);
+  hipLaunchKernelGGL(rope_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (bf16_t*)qk, pos, t,
+                     row_stride, col0, (int)n_heads, (int)head_dim, log2((double)rope_base), inverse);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f, hipStream_t s) {
+  if (t == 0) return hipSuccess;
+  if (f % 8 != 0) return hipErrorInvalidValue;
+  const int64_t nvec = t * f / 8;
+  if (act == 2)
+    hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s,
+                       (const bf16_t*)pre, (bf16_t*)a, t, f);
+  else
+    hipLaunchKernelGGL(gelu_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, act,
+                       (const bf16_t*)pre, (bf16_t*)a, nvec);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t,
+                          int64_t f, hipStream_t s) {
+  if (t == 0) return hipSuccess;
+  if (f % 8 != 0) return hipErrorInvalidValue;
+  const int64_t nvec = t * f / 8;
+  if (act == 2)
+    hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s,
+                       (const bf16_t*)da, (const bf16_t*)pre, (bf16_t*)dpre, t, f);
+  else
+    hipLaunchKernelGGL(gelu_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, act,
+                       (const bf16_t*)da, (const bf16_t*)pre, (bf16_t*)dpre, nvec);
+  return hipGetLastError();
+}
+
+int64_t colsum_partial_rows(int64_t t) {
+  if (t < 1) return 1;
+  return t < 512 ? t : 512;
+}
+
+hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate, float* partial,
+                         int64_t t, int64_t n, hipStream_t s) {
+  if (n % 8 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
+  const int64_t P = colsum_partial_rows(t);
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks_for(n, 512), (unsigned)P), dim3(64), 0, s,
+                     (const bf16_t*)x, ldx, partial, t, n);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, partial,
+                     out, (int)P, n, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows,
+                               int64_t d, int gather, hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  if (d % 8 != 0) return hipErrorInvalidValue;
+  const int64_t n = n_rows * (d / 8);
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s,
+                     (const bf16_t*)src, (bf16_t*)dst, rows, n_rows, d / 8, gather);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_rows(void* dst, const int32_t* rows, int64_t n_rows, int64_t d,
+                            hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  if (d % 8 != 0) return hipErrorInvalidValue;
+  const int64_t n = n_rows * (d / 8);
+  hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (bf16_t*)dst,
+                     rows, n_rows, d / 8);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16 != 0) return hipErrorInvalidValue;
+  const int64_t nvec = (int64_t)(bytes / 16);
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, (const uint4*)src,
+                     (uint4*)dst, nvec);
+  return hipGetLastError();
+}
+
+}  // namespace mllm

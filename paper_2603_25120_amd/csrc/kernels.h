@@ -1,0 +1,70 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mllm {
+
+struct GemmArgs {
+  const void* a;
+  const void* b;
+  void* c;
+  int64_t m, n, k;
+  int64_t lda, ldb, ldc;   // leading dimensions (elements) of the matrices as stored
+  int a_layout;            // 0: A stored [M,K]; 1: A stored [K,M]
+  int b_layout;            // 0: B stored [K,N]; 1: B stored [N,K]
+  int out_fp32;            // 0: bf16 C; 1: fp32 C
+  int accumulate;          // fp32 C only: C += product
+  const void* bias;        // bf16 [N] or null
+  const void* residual;    // bf16 [M,N] (ld = ldres) or null; bf16 C only
+  int64_t ldres;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// One entry per (segment, query tile) or (segment, key tile); built on the host, longest first.
+struct AttnTile {
+  int32_t seg_start;  // first packed row of the segment
+  int32_t seg_len;
+  int32_t tile0;      // first row of the tile inside the segment
+  int32_t causal;
+};
+struct AttnArgs {
+  const void* q; const void* k; const void* v; void* o; float* lse;
+  const void* d_o; void* dq; void* dk; void* dv; float* delta;
+  int64_t q_stride, kv_stride, o_stride;   // row strides in elements (dq/dk/dv/do share them)
+  int32_t total_tokens, n_q_heads, n_kv_heads, head_dim;
+  const AttnTile* q_tiles; int32_t n_q_tiles;     // device
+  const AttnTile* kv_tiles; int32_t n_kv_tiles;   // device
+};
+constexpr int ATTN_FWD_Q_TILE = 128;   // query rows per workgroup, forward and dQ pass
+constexpr int ATTN_BWD_KV_TILE = 128;  // key rows per workgroup, dK/dV pass
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
+
+// kind 0 LayerNorm, 1 RMSNorm.  stats: [2][T] fp32 (rstd, mean).
+hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const void* beta, void* y,
+                           float* stats, int64_t t, int64_t d, float eps, hipStream_t s);
+int64_t norm_bwd_partial_rows(int64_t t);
+hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
+                           const float* stats, const void* dres, void* dx, float* dgamma,
+                           float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
+                           hipStream_t s);
+hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride, int64_t col0,
+                       int32_t n_heads, int32_t head_dim, float rope_base, int inverse,
+                       hipStream_t s);
+hipError_t launch_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f, hipStream_t s);
+hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t,
+                          int64_t f, hipStream_t s);
+int64_t colsum_partial_rows(int64_t t);
+hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate, float* partial,
+                         int64_t t, int64_t n, hipStream_t s);
+// dst[rows[i], :] = src[i, :] (scatter) or dst[i, :] = src[rows[i], :] (gather); bf16 rows of d.
+hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows,
+                               int64_t d, int gather, hipStream_t s);
+// Zero the rows named by rows[] of a bf16 [*, d] matrix.
+hipError_t launch_zero_rows(void* dst, const int32_t* rows, int64_t n_rows, int64_t d,
+                            hipStream_t s);
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
+}  // namespace mllm

@@ -1,0 +1,232 @@
+// C ABI for the single operations (mllm_op_*): argument checks, then the same launchers the
+// stage uses.  The attention entry points build their tile list on the host and copy it into the
+// caller's workspace with a blocking copy (they exist for checking kernels, not for pipelining).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/mllm_stage.h"
+#include "kernels.h"
+
+using namespace mllm;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+int count_tiles(const mllm_pack_t& p, int tile) {
+  int n = 0;
+  for (int s = 0; s < p.n_segments; s++) n += (p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s] + tile - 1) / tile;
+  return n;
+}
+
+void build_tiles(const mllm_pack_t& p, int tile, bool kv_major, std::vector<AttnTile>& out) {
+  struct Item { AttnTile t; int64_t work; };
+  std::vector<Item> items;
+  for (int s = 0; s < p.n_segments; s++) {
+    const int start = p.cu_seqlens_host[s], len = p.cu_seqlens_host[s + 1] - start;
+    const int causal = p.mask_kind_host[s] == MLLM_MASK_CAUSAL;
+    for (int t0 = 0; t0 < len; t0 += tile) {
+      int64_t work = !causal ? len : (kv_major ? len - t0 : std::min(len, t0 + tile));
+      items.push_back({{start, len, t0, causal}, work});
+    }
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
+  out.clear();
+  for (auto& it : items) out.push_back(it.t);
+}
+
+}  // namespace
+
+// One thread-local error slot for the whole library; it lives beside mllm_last_error().
+namespace mllm_detail { void set_last_error(const char* msg); }
+
+namespace {
+mllm_status_t op_fail(mllm_status_t st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  mllm_detail::set_last_error(buf);
+  return st;
+}
+
+mllm_status_t check_pack(const mllm_pack_t* p) {
+  if (!p || !p->cu_seqlens_host || (p->n_segments > 0 && !p->mask_kind_host)) return op_fail(MLLM_ERR_NULL, "pack or its arrays are NULL");
+  if (p->n_segments < 0 || p->total_tokens < 0) return op_fail(MLLM_ERR_SHAPE, "negative sizes");
+  if (p->cu_seqlens_host[0] != 0) return op_fail(MLLM_ERR_CU_SEQLENS, "cu_seqlens[0] != 0");
+  int longest = 0;
+  for (int s = 0; s < p->n_segments; s++) {
+    int len = p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+    if (len < 0) return op_fail(MLLM_ERR_CU_SEQLENS, "cu_seqlens decreases at segment %d", s);
+    longest = std::max(longest, len);
+    if (p->mask_kind_host[s] > 1) return op_fail(MLLM_ERR_MASK_KIND, "mask kind %d at segment %d", (int)p->mask_kind_host[s], s);
+  }
+  if (p->cu_seqlens_host[p->n_segments] != p->total_tokens) return op_fail(MLLM_ERR_CU_SEQLENS, "cu_seqlens does not end at total_tokens");
+  if (p->max_seqlen < longest) return op_fail(MLLM_ERR_SHAPE, "max_seqlen below the longest segment");
+  return MLLM_OK;
+}
+
+mllm_status_t check_attn(const mllm_pack_t* pack, int32_t hq, int32_t hkv, int32_t hd, int64_t qs,
+                         int64_t kvs, int64_t os, const void* ws, size_t ws_bytes) {
+  mllm_status_t r = check_pack(pack);
+  if (r != MLLM_OK) return r;
+  if (hd != 64 && hd != 128) return op_fail(MLLM_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (hq <= 0 || hkv <= 0 || hq % hkv) return op_fail(MLLM_ERR_SHAPE, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (qs < (int64_t)hq * hd || kvs < (int64_t)hkv * hd || os < (int64_t)hq * hd || qs % 8 || kvs % 8 || os % 8)
+    return op_fail(MLLM_ERR_SHAPE, "row strides too small or not multiples of 8");
+  if (!ws) return op_fail(MLLM_ERR_NULL, "workspace is NULL");
+  if (ws_bytes < mllm_op_attn_workspace_bytes(pack->n_segments, pack->total_tokens)) return op_fail(MLLM_ERR_WORKSPACE, "attention workspace too small");
+  return MLLM_OK;
+}
+
+#define OP_TRY(expr)                                                                        \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return op_fail(MLLM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a) {
+  std::vector<AttnTile> qt, kt;
+  build_tiles(*pack, ATTN_FWD_Q_TILE, false, qt);
+  build_tiles(*pack, ATTN_BWD_KV_TILE, true, kt);
+  char* w = (char*)ws;
+  const size_t koff = align_up(sizeof(AttnTile) * qt.size());
+  if (!qt.empty()) OP_TRY(hipMemcpy(w, qt.data(), sizeof(AttnTile) * qt.size(), hipMemcpyHostToDevice));
+  if (!kt.empty()) OP_TRY(hipMemcpy(w + koff, kt.data(), sizeof(AttnTile) * kt.size(), hipMemcpyHostToDevice));
+  a.q_tiles = (const AttnTile*)w;
+  a.kv_tiles = (const AttnTile*)(w + koff);
+  a.n_q_tiles = (int)qt.size();
+  a.n_kv_tiles = (int)kt.size();
+  return MLLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+mllm_status_t mllm_op_gemm(const void* a, const void* b, void* c, int64_t m, int64_t n, int64_t k,
+                           int a_layout, int b_layout, int out_fp32, int accumulate,
+                           const void* bias, const void* residual, void* hip_stream) {
+  if (!a || !b || !c) return op_fail(MLLM_ERR_NULL, "a, b or c is NULL");
+  if (m < 0 || n < 0 || k < 0) return op_fail(MLLM_ERR_SHAPE, "negative size");
+  if ((a_layout | b_layout) & ~1) return op_fail(MLLM_ERR_SHAPE, "layouts must be 0 or 1");
+  const int64_t lda = a_layout ? m : k, ldb = b_layout ? k : n;
+  if (lda % 8 || ldb % 8 || n % 8) return op_fail(MLLM_ERR_SHAPE, "contiguous dimensions must be multiples of 8");
+  if (out_fp32 && residual) return op_fail(MLLM_ERR_UNSUPPORTED, "residual needs a bf16 output");
+  if (!out_fp32 && accumulate) return op_fail(MLLM_ERR_UNSUPPORTED, "accumulate needs an fp32 output");
+  GemmArgs g;
+  g.a = a; g.b = b; g.c = c; g.m = m; g.n = n; g.k = k; g.lda = lda; g.ldb = ldb; g.ldc = n;
+  g.a_layout = a_layout; g.b_layout = b_layout; g.out_fp32 = out_fp32; g.accumulate = accumulate;
+  g.bias = bias; g.residual = residual; g.ldres = n;
+  OP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens) {
+  const size_t max_tiles = (size_t)std::max(0, total_tokens) / 128 + (size_t)std::max(0, n_segments) + 1;
+  return 2 * align_up(sizeof(AttnTile) * max_tiles);
+}
+
+mllm_status_t mllm_op_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                               const mllm_pack_t* pack, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t head_dim, int64_t q_stride, int64_t kv_stride,
+                               int64_t o_stride, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  if (!q || !k || !v || !o || !lse) return op_fail(MLLM_ERR_NULL, "a tensor pointer is NULL");
+  mllm_status_t r = check_attn(pack, n_q_heads, n_kv_heads, head_dim, q_stride, kv_stride, o_stride, workspace, workspace_bytes);
+  if (r != MLLM_OK) return r;
+  AttnArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.q_stride = q_stride; a.kv_stride = kv_stride; a.o_stride = o_stride;
+  a.total_tokens = pack->total_tokens; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+  if ((r = upload_tiles(pack, workspace, a)) != MLLM_OK) return r;
+  OP_TRY(launch_attn_fwd(a, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, const void* o,
+                               const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                               float* delta, const mllm_pack_t* pack, int32_t n_q_heads,
+                               int32_t n_kv_heads, int32_t head_dim, int64_t q_stride,
+                               int64_t kv_stride, int64_t o_stride, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta) return op_fail(MLLM_ERR_NULL, "a tensor pointer is NULL");
+  mllm_status_t r = check_attn(pack, n_q_heads, n_kv_heads, head_dim, q_stride, kv_stride, o_stride, workspace, workspace_bytes);
+  if (r != MLLM_OK) return r;
+  AttnArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
+  a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta;
+  a.q_stride = q_stride; a.kv_stride = kv_stride; a.o_stride = o_stride;
+  a.total_tokens = pack->total_tokens; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+  if ((r = upload_tiles(pack, workspace, a)) != MLLM_OK) return r;
+  OP_TRY(launch_attn_bwd(a, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_norm_fwd(int kind, const void* x, const void* gamma, const void* beta,
+                               void* y, float* stats, int64_t t, int64_t d, float eps,
+                               void* hip_stream) {
+  if (!x || !gamma || !y || !stats || (kind == 0 && !beta)) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
+  if (t < 0 || d <= 0 || d % 8 || d > 8192) return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 8192");
+  OP_TRY(launch_norm_fwd(kind, x, gamma, beta, y, stats, t, d, eps, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+size_t mllm_op_norm_bwd_partial_bytes(int64_t t, int64_t d) {
+  return (size_t)norm_bwd_partial_rows(t) * (size_t)d * 4 * 2;
+}
+
+mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
+                               const float* stats, const void* dres, void* dx, float* dgamma,
+                               float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
+                               void* hip_stream) {
+  if (!dy || !x || !gamma || !stats || !dx || !dgamma || !partial || (kind == 0 && !dbeta)) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
+  if (t < 0 || d <= 0 || d % 8 || d > 8192) return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 8192");
+  OP_TRY(launch_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride,
+                           int64_t col0, int32_t n_heads, int32_t head_dim, float rope_base,
+                           int inverse, void* hip_stream) {
+  if (!qk || !pos) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (t < 0 || n_heads < 0 || head_dim <= 0 || head_dim % 16 || row_stride % 8 || col0 % 8 ||
+      col0 + (int64_t)n_heads * head_dim > row_stride)
+    return op_fail(MLLM_ERR_SHAPE, "bad rope geometry");
+  OP_TRY(launch_rope(qk, pos, t, row_stride, col0, n_heads, head_dim, rope_base, inverse, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f, void* hip_stream) {
+  if (!pre || !a) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (act < 0 || act > 2 || t < 0 || f <= 0 || f % 8) return op_fail(MLLM_ERR_SHAPE, "bad activation arguments");
+  OP_TRY(launch_act_fwd(act, pre, a, t, f, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t, int64_t f, void* hip_stream) {
+  if (!da || !pre || !dpre) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (act < 0 || act > 2 || t < 0 || f <= 0 || f % 8) return op_fail(MLLM_ERR_SHAPE, "bad activation arguments");
+  OP_TRY(launch_act_bwd(act, da, pre, dpre, t, f, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+size_t mllm_op_colsum_partial_bytes(int64_t t, int64_t n) { return (size_t)colsum_partial_rows(t) * (size_t)n * 4; }
+
+mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* partial, int64_t t, int64_t n, void* hip_stream) {
+  if (!x || !out || !partial) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (t < 0 || n <= 0 || n % 8) return op_fail(MLLM_ERR_SHAPE, "n must be a positive multiple of 8");
+  OP_TRY(launch_colsum(x, n, out, accumulate, partial, t, n, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+}  // extern "C"

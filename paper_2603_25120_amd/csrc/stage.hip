@@ -1,0 +1,673 @@
+// Host side of the library: stage handle, argument validation, buffer plan, the launch sequence
+// of one stage forward / backward pass, and the C ABI declared in mllm_stage.h.
+//
+// One call runs every layer of the stage over one packed microbatch (Background and Motivation,
+// Fig. 1: the forward and backward boxes of one stage).  Linear operations run over the whole
+// packed token matrix; attention runs per instance from a tile list built here from cu_seqlens
+// (Model Profiler, "Throughput Profiling").
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/mllm_stage.h"
+#include "kernels.h"
+
+using namespace mllm;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+mllm_status_t fail(mllm_status_t st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return st;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(MLLM_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));         \
+  } while (0)
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct ParamInfo {
+  const char* name;
+  int32_t layer;
+  int64_t rows, cols;
+};
+
+int64_t nqkv_of(const mllm_layer_desc_t& L) { return (int64_t)(L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim; }
+
+}  // namespace
+
+namespace mllm_detail {
+void set_last_error(const char* msg) { g_last_error = msg; }
+}  // namespace mllm_detail
+
+struct mllm_stage {
+  std::vector<mllm_layer_desc_t> layers;
+  std::vector<ParamInfo> params;
+  std::vector<int> param_off;  // first parameter index of each layer
+  int n_vit = 0, n_dec = 0, proj = -1;
+  // pinned host staging for the per-call metadata upload
+  void* pinned = nullptr;
+  size_t pinned_bytes = 0;
+  hipEvent_t upload_done = nullptr;
+  bool upload_pending = false;
+};
+
+namespace {
+
+// -------------------------------------------------------------------------------------------
+// validation
+// -------------------------------------------------------------------------------------------
+mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
+  auto m64 = [](int64_t v) { return v > 0 && v % 64 == 0; };
+  if (L.kind == MLLM_LAYER_PROJECTOR) {
+    if (!m64(L.d_model) || !m64(L.d_out)) return fail(MLLM_ERR_DESC, "layer %d: projector widths must be positive multiples of 64", i);
+    if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: projector needs has_bias = 1", i);
+    return MLLM_OK;
+  }
+  if (L.kind != MLLM_LAYER_VIT && L.kind != MLLM_LAYER_DECODER) return fail(MLLM_ERR_DESC, "layer %d: unknown kind %d", i, L.kind);
+  if (L.head_dim != 64 && L.head_dim != 128) return fail(MLLM_ERR_DESC, "layer %d: head_dim must be 64 or 128", i);
+  if (L.n_q_heads <= 0 || L.n_kv_heads <= 0 || L.n_q_heads % L.n_kv_heads != 0)
+    return fail(MLLM_ERR_DESC, "layer %d: n_q_heads must be a positive multiple of n_kv_heads", i);
+  if (L.d_model != L.n_q_heads * L.head_dim) return fail(MLLM_ERR_DESC, "layer %d: d_model != n_q_heads * head_dim", i);
+  if (!m64(L.d_model) || !m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: widths must be positive multiples of 64", i);
+  if (L.d_model > 8192) return fail(MLLM_ERR_DESC, "layer %d: d_model above 8192", i);
+  if (!(L.norm_eps > 0.f)) return fail(MLLM_ERR_DESC, "layer %d: norm_eps must be positive", i);
+  if (L.kind == MLLM_LAYER_VIT) {
+    if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: ViT layer needs has_bias = 1", i);
+    if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: ViT activation must be GELU", i);
+    if (L.n_q_heads != L.n_kv_heads) return fail(MLLM_ERR_DESC, "layer %d: ViT layer needs n_kv_heads == n_q_heads", i);
+  } else {
+    if (L.has_bias != 0) return fail(MLLM_ERR_DESC, "layer %d: decoder layer needs has_bias = 0", i);
+    if (L.act != MLLM_ACT_SWIGLU) return fail(MLLM_ERR_DESC, "layer %d: decoder activation must be SwiGLU", i);
+    if (!(L.rope_base > 1.f)) return fail(MLLM_ERR_DESC, "layer %d: rope_base must exceed 1", i);
+  }
+  return MLLM_OK;
+}
+
+mllm_status_t check_pack(const mllm_pack_t& p, const char* what) {
+  if (p.total_tokens < 0 || p.n_segments < 0) return fail(MLLM_ERR_SHAPE, "%s: negative sizes", what);
+  if (!p.cu_seqlens_host) return fail(MLLM_ERR_NULL, "%s: cu_seqlens_host is NULL", what);
+  if (p.n_segments > 0 && !p.mask_kind_host) return fail(MLLM_ERR_NULL, "%s: mask_kind_host is NULL", what);
+  if (p.cu_seqlens_host[0] != 0) return fail(MLLM_ERR_CU_SEQLENS, "%s: cu_seqlens[0] != 0", what);
+  int32_t longest = 0;
+  for (int s = 0; s < p.n_segments; s++) {
+    int32_t len = p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s];
+    if (len < 0) return fail(MLLM_ERR_CU_SEQLENS, "%s: cu_seqlens decreases at segment %d", what, s);
+    longest = std::max(longest, len);
+    if (p.mask_kind_host[s] > 1) return fail(MLLM_ERR_MASK_KIND, "%s: mask kind %d at segment %d", what, (int)p.mask_kind_host[s], s);
+  }
+  if (p.cu_seqlens_host[p.n_segments] != p.total_tokens)
+    return fail(MLLM_ERR_CU_SEQLENS, "%s: cu_seqlens ends at %d, total_tokens is %d", what, p.cu_seqlens_host[p.n_segments], p.total_tokens);
+  if (p.max_seqlen < longest) return fail(MLLM_ERR_SHAPE, "%s: max_seqlen %d below the longest segment %d", what, p.max_seqlen, longest);
+  return MLLM_OK;
+}
+
+mllm_status_t check_batch(const mllm_stage* st, const mllm_batch_t* b) {
+  if (!st || !b) return fail(MLLM_ERR_NULL, "stage or batch is NULL");
+  mllm_status_t r;
+  const bool need_img = st->n_vit > 0 || st->proj >= 0;
+  const bool need_seq = st->n_dec > 0 || st->proj >= 0;
+  if (need_img && (r = check_pack(b->img, "img")) != MLLM_OK) return r;
+  if (need_seq && (r = check_pack(b->seq, "seq")) != MLLM_OK) return r;
+  if (st->proj >= 0) {
+    if (b->img.total_tokens > 0 && !b->img_to_seq_row_host) return fail(MLLM_ERR_NULL, "img_to_seq_row_host is NULL");
+    int64_t prev = -1;
+    for (int i = 0; i < b->img.total_tokens; i++) {
+      int32_t r0 = b->img_to_seq_row_host[i];
+      if (r0 < 0 || r0 >= b->seq.total_tokens) return fail(MLLM_ERR_INDEX, "img_to_seq_row[%d] = %d out of range", i, r0);
+      if (r0 <= prev) return fail(MLLM_ERR_INDEX, "img_to_seq_row not strictly increasing at %d", i);
+      prev = r0;
+    }
+  }
+  return MLLM_OK;
+}
+
+// -------------------------------------------------------------------------------------------
+// buffer plan.  Every offset is a function of (stage, batch) only, so sizes(), fwd() and bwd()
+// agree by construction.
+// -------------------------------------------------------------------------------------------
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += align_up(bytes);
+    return o;
+  }
+};
+
+struct LayerSaved {  // byte offsets into `saved`
+  size_t x, stats1, n1, qkv, o, lse, x1, stats2, n2, pre, act;
+};
+
+struct Meta {  // byte offsets into the metadata blob at the head of the workspace
+  size_t img_q_tiles = 0, img_kv_tiles = 0, seq_q_tiles = 0, seq_kv_tiles = 0, pos = 0, i2s = 0;
+  int n_img_q = 0, n_img_kv = 0, n_seq_q = 0, n_seq_kv = 0;
+  size_t bytes = 0;
+};
+
+int count_tiles(const mllm_pack_t& p, int tile) {
+  int n = 0;
+  for (int s = 0; s < p.n_segments; s++) {
+    int len = p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s];
+    n += (len + tile - 1) / tile;
+  }
+  return n;
+}
+
+struct Plan {
+  std::vector<LayerSaved> saved;  // per layer
+  size_t saved_bytes = 0;
+  Meta meta;
+  // workspace offsets (after the metadata)
+  size_t w_partial = 0;           // fp32 partial sums of norm / bias gradients
+  size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0;
+  size_t workspace_bytes = 0;
+  int64_t T_img = 0, T_seq = 0;
+};
+
+Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
+  Plan P;
+  const bool need_img = st->n_vit > 0 || st->proj >= 0;
+  const bool need_seq = st->n_dec > 0 || st->proj >= 0;
+  P.T_img = need_img ? b->img.total_tokens : 0;
+  P.T_seq = need_seq ? b->seq.total_tokens : 0;
+  Bump sv;
+  P.saved.resize(st->layers.size());
+  for (size_t i = 0; i < st->layers.size(); i++) {
+    const mllm_layer_desc_t& L = st->layers[i];
+    LayerSaved& S = P.saved[i];
+    memset(&S, 0, sizeof S);
+    if (L.kind == MLLM_LAYER_PROJECTOR) {
+      S.x = sv.take((size_t)P.T_img * L.d_model * 2);   // connector input
+      continue;
+    }
+    const size_t T = L.kind == MLLM_LAYER_VIT ? P.T_img : P.T_seq;
+    const size_t d = L.d_model, f = L.d_ff;
+    S.x = sv.take(T * d * 2);
+    S.stats1 = sv.take(T * 2 * 4);
+    S.n1 = sv.take(T * d * 2);
+    S.qkv = sv.take(T * nqkv_of(L) * 2);
+    S.o = sv.take(T * d * 2);
+    S.lse = sv.take(T * L.n_q_heads * 4);
+    S.x1 = sv.take(T * d * 2);
+    S.stats2 = sv.take(T * 2 * 4);
+    S.n2 = sv.take(T * d * 2);
+    S.pre = sv.take(T * (L.kind == MLLM_LAYER_VIT ? f : 2 * f) * 2);
+    S.act = sv.take(T * f * 2);
+  }
+  P.saved_bytes = std::max<size_t>(sv.off, ALIGN);
+
+  Bump ws;
+  Meta& M = P.meta;
+  if (st->n_vit > 0) {
+    M.n_img_q = count_tiles(b->img, ATTN_FWD_Q_TILE);
+    M.n_img_kv = count_tiles(b->img, ATTN_BWD_KV_TILE);
+    M.img_q_tiles = ws.take(sizeof(AttnTile) * M.n_img_q);
+    M.img_kv_tiles = ws.take(sizeof(AttnTile) * M.n_img_kv);
+  }
+  if (st->n_dec > 0) {
+    M.n_seq_q = count_tiles(b->seq, ATTN_FWD_Q_TILE);
+    M.n_seq_kv = count_tiles(b->seq, ATTN_BWD_KV_TILE);
+    M.seq_q_tiles = ws.take(sizeof(AttnTile) * M.n_seq_q);
+    M.seq_kv_tiles = ws.take(sizeof(AttnTile) * M.n_seq_kv);
+    M.pos = ws.take(sizeof(int32_t) * P.T_seq);
+  }
+  if (st->proj >= 0) M.i2s = ws.take(sizeof(int32_t) * P.T_img);
+  M.bytes = ws.off;
+
+  size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0;
+  for (const mllm_layer_desc_t& L : st->layers) {
+    if (L.kind == MLLM_LAYER_PROJECTOR) {
+      proj = (size_t)P.T_img * L.d_out * 2;
+      part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * L.d_out * 4);
+      g = std::max(g, (size_t)P.T_img * L.d_model * 2);
+      g = std::max(g, (size_t)P.T_seq * L.d_out * 2);
+      continue;
+    }
+    const size_t T = L.kind == MLLM_LAYER_VIT ? P.T_img : P.T_seq;
+    const size_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
+    const size_t widest = std::max<size_t>(std::max(d, 2 * f), nq);
+    part = std::max(part, (size_t)norm_bwd_partial_rows(T) * d * 4 * 2);
+    part = std::max(part, (size_t)colsum_partial_rows(T) * widest * 4);
+    a = std::max(a, T * f * 2);
+    bb = std::max(bb, L.kind == MLLM_LAYER_DECODER ? T * 2 * f * 2 : 0);
+    c = std::max(c, T * d * 2);
+    e = std::max(e, T * nq * 2);
+    delta = std::max(delta, T * L.n_q_heads * 4);
+    g = std::max(g, T * d * 2);
+  }
+  P.w_partial = ws.take(part);
+  P.w_a = ws.take(a);
+  P.w_b = ws.take(bb);
+  P.w_c = ws.take(c);
+  P.w_d = ws.take(c);
+  P.w_e = ws.take(e);
+  P.w_delta = ws.take(delta);
+  P.w_g0 = ws.take(g);
+  P.w_g1 = ws.take(g);
+  P.w_proj = ws.take(proj);
+  P.workspace_bytes = std::max<size_t>(ws.off, ALIGN);
+  return P;
+}
+
+// -------------------------------------------------------------------------------------------
+// metadata: attention tile lists (heaviest first), positions, scatter rows
+// -------------------------------------------------------------------------------------------
+void build_tiles(const mllm_pack_t& p, int tile, bool kv_major, AttnTile* out) {
+  struct Item { AttnTile t; int64_t work; int idx; };
+  std::vector<Item> items;
+  for (int s = 0; s < p.n_segments; s++) {
+    const int start = p.cu_seqlens_host[s], len = p.cu_seqlens_host[s + 1] - start;
+    const int causal = p.mask_kind_host[s] == MLLM_MASK_CAUSAL;
+    for (int t0 = 0; t0 < len; t0 += tile) {
+      int64_t work;
+      if (!causal) work = len;
+      else work = kv_major ? (len - t0) : std::min(len, t0 + tile);
+      items.push_back({{start, len, t0, causal}, work, (int)items.size()});
+    }
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
+  for (size_t i = 0; i < items.size(); i++) out[i] = items[i].t;
+}
+
+mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, void* workspace,
+                          hipStream_t s) {
+  const Meta& M = P.meta;
+  if (M.bytes == 0) return MLLM_OK;
+  if (!st->upload_done) HIP_TRY(hipEventCreateWithFlags(&st->upload_done, hipEventDisableTiming));
+  if (st->upload_pending) {  // the previous call's copy must have left the staging buffer
+    HIP_TRY(hipEventSynchronize(st->upload_done));
+    st->upload_pending = false;
+  }
+  if (st->pinned_bytes < M.bytes) {
+    if (st->pinned) HIP_TRY(hipHostFree(st->pinned));
+    st->pinned = nullptr;
+    st->pinned_bytes = 0;
+    HIP_TRY(hipHostMalloc(&st->pinned, M.bytes * 2, hipHostMallocDefault));
+    st->pinned_bytes = M.bytes * 2;
+  }
+  char* h = (char*)st->pinned;
+  memset(h, 0, M.bytes);
+  if (st->n_vit > 0) {
+    build_tiles(b->img, ATTN_FWD_Q_TILE, false, (AttnTile*)(h + M.img_q_tiles));
+    build_tiles(b->img, ATTN_BWD_KV_TILE, true, (AttnTile*)(h + M.img_kv_tiles));
+  }
+  if (st->n_dec > 0) {
+    build_tiles(b->seq, ATTN_FWD_Q_TILE, false, (AttnTile*)(h + M.seq_q_tiles));
+    build_tiles(b->seq, ATTN_BWD_KV_TILE, true, (AttnTile*)(h + M.seq_kv_tiles));
+    int32_t* pos = (int32_t*)(h + M.pos);
+    for (int sgm = 0; sgm < b->seq.n_segments; sgm++)
+      for (int t = b->seq.cu_seqlens_host[sgm]; t < b->seq.cu_seqlens_host[sgm + 1]; t++)
+        pos[t] = t - b->seq.cu_seqlens_host[sgm];
+  }
+  if (st->proj >= 0 && P.T_img > 0) memcpy(h + M.i2s, b->img_to_seq_row_host, sizeof(int32_t) * P.T_img);
+  HIP_TRY(hipMemcpyAsync(workspace, h, M.bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipEventRecord(st->upload_done, s));
+  st->upload_pending = true;
+  return MLLM_OK;
+}
+
+hipError_t gemm(const void* a, int64_t lda, int a_layout, const void* b, int64_t ldb, int b_layout,
+                void* c, int64_t ldc, int64_t m, int64_t n, int64_t k, int out_fp32, int accumulate,
+                const void* bias, const void* res, int64_t ldres, hipStream_t s) {
+  GemmArgs g;
+  g.a = a; g.b = b; g.c = c; g.m = m; g.n = n; g.k = k; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.a_layout = a_layout; g.b_layout = b_layout; g.out_fp32 = out_fp32; g.accumulate = accumulate;
+  g.bias = bias; g.residual = res; g.ldres = ldres;
+  return launch_gemm(g, s);
+}
+// Y[T,n] = X[T,k].W[k,n] (+bias) (+res)
+hipError_t linear_fwd(const void* x, const void* w, void* y, int64_t T, int64_t k, int64_t n,
+                      const void* bias, const void* res, hipStream_t s) {
+  return gemm(x, k, 0, w, n, 0, y, n, T, n, k, 0, 0, bias, res, n, s);
+}
+// dX[T,k] = dY[T,n].W[k,n]^T
+hipError_t linear_dx(const void* dy, const void* w, void* dx, int64_t T, int64_t k, int64_t n, hipStream_t s) {
+  return gemm(dy, n, 0, w, n, 1, dx, k, T, k, n, 0, 0, nullptr, nullptr, 0, s);
+}
+// dW[k,n] (+)= X[T,k]^T.dY[T,n]
+hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t k, int64_t n, int accumulate, hipStream_t s) {
+  return gemm(x, k, 1, dy, n, 0, dw, n, k, n, T, 1, accumulate, nullptr, nullptr, 0, s);
+}
+
+AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char* ws, const Meta& M, bool img) {
+  AttnArgs a;
+  memset(&a, 0, sizeof a);
+  const int64_t nq = nqkv_of(L);
+  a.q = qkv;
+  a.k = qkv + (int64_t)L.n_q_heads * L.head_dim * 2;
+  a.v = qkv + (int64_t)(L.n_q_heads + L.n_kv_heads) * L.head_dim * 2;
+  a.q_stride = a.kv_stride = nq;
+  a.o_stride = L.d_model;
+  a.total_tokens = (int32_t)T;
+  a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads; a.head_dim = L.head_dim;
+  a.q_tiles = (const AttnTile*)(ws + (img ? M.img_q_tiles : M.seq_q_tiles));
+  a.kv_tiles = (const AttnTile*)(ws + (img ? M.img_kv_tiles : M.seq_kv_tiles));
+  a.n_q_tiles = img ? M.n_img_q : M.n_seq_q;
+  a.n_kv_tiles = img ? M.n_img_kv : M.n_seq_kv;
+  return a;
+}
+
+#define K_TRY(expr)                                                                        \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return fail(MLLM_ERR_HIP, "launch failed (%s): %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+// -------------------------------------------------------------------------------------------
+// one transformer layer, forward.  x -> y; everything backward needs goes to `saved`.
+// -------------------------------------------------------------------------------------------
+mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, const LayerSaved& S,
+                        char* saved, char* ws, const Plan& P, int64_t T, void* y, hipStream_t s) {
+  const bool vit = L.kind == MLLM_LAYER_VIT;
+  const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
+  char* x = saved + S.x;
+  char* n1 = saved + S.n1;
+  char* qkv = saved + S.qkv;
+  char* o = saved + S.o;
+  char* x1 = saved + S.x1;
+  char* n2 = saved + S.n2;
+  char* pre = saved + S.pre;
+  char* act = saved + S.act;
+  // parameter slots
+  const void *g1, *b1n = nullptr, *wqkv, *bqkv = nullptr, *wo, *bo = nullptr, *g2, *b2n = nullptr,
+             *wup, *bup = nullptr, *wdn, *bdn = nullptr;
+  if (vit) { g1 = prm[0]; b1n = prm[1]; wqkv = prm[2]; bqkv = prm[3]; wo = prm[4]; bo = prm[5];
+             g2 = prm[6]; b2n = prm[7]; wup = prm[8]; bup = prm[9]; wdn = prm[10]; bdn = prm[11]; }
+  else { g1 = prm[0]; wqkv = prm[1]; wo = prm[2]; g2 = prm[3]; wup = prm[4]; wdn = prm[5]; }
+
+  K_TRY(launch_norm_fwd(vit ? 0 : 1, x, g1, b1n, n1, (float*)(saved + S.stats1), T, d, L.norm_eps, s));
+  K_TRY(linear_fwd(n1, wqkv, qkv, T, d, nq, bqkv, nullptr, s));
+  if (!vit)
+    K_TRY(launch_rope(qkv, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
+                      L.head_dim, L.rope_base, 0, s));
+  AttnArgs a = attn_args(L, qkv, T, ws, P.meta, vit);
+  a.o = o;
+  a.lse = (float*)(saved + S.lse);
+  K_TRY(launch_attn_fwd(a, s));
+  K_TRY(linear_fwd(o, wo, x1, T, d, d, bo, x, s));
+  K_TRY(launch_norm_fwd(vit ? 0 : 1, x1, g2, b2n, n2, (float*)(saved + S.stats2), T, d, L.norm_eps, s));
+  K_TRY(linear_fwd(n2, wup, pre, T, d, vit ? f : 2 * f, bup, nullptr, s));
+  K_TRY(launch_act_fwd(L.act, pre, act, T, f, s));
+  K_TRY(linear_fwd(act, wdn, y, T, f, d, bdn, x1, s));
+  return MLLM_OK;
+}
+
+// dy -> dx (both bf16 [T,d]); parameter gradients into dprm (fp32).
+mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void* const* dprm,
+                        int accumulate, const LayerSaved& S, const char* saved, char* ws,
+                        const Plan& P, int64_t T, const void* dy, void* dx, hipStream_t s) {
+  const bool vit = L.kind == MLLM_LAYER_VIT;
+  const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
+  const char* x = saved + S.x;
+  const char* n1 = saved + S.n1;
+  char* qkv = const_cast<char*>(saved + S.qkv);
+  const char* o = saved + S.o;
+  const char* x1 = saved + S.x1;
+  const char* n2 = saved + S.n2;
+  const char* pre = saved + S.pre;
+  const char* act = saved + S.act;
+  float* partial = (float*)(ws + P.w_partial);
+  char* wa = ws + P.w_a;      // d act            [T, f]
+  char* wb = ws + P.w_b;      // d (gate|up)      [T, 2f]  (decoder)
+  char* wc = ws + P.w_c;      // d n2 / d o / d n1 [T, d]
+  char* wd = ws + P.w_d;      // d x1             [T, d]
+  char* we = ws + P.w_e;      // d qkv            [T, nq]
+  int ig1, ib1n = -1, iwqkv, ibqkv = -1, iwo, ibo = -1, ig2, ib2n = -1, iwup, ibup = -1, iwdn, ibdn = -1;
+  if (vit) { ig1 = 0; ib1n = 1; iwqkv = 2; ibqkv = 3; iwo = 4; ibo = 5; ig2 = 6; ib2n = 7; iwup = 8; ibup = 9; iwdn = 10; ibdn = 11; }
+  else { ig1 = 0; iwqkv = 1; iwo = 2; ig2 = 3; iwup = 4; iwdn = 5; }
+  const int64_t fup = vit ? f : 2 * f;
+
+  // MLP
+  K_TRY(linear_dw(act, dy, dprm[iwdn], T, f, d, accumulate, s));
+  if (vit) K_TRY(launch_colsum(dy, d, (float*)dprm[ibdn], accumulate, partial, T, d, s));
+  K_TRY(linear_dx(dy, prm[iwdn], wa, T, f, d, s));
+  char* dpre = vit ? wa : wb;
+  K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
+  K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s));
+  if (vit) K_TRY(launch_colsum(dpre, fup, (float*)dprm[ibup], accumulate, partial, T, fup, s));
+  K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));
+  K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x1, prm[ig2], (const float*)(saved + S.stats2), dy, wd,
+                        (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, s));
+  // attention block
+  K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s));
+  if (vit) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
+  K_TRY(linear_dx(wd, prm[iwo], wc, T, d, d, s));
+  AttnArgs a = attn_args(L, qkv, T, ws, P.meta, vit);
+  a.o = const_cast<char*>(o);
+  a.lse = (float*)const_cast<char*>(saved + S.lse);
+  a.d_o = wc;
+  a.dq = we;
+  a.dk = we + (int64_t)L.n_q_heads * L.head_dim * 2;
+  a.dv = we + (int64_t)(L.n_q_heads + L.n_kv_heads) * L.head_dim * 2;
+  a.delta = (float*)(ws + P.w_delta);
+  K_TRY(launch_attn_bwd(a, s));
+  if (!vit)
+    K_TRY(launch_rope(we, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
+                      L.head_dim, L.rope_base, 1, s));
+  K_TRY(linear_dw(n1, we, dprm[iwqkv], T, d, nq, accumulate, s));
+  if (vit) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
+  K_TRY(linear_dx(we, prm[iwqkv], wc, T, d, nq, s));
+  K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x, prm[ig1], (const float*)(saved + S.stats1), wd, dx,
+                        (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, s));
+  return MLLM_OK;
+}
+
+mllm_status_t check_io(const mllm_stage* st, const mllm_batch_t* b, const void* const* params,
+                       const Plan& P, size_t saved_bytes, size_t workspace_bytes, const void* saved,
+                       const void* workspace) {
+  if (!params) return fail(MLLM_ERR_NULL, "params is NULL");
+  for (size_t i = 0; i < st->params.size(); i++)
+    if (!params[i]) return fail(MLLM_ERR_NULL, "params[%zu] (%s) is NULL", i, st->params[i].name);
+  if (!saved || !workspace) return fail(MLLM_ERR_NULL, "saved or workspace is NULL");
+  if (((uintptr_t)saved | (uintptr_t)workspace) % ALIGN) return fail(MLLM_ERR_WORKSPACE, "saved and workspace must be 256-byte aligned");
+  if (saved_bytes < P.saved_bytes) return fail(MLLM_ERR_WORKSPACE, "saved buffer has %zu bytes, %zu needed", saved_bytes, P.saved_bytes);
+  if (workspace_bytes < P.workspace_bytes) return fail(MLLM_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, P.workspace_bytes);
+  (void)b;
+  return MLLM_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* mllm_last_error(void) { return g_last_error.c_str(); }
+
+mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** out) {
+  if (!desc || !out) return fail(MLLM_ERR_NULL, "desc or out is NULL");
+  *out = nullptr;
+  if (desc->n_layers <= 0 || !desc->layers) return fail(MLLM_ERR_DESC, "stage needs at least one layer");
+  mllm_stage* st = new mllm_stage();
+  int phase = 0;  // 0: ViT layers, 1: after projector / decoder layers
+  int64_t width = -1;
+  for (int i = 0; i < desc->n_layers; i++) {
+    const mllm_layer_desc_t& L = desc->layers[i];
+    mllm_status_t r = check_layer(L, i);
+    if (r != MLLM_OK) { delete st; return r; }
+    if (width >= 0 && L.d_model != width) { delete st; return fail(MLLM_ERR_DESC, "layer %d: input width %d does not follow the previous layer's %lld", i, L.d_model, (long long)width); }
+    if (L.kind == MLLM_LAYER_VIT) {
+      if (phase != 0) { delete st; return fail(MLLM_ERR_DESC, "layer %d: ViT layer after projector / decoder", i); }
+      st->n_vit++;
+      width = L.d_model;
+    } else if (L.kind == MLLM_LAYER_PROJECTOR) {
+      if (phase != 0) { delete st; return fail(MLLM_ERR_DESC, "layer %d: projector must come before the decoder layers and only once", i); }
+      st->proj = i;
+      phase = 1;
+      width = L.d_out;
+    } else {
+      if (st->n_vit > 0 && st->proj < 0) { delete st; return fail(MLLM_ERR_DESC, "layer %d: decoder after ViT needs a projector in between", i); }
+      phase = 1;
+      st->n_dec++;
+      width = L.d_model;
+    }
+    st->layers.push_back(L);
+    st->param_off.push_back((int)st->params.size());
+    const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
+    if (L.kind == MLLM_LAYER_VIT) {
+      const ParamInfo ps[] = {{"ln1_g", i, 1, d}, {"ln1_b", i, 1, d}, {"w_qkv", i, d, nq}, {"b_qkv", i, 1, nq},
+                              {"w_o", i, d, d}, {"b_o", i, 1, d}, {"ln2_g", i, 1, d}, {"ln2_b", i, 1, d},
+                              {"w_1", i, d, f}, {"b_1", i, 1, f}, {"w_2", i, f, d}, {"b_2", i, 1, d}};
+      st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
+    } else if (L.kind == MLLM_LAYER_DECODER) {
+      const ParamInfo ps[] = {{"rms1_g", i, 1, d}, {"w_qkv", i, d, nq}, {"w_o", i, d, d},
+                              {"rms2_g", i, 1, d}, {"w_gu", i, d, 2 * f}, {"w_d", i, f, d}};
+      st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
+    } else {
+      const ParamInfo ps[] = {{"w_p", i, d, L.d_out}, {"b_p", i, 1, L.d_out}};
+      st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
+    }
+  }
+  *out = st;
+  return MLLM_OK;
+}
+
+void mllm_stage_destroy(mllm_stage_t* st) {
+  if (!st) return;
+  if (st->upload_pending) (void)hipEventSynchronize(st->upload_done);
+  if (st->upload_done) (void)hipEventDestroy(st->upload_done);
+  if (st->pinned) (void)hipHostFree(st->pinned);
+  delete st;
+}
+
+size_t mllm_stage_param_count(const mllm_stage_t* st) { return st ? st->params.size() : 0; }
+
+mllm_status_t mllm_stage_param_info(const mllm_stage_t* st, size_t i, const char** name, int32_t* layer,
+                                    int64_t* rows, int64_t* cols) {
+  if (!st) return fail(MLLM_ERR_NULL, "stage is NULL");
+  if (i >= st->params.size()) return fail(MLLM_ERR_SHAPE, "parameter index %zu out of range", i);
+  if (name) *name = st->params[i].name;
+  if (layer) *layer = st->params[i].layer;
+  if (rows) *rows = st->params[i].rows;
+  if (cols) *cols = st->params[i].cols;
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_stage_sizes(const mllm_stage_t* st, const mllm_batch_t* b, size_t* saved_bytes,
+                               size_t* workspace_bytes) {
+  mllm_status_t r = check_batch(st, b);
+  if (r != MLLM_OK) return r;
+  Plan P = make_plan(st, b);
+  if (saved_bytes) *saved_bytes = P.saved_bytes;
+  if (workspace_bytes) *workspace_bytes = P.workspace_bytes;
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void* const* params,
+                             const void* x_img, const void* x_seq, void* y, void* saved_v,
+                             size_t saved_bytes, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  mllm_status_t r = check_batch(st, b);
+  if (r != MLLM_OK) return r;
+  Plan P = make_plan(st, b);
+  if ((r = check_io(st, b, params, P, saved_bytes, workspace_bytes, saved_v, workspace)) != MLLM_OK) return r;
+  const bool need_img = st->n_vit > 0 || st->proj >= 0;
+  const bool need_seq = st->n_dec > 0 || st->proj >= 0;
+  if (need_img && P.T_img > 0 && !x_img) return fail(MLLM_ERR_NULL, "x_img is NULL");
+  if (need_seq && P.T_seq > 0 && !x_seq) return fail(MLLM_ERR_NULL, "x_seq is NULL");
+  if (!y) return fail(MLLM_ERR_NULL, "y is NULL");
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* saved = (char*)saved_v;
+  char* ws = (char*)workspace;
+  if ((r = upload_meta(st, b, P, workspace, s)) != MLLM_OK) return r;
+
+  const int n = (int)st->layers.size();
+  for (int i = 0; i < n; i++) {
+    const mllm_layer_desc_t& L = st->layers[i];
+    const bool last = i == n - 1;
+    const void* const* prm = params + st->param_off[i];
+    if (L.kind == MLLM_LAYER_PROJECTOR) {
+      // input = x_img if this is the first layer (copied so that backward owns it), else the
+      // previous ViT layer already wrote its output into S.x
+      if (i == 0) K_TRY(launch_copy(x_img, saved + P.saved[i].x, (size_t)P.T_img * L.d_model * 2, s));
+      void* dst = last ? y : (void*)(saved + P.saved[i + 1].x);
+      K_TRY(launch_copy(x_seq, dst, (size_t)P.T_seq * L.d_out * 2, s));
+      K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], ws + P.w_proj, P.T_img, L.d_model, L.d_out, prm[1], nullptr, s));
+      K_TRY(launch_scatter_rows(ws + P.w_proj, dst, (const int32_t*)(ws + P.meta.i2s), P.T_img, L.d_out, 0, s));
+      continue;
+    }
+    const bool vit = L.kind == MLLM_LAYER_VIT;
+    const int64_t T = vit ? P.T_img : P.T_seq;
+    if (i == 0) K_TRY(launch_copy(vit ? x_img : x_seq, saved + P.saved[i].x, (size_t)T * L.d_model * 2, s));
+    void* out = last ? y : (void*)(saved + P.saved[i + 1].x);
+    if ((r = layer_fwd(L, prm, P.saved[i], saved, ws, P, T, out, s)) != MLLM_OK) return r;
+  }
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void* const* params,
+                             const void* dy, const void* saved_v, size_t saved_bytes, void* dx_img,
+                             void* dx_seq, void* const* dparams, int accumulate, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  mllm_status_t r = check_batch(st, b);
+  if (r != MLLM_OK) return r;
+  Plan P = make_plan(st, b);
+  if ((r = check_io(st, b, params, P, saved_bytes, workspace_bytes, saved_v, workspace)) != MLLM_OK) return r;
+  if (!dy) return fail(MLLM_ERR_NULL, "dy is NULL");
+  if (!dparams) return fail(MLLM_ERR_NULL, "dparams is NULL");
+  for (size_t i = 0; i < st->params.size(); i++)
+    if (!dparams[i]) return fail(MLLM_ERR_NULL, "dparams[%zu] (%s) is NULL", i, st->params[i].name);
+  hipStream_t s = (hipStream_t)hip_stream;
+  const char* saved = (const char*)saved_v;
+  char* ws = (char*)workspace;
+  if ((r = upload_meta(st, b, P, workspace, s)) != MLLM_OK) return r;
+
+  const int n = (int)st->layers.size();
+  const void* cur = dy;  // gradient w.r.t. the output of layer i
+  char* pp[2] = {ws + P.w_g0, ws + P.w_g1};
+  int flip = 0;
+  for (int i = n - 1; i >= 0; i--) {
+    const mllm_layer_desc_t& L = st->layers[i];
+    const void* const* prm = params + st->param_off[i];
+    void* const* dprm = dparams + st->param_off[i];
+    if (L.kind == MLLM_LAYER_PROJECTOR) {
+      const int32_t* i2s = (const int32_t*)(ws + P.meta.i2s);
+      char* dproj = ws + P.w_proj;
+      K_TRY(launch_scatter_rows(cur, dproj, i2s, P.T_img, L.d_out, 1, s));
+      if (dx_seq) {
+        K_TRY(launch_copy(cur, dx_seq, (size_t)P.T_seq * L.d_out * 2, s));
+        K_TRY(launch_zero_rows(dx_seq, i2s, P.T_img, L.d_out, s));
+      }
+      K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s));
+      K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, (float*)(ws + P.w_partial), P.T_img, L.d_out, s));
+      void* out = (i == 0 && dx_img) ? dx_img : (void*)pp[flip];
+      K_TRY(linear_dx(dproj, prm[0], out, P.T_img, L.d_model, L.d_out, s));
+      cur = out;
+      flip ^= 1;
+      continue;
+    }
+    const bool vit = L.kind == MLLM_LAYER_VIT;
+    const int64_t T = vit ? P.T_img : P.T_seq;
+    void* out = pp[flip];
+    if (i == 0) {
+      void* want = vit ? dx_img : dx_seq;
+      if (want) out = want;
+    }
+    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, s)) != MLLM_OK) return r;
+    cur = out;
+    flip ^= 1;
+  }
+  return MLLM_OK;
+}
+
+}  // extern "C"

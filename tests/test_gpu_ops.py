@@ -1,0 +1,224 @@
+"""Per-kernel parity: each HIP operation, called through the C ABI, against the fp64 oracle on the
+same seeded bf16-grid inputs.  Sizes span several tiles and a ragged tail.
+
+Tolerances (normalised max error, max|gpu - oracle| / max|oracle|):
+  * a single operation whose output is bf16 carries one rounding of the result (2^-9 relative)
+    plus fp32 accumulation error: 1e-2 is used (outputs far below the row maximum dominate);
+  * fp32 outputs of bf16 products accumulated in fp32: 2e-3;
+  * attention: bf16 probabilities inside the kernel, so the stage tolerances apply: 2e-2 on
+    outputs, 3e-2 on gradients.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import stage_oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from tests.gpu_util import dev_bf16, empty_bf16, host_f64, nmax_err, scratch  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_25120_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("m,n,k", [(263, 576, 192), (128, 128, 64), (300, 256, 1024), (1, 64, 64), (517, 192, 263 * 8)])
+@pytest.mark.parametrize("a_layout,b_layout", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_gemm_layouts(B, m, n, k, a_layout, b_layout):
+    if (a_layout and m % 8) or (b_layout and k % 8) or (not a_layout and k % 8):
+        pytest.skip("contiguous dimension not a multiple of 8")
+    a = W.draw_tensor(1, m, k)
+    b = W.draw_tensor(2, k, n) * np.float32(0.125)
+    a_st = np.ascontiguousarray(a.T) if a_layout else a
+    b_st = np.ascontiguousarray(b.T) if b_layout else b
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    c = empty_bf16(m, n)
+    B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout)
+    assert nmax_err(host_f64(c), ref) < 1e-2
+    c32 = torch.empty(m, n, dtype=torch.float32, device="cuda")
+    B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c32, m, n, k, a_layout, b_layout, out_fp32=1)
+    assert nmax_err(host_f64(c32), ref) < 2e-3
+
+
+def test_gemm_epilogues(B):
+    m, n, k = 333, 192, 256
+    a, b = W.draw_tensor(3, m, k), W.bf16_round(W.draw_tensor(4, k, n) * np.float32(0.1))
+    bias, res = W.draw_tensor(5, 1, n), W.draw_tensor(6, m, n)
+    ref = a.astype(np.float64) @ b + bias + res
+    c = empty_bf16(m, n)
+    B.mllm_op_gemm(dev_bf16(a), dev_bf16(b), c, m, n, k, bias=dev_bf16(bias), residual=dev_bf16(res))
+    assert nmax_err(host_f64(c), ref) < 1e-2
+    # fp32 accumulate: C += A.B twice on top of an initial value
+    init = np.random.default_rng(7).standard_normal((m, n)).astype(np.float32)
+    c32 = torch.from_numpy(init.copy()).cuda()
+    for _ in range(2):
+        B.mllm_op_gemm(dev_bf16(a), dev_bf16(b), c32, m, n, k, out_fp32=1, accumulate=1)
+    assert nmax_err(host_f64(c32), init + 2 * (a.astype(np.float64) @ b)) < 2e-3
+
+
+def test_gemm_weight_gradient_shape(B):
+    # dW[k, n] = X[T, k]^T . dY[T, n], contraction over a ragged token count
+    T, k, n = 263, 192, 576
+    x, dy = W.draw_tensor(8, T, k), W.draw_tensor(9, T, n)
+    dw = torch.empty(k, n, dtype=torch.float32, device="cuda")
+    B.mllm_op_gemm(dev_bf16(x), dev_bf16(dy), dw, k, n, T, a_layout=1, b_layout=0, out_fp32=1)
+    assert nmax_err(host_f64(dw), x.astype(np.float64).T @ dy) < 2e-3
+
+
+def test_gemm_zero_contraction(B):
+    c32 = torch.full((64, 64), 3.0, dtype=torch.float32, device="cuda")
+    dummy = empty_bf16(64, 8)
+    B.mllm_op_gemm(dummy, dummy, c32, 64, 64, 0, a_layout=1, b_layout=0, out_fp32=1)
+    assert float(c32.abs().max()) == 0.0
+
+
+ATTN_CASES = [
+    # (head_dim, n_q, n_kv, lengths, kinds)
+    (64, 3, 3, [64, 64], [0, 0]),
+    (64, 4, 4, [96, 0, 1, 130, 257], [1, 1, 1, 1, 1]),
+    (128, 4, 2, [300, 5, 127, 128, 129], [1, 0, 1, 0, 1]),
+    (128, 8, 2, [700], [1]),
+    (64, 2, 2, [576, 576], [0, 0]),
+]
+
+
+@pytest.mark.parametrize("hd,hq,hkv,lengths,kinds", ATTN_CASES)
+def test_attention_fwd_bwd(B, hd, hq, hkv, lengths, kinds):
+    pack = W.make_pack(lengths, 0)
+    pack.mask_kind[:] = np.asarray(kinds, dtype=np.uint8)
+    T = pack.total_tokens
+    nq = (hq + 2 * hkv) * hd
+    qkv = W.draw_tensor(11, T, nq)
+    do = W.draw_tensor(12, T, hq * hd)
+    q = qkv[:, :hq * hd].reshape(T, hq, hd).astype(np.float64)
+    k = qkv[:, hq * hd:(hq + hkv) * hd].reshape(T, hkv, hd).astype(np.float64)
+    v = qkv[:, (hq + hkv) * hd:].reshape(T, hkv, hd).astype(np.float64)
+    o_ref, lse_ref = O.attention_fwd(q, k, v, pack.cu_seqlens, pack.mask_kind, return_lse=True)
+    dq_ref, dk_ref, dv_ref = O.attention_bwd(do.reshape(T, hq, hd).astype(np.float64), q, k, v,
+                                             pack.cu_seqlens, pack.mask_kind)
+    d_qkv = dev_bf16(qkv)
+    o = torch.zeros(T, hq * hd, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    esz = 2
+    qp, kp, vp = d_qkv.data_ptr(), d_qkv.data_ptr() + hq * hd * esz, d_qkv.data_ptr() + (hq + hkv) * hd * esz
+    B.mllm_op_attn_fwd(qp, kp, vp, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    assert nmax_err(host_f64(o), o_ref.reshape(T, -1)) < 2e-2
+    assert np.max(np.abs(host_f64(lse) - lse_ref)) < 2e-2
+    dqkv = torch.zeros(T, nq, dtype=torch.bfloat16, device="cuda")
+    delta = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    gp = dqkv.data_ptr()
+    B.mllm_op_attn_bwd(qp, kp, vp, o, lse, dev_bf16(do), gp, gp + hq * hd * esz, gp + (hq + hkv) * hd * esz,
+                       delta, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    g = host_f64(dqkv)
+    assert nmax_err(g[:, :hq * hd], dq_ref.reshape(T, -1)) < 3e-2
+    assert nmax_err(g[:, hq * hd:(hq + hkv) * hd], dk_ref.reshape(T, -1)) < 3e-2
+    assert nmax_err(g[:, (hq + hkv) * hd:], dv_ref.reshape(T, -1)) < 3e-2
+
+
+def test_attention_exact_cases(B):
+    """Length-1 segments and the first token of a causal segment return v bit for bit."""
+    hd, hq = 64, 2
+    pack = W.make_pack([1, 40, 1], 1)
+    T = pack.total_tokens
+    qkv = W.draw_tensor(13, T, 3 * hq * hd)
+    d = dev_bf16(qkv)
+    o = empty_bf16(T, hq * hd)
+    lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    ws = scratch(B.mllm_op_attn_workspace_bytes(3, T))
+    B.mllm_op_attn_fwd(d.data_ptr(), d.data_ptr() + hq * hd * 2, d.data_ptr() + 2 * hq * hd * 2, o, lse, pack,
+                       hq, hq, hd, 3 * hq * hd, 3 * hq * hd, hq * hd, ws)
+    got = host_f64(o)
+    v = qkv[:, 2 * hq * hd:].astype(np.float64)
+    for t in (0, 1, T - 1):
+        assert np.array_equal(got[t], v[t])
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("t,d", [(263, 192), (130, 1024), (37, 4096), (5, 256)])
+def test_norm_fwd_bwd(B, kind, t, d):
+    x = W.bf16_round(W.draw_tensor(21, t, d) * np.float32(1.5) + np.float32(0.25))
+    g = W.bf16_round(1 + 0.02 * np.random.default_rng(22).standard_normal((1, d)).astype(np.float32))
+    b = W.bf16_round(0.02 * np.random.default_rng(23).standard_normal((1, d)).astype(np.float32))
+    dy, dres = W.draw_tensor(24, t, d), W.draw_tensor(25, t, d)
+    eps = 1e-5
+    if kind == 0:
+        y_ref, cache = O.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), eps)
+        dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy.astype(np.float64), cache, g.astype(np.float64))
+    else:
+        y_ref, cache = O.rmsnorm_fwd(x.astype(np.float64), g.astype(np.float64), eps)
+        dx_ref, dg_ref = O.rmsnorm_bwd(dy.astype(np.float64), cache, g.astype(np.float64))
+    dx_ref = dx_ref + dres
+    dx_, dg_, db_ = dev_bf16(x), dev_bf16(g), dev_bf16(b)
+    y = empty_bf16(t, d)
+    stats = torch.zeros(2, t, dtype=torch.float32, device="cuda")
+    B.mllm_op_norm_fwd(kind, dx_, dg_, db_, y, stats, t, d, eps)
+    assert nmax_err(host_f64(y), y_ref) < 1e-2
+    dx = empty_bf16(t, d)
+    dgam = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    dbet = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    part = scratch(B.mllm_op_norm_bwd_partial_bytes(t, d))
+    B.mllm_op_norm_bwd(kind, dev_bf16(dy), dx_, dg_, stats, dev_bf16(dres), dx, dgam, dbet, 1, part, t, d)
+    assert nmax_err(host_f64(dx), dx_ref) < 1e-2
+    assert nmax_err(host_f64(dgam), dg_ref[0] + 1.0) < 2e-3
+    if kind == 0:
+        assert nmax_err(host_f64(dbet), db_ref[0] + 1.0) < 2e-3
+
+
+@pytest.mark.parametrize("hd,base", [(64, 10000.0), (128, 500000.0)])
+def test_rope(B, hd, base):
+    lengths = [70, 1, 129]
+    T, heads = sum(lengths), 5
+    stride = heads * hd + 64
+    z = W.draw_tensor(31, T, stride)
+    pos = O.segment_positions(W.make_pack(lengths, 1).cu_seqlens) + 13000   # large angles too
+    cos, sin = O.rope_tables(pos, hd, base)
+    ref = O.rope_apply(z[:, :heads * hd].reshape(T, heads, hd).astype(np.float64), cos, sin).reshape(T, -1)
+    dz = dev_bf16(z)
+    dpos = torch.from_numpy(pos.astype(np.int32)).cuda()
+    B.mllm_op_rope(dz, dpos, T, stride, 0, heads, hd, base, 0)
+    got = host_f64(dz)
+    assert nmax_err(got[:, :heads * hd], ref) < 1e-2
+    assert np.array_equal(got[:, heads * hd:], z[:, heads * hd:].astype(np.float64))   # untouched columns
+    B.mllm_op_rope(dz, dpos, T, stride, 0, heads, hd, base, 1)                          # inverse brings it back
+    assert nmax_err(host_f64(dz)[:, :heads * hd], z[:, :heads * hd].astype(np.float64)) < 2e-2
+
+
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_activations(B, act):
+    t, f = 77, 768
+    width = 2 * f if act == 2 else f
+    pre = W.draw_tensor(41, t, width) * np.float32(2.0)
+    da = W.draw_tensor(42, t, f)
+    p64 = pre.astype(np.float64)
+    if act == 2:
+        a_ref = O.swiglu_fwd(p64[:, :f], p64[:, f:])
+        dgate, dup = O.swiglu_bwd(da.astype(np.float64), p64[:, :f], p64[:, f:])
+        d_ref = np.concatenate([dgate, dup], axis=1)
+    elif act == 1:
+        a_ref, d_ref = O.gelu_tanh(p64), da * O.gelu_tanh_grad(p64)
+    else:
+        a_ref, d_ref = O.gelu_erf(p64), da * O.gelu_erf_grad(p64)
+    a, dpre = empty_bf16(t, f), empty_bf16(t, width)
+    B.mllm_op_act_fwd(act, dev_bf16(pre), a, t, f)
+    B.mllm_op_act_bwd(act, dev_bf16(da), dev_bf16(pre), dpre, t, f)
+    assert nmax_err(host_f64(a), a_ref) < 1e-2
+    assert nmax_err(host_f64(dpre), d_ref) < 1e-2
+
+
+@pytest.mark.parametrize("t,n", [(263, 576), (1, 64), (2000, 192), (0, 64)])
+def test_colsum(B, t, n):
+    x = W.draw_tensor(51, max(t, 1), n)[:t]
+    out = torch.full((n,), 2.0, dtype=torch.float32, device="cuda")
+    part = scratch(B.mllm_op_colsum_partial_bytes(t, n))
+    xd = dev_bf16(x) if t else empty_bf16(1, n)
+    B.mllm_op_colsum(xd, out, 1, part, t, n)
+    ref = x.astype(np.float64).sum(axis=0) + 2.0
+    assert np.max(np.abs(host_f64(out) - ref)) < 1e-3 * max(1.0, math.sqrt(t))

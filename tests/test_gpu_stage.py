@@ -1,0 +1,205 @@
+"""Whole-stage parity: mllm_stage_fwd / mllm_stage_bwd through the C ABI against the fp64 oracle on
+the same seeded inputs.  Tolerances are the stated ones: normalised max error <= 2e-2 on outputs and
+<= 3e-2 on every gradient; packed-sequence indexing is exact (packed == per-sample bit for bit on
+the GPU, causality and segment isolation bit for bit)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import stage_oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from tests.gpu_util import dev_bf16, empty_bf16, host_f64, nmax_err, scratch  # noqa: E402
+
+TOL_OUT, TOL_GRAD = 2e-2, 3e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_25120_amd import binding
+    binding.lib()
+    return binding
+
+
+class GpuStage:
+    """Allocate buffers with PyTorch, run the library's forward and backward."""
+
+    def __init__(self, B, layers):
+        self.B, self.layers = B, layers
+        self.h = B.mllm_stage_create(layers)
+        self.infos = [B.mllm_stage_param_info(self.h, i) for i in range(B.mllm_stage_param_count(self.h))]
+
+    def close(self):
+        self.B.mllm_stage_destroy(self.h)
+
+    def run(self, wl, accumulate=0, dparams=None, want_dx=True):
+        B = self.B
+        params = [dev_bf16(p) for p in wl.params]
+        x_img = dev_bf16(wl.x_img) if wl.x_img is not None else None
+        x_seq = dev_bf16(wl.x_seq) if wl.x_seq is not None else None
+        dy = dev_bf16(wl.dy)
+        sb, wb = B.mllm_stage_sizes(self.h, wl.batch)
+        saved, ws = scratch(sb), scratch(wb)
+        y = torch.zeros(wl.dy.shape, dtype=torch.bfloat16, device="cuda")
+        B.mllm_stage_fwd(self.h, wl.batch, params, x_img, x_seq, y, saved, ws)
+        if dparams is None:
+            dparams = [torch.full((r, c), float("nan") if not accumulate else 0.0, dtype=torch.float32, device="cuda")
+                       for _, _, r, c in self.infos]
+        dx_img = torch.zeros_like(x_img) if (x_img is not None and want_dx) else None
+        dx_seq = torch.zeros_like(x_seq) if (x_seq is not None and want_dx) else None
+        B.mllm_stage_bwd(self.h, wl.batch, params, dy, saved, dx_img, dx_seq, dparams, accumulate, ws)
+        torch.cuda.synchronize()
+        return y, dx_img, dx_seq, dparams
+
+
+def oracle_run(wl):
+    y, caches = O.stage_fwd(wl.layers, wl.params, wl.batch, wl.x_img, wl.x_seq)
+    dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, wl.dy.astype(np.float64))
+    return y, dx_img, dx_seq, dparams
+
+
+def compare(stage, wl, got, ref):
+    y, dx_img, dx_seq, dparams = got
+    y_r, dxi_r, dxs_r, dp_r = ref
+    errs = {"y": nmax_err(host_f64(y), y_r)}
+    assert errs["y"] <= TOL_OUT, errs
+    if dxi_r is not None:
+        errs["dx_img"] = nmax_err(host_f64(dx_img), dxi_r)
+    if dxs_r is not None:
+        errs["dx_seq"] = nmax_err(host_f64(dx_seq), dxs_r)
+    for (name, layer, _, _), g, r in zip(stage.infos, dparams, dp_r):
+        errs["L%d.%s" % (layer, name)] = nmax_err(host_f64(g), r)
+    bad = {k: v for k, v in errs.items() if k != "y" and not v <= TOL_GRAD}
+    assert not bad, bad
+    return errs
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_tiny_stage_matches_oracle(B, seed):
+    wl = W.workload_tiny(seed)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+def test_tiny_stage_deterministic_and_accumulates(B):
+    wl = W.workload_tiny(4)
+    st = GpuStage(B, wl.layers)
+    try:
+        a = st.run(wl)
+        b = st.run(wl)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+        for ga, gb in zip(a[3], b[3]):
+            assert torch.equal(ga, gb)
+        # accumulate: two passes into the same fp32 buffers give twice the gradient
+        acc = [torch.zeros_like(g) for g in a[3]]
+        st.run(wl, accumulate=1, dparams=acc)
+        st.run(wl, accumulate=1, dparams=acc)
+        for g2, g1 in zip(acc, a[3]):
+            assert nmax_err(host_f64(g2), 2 * host_f64(g1)) < 1e-5
+    finally:
+        st.close()
+
+
+def test_packed_equals_per_sample_on_gpu(B):
+    """Rows of a sample do not depend on what else is packed with it: bitwise on the GPU."""
+    wl = W.workload_tiny(5)
+    st = GpuStage(B, wl.layers)
+    try:
+        y, dx_img, dx_seq, _ = st.run(wl)
+        cu = wl.batch.seq.cu_seqlens
+        for s, (k, t) in enumerate(wl.batch.samples):
+            one = W.Workload("one", wl.layers, W.batch_from_samples([(k, t)], img_tokens=64), wl.params,
+                             wl.x_img[64 * s:64 * (s + 1)], wl.x_seq[cu[s]:cu[s + 1]], wl.dy[cu[s]:cu[s + 1]])
+            y1, dxi1, dxs1, _ = st.run(one)
+            assert torch.equal(y1, y[cu[s]:cu[s + 1]])
+            assert torch.equal(dxi1, dx_img[64 * s:64 * (s + 1)])
+            assert torch.equal(dxs1, dx_seq[cu[s]:cu[s + 1]])
+    finally:
+        st.close()
+
+
+def test_causality_and_isolation_on_gpu(B):
+    wl = W.workload_tiny(6)
+    st = GpuStage(B, wl.layers)
+    try:
+        y, _, _, _ = st.run(wl)
+        cu = wl.batch.seq.cu_seqlens
+        t = int(cu[1]) - 1
+        xs = wl.x_seq.copy()
+        xs[t] = W.bf16_round(xs[t] + np.linspace(-1, 1, xs.shape[1], dtype=np.float32))
+        wl2 = W.Workload("p", wl.layers, wl.batch, wl.params, wl.x_img, xs, wl.dy)
+        y2, _, _, _ = st.run(wl2)
+        assert torch.equal(y2[:t], y[:t]) and torch.equal(y2[cu[1]:], y[cu[1]:])
+        assert not torch.equal(y2[t], y[t])
+    finally:
+        st.close()
+
+
+def _layer_case(B, layers, batch, seed):
+    wl = W.make_workload("case", layers, batch, seed)
+    st = GpuStage(B, layers)
+    try:
+        return compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+def test_vit_layer_ragged_images(B):
+    # ViT-L-shaped layer at reduced token count: 576-token images plus odd-sized segments
+    batch = W.Batch(W.make_pack([576, 576, 100, 1, 0, 333], W.MASK_BIDIR), None, None, [])
+    _layer_case(B, [W.vit_l_layer()], batch, 20)
+
+
+def test_decoder_layer_gqa_long_tail(B):
+    # 8B-GQA head geometry (4 query heads per kv head, head_dim 128) at reduced widths
+    layer = W.decoder_layer(1024, 8, 2, 128, 1792, 500000.0)
+    batch = W.Batch(None, W.make_pack([1200, 1, 77, 0, 640, 129], W.MASK_CAUSAL), None, [])
+    _layer_case(B, [layer], batch, 21)
+
+
+def test_decoder_layer_mha(B):
+    layer = W.decoder_layer(512, 4, 4, 128, 1408, 10000.0)
+    batch = W.batch_from_samples(W.draw_samples_mix7b(22, budget=1500), with_images=False)
+    _layer_case(B, [layer], batch, 22)
+
+
+def test_multi_layer_stage(B):
+    # 2 ViT layers + projector + 2 decoder layers at small widths, mixed samples incl. a text-only one
+    layers = [W.vit_layer(256, 4, 64, 512), W.vit_layer(256, 4, 64, 512), W.projector_layer(256, 384),
+              W.decoder_layer(384, 6, 2, 64, 640, 500000.0), W.decoder_layer(384, 6, 2, 64, 640, 500000.0)]
+    batch = W.batch_from_samples([(2, 37), (0, 150), (1, 1)], img_tokens=96)
+    _layer_case(B, layers, batch, 23)
+
+
+def test_stage_without_dx_and_vit_only(B):
+    wl = W.make_workload("v", [W.vit_layer(192, 3, 64, 768)], W.Batch(W.make_pack([64, 30], 0), None, None, []), 24)
+    st = GpuStage(B, wl.layers)
+    try:
+        got = st.run(wl, want_dx=False)
+        ref = oracle_run(wl)
+        assert nmax_err(host_f64(got[0]), ref[0]) <= TOL_OUT
+        for g, r in zip(got[3], ref[3]):
+            assert nmax_err(host_f64(g), r) <= TOL_GRAD
+    finally:
+        st.close()
+
+
+def test_error_statuses_touch_nothing(B):
+    wl = W.workload_tiny(7)
+    st = GpuStage(B, wl.layers)
+    try:
+        sb, wb = B.mllm_stage_sizes(st.h, wl.batch)
+        params = [dev_bf16(p) for p in wl.params]
+        y = torch.full(wl.dy.shape, 7.0, dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(B.MllmError) as e:
+            B.mllm_stage_fwd(st.h, wl.batch, params, dev_bf16(wl.x_img), dev_bf16(wl.x_seq), y, scratch(sb), scratch(wb // 2))
+        assert e.value.status == 7
+        torch.cuda.synchronize()
+        assert float((y.float() - 7.0).abs().max()) == 0.0
+    finally:
+        st.close()
