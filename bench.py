@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark: packed tokens/s of one pipeline stage forward+backward (bf16) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one mllm_stage_fwd + mllm_stage_bwd over one synthetic packed microbatch whose
+inputs, parameters and gradient buffers already live in HBM.  The default workload is the full
+stage slice (24 ViT-L layers + connector + 8 8B-GQA decoder layers) on a 32768-token microbatch
+drawn with the long-tailed length mix; other named workloads time one layer.
+
+Prints ONE JSON line (see the keys below): throughput, the model-FLOP fraction of the bf16 MFMA
+peak, a `roofline` object for the dominant kernel (per-launch durations from HIP events recorded
+inside the timed region on the launch stream), a `cpu_baseline` object (the fp64 oracle timed on
+the host cores on a bounded sample of the same workload) and a per-class time breakdown.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+MFMA_BF16_PEAK = 2.5e15   # dense, FLOP/s
+HBM_PEAK = 8.0e12         # B/s
+
+
+# ---------------------------------------------------------------------------------------------
+# model FLOPs: 2mnk per GEMM, backward = 2x forward, causal attention at half the square,
+# no credit for recomputation
+# ---------------------------------------------------------------------------------------------
+def visible_pairs(pack) -> float:
+    lens = np.diff(pack.cu_seqlens).astype(np.float64)
+    w = np.where(pack.mask_kind == W.MASK_CAUSAL, 0.5, 1.0)
+    return float(np.sum(w * lens * lens))
+
+
+def stage_fwd_flops(layers, batch):
+    lin = attn = 0.0
+    for L in layers:
+        if L.kind == W.LAYER_PROJECTOR:
+            lin += 2.0 * batch.img.total_tokens * L.d_model * L.d_out
+            continue
+        pack = batch.img if L.kind == W.LAYER_VIT else batch.seq
+        T = pack.total_tokens
+        nqkv = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim
+        fup = L.d_ff if L.kind == W.LAYER_VIT else 2 * L.d_ff
+        lin += 2.0 * T * L.d_model * (nqkv + L.d_model + fup) + 2.0 * T * L.d_ff * L.d_model
+        attn += 4.0 * visible_pairs(pack) * L.n_q_heads * L.head_dim
+    return lin, attn
+
+
+def build_workload(name: str):
+    if name == "full_stage_32k":
+        wl = W.workload_full_stage(414, 32768, "8b", with_data=False)
+        desc = "24 ViT-L layers + connector 1024->4096 + 8 8B-GQA decoder layers, 32768-token microbatch, long-tailed mix, seed 414"
+    elif name == "full_stage_4k":
+        wl = W.workload_full_stage(402, 4096, "8b", with_data=False)
+        desc = "24 ViT-L + connector + 8 8B-GQA decoder layers, 4096-token microbatch, seed 402"
+    elif name == "dec8b":
+        wl = W.workload_dec8b(300, with_data=False)
+        desc = "one 8B-GQA decoder layer, 32768-token microbatch, long-tailed mix, seed 300"
+    elif name == "dec7b":
+        wl = W.workload_dec7b(200, with_data=False)
+        desc = "one 7B decoder layer, 8192-token microbatch, seed 200"
+    elif name == "vit_l":
+        wl = W.workload_vit_l(100, with_data=False)
+        desc = "one ViT-L/14-336 layer, 16 samples x 1..4 images of 576 tokens, seed 100"
+    else:
+        raise SystemExit("unknown workload %r" % name)
+    return wl, desc
+
+
+def run_gpu(args, wl):
+    import torch
+    from paper_2603_25120_amd import binding as B
+
+    B.lib()  # raises if the HIP library is missing: there is no fallback
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    h = B.mllm_stage_create(wl.layers)
+    infos = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+
+    def randn(r, c, scale=1.0, shift=0.0):
+        return (torch.randn(r, c, generator=gen, device=dev, dtype=torch.float32) * scale + shift).to(torch.bfloat16)
+
+    params = [randn(r, c, 0.02, 1.0 if name.endswith("_g") else 0.0) for name, _, r, c in infos]
+    dparams = [torch.zeros(r, c, dtype=torch.float32, device=dev) for _, _, r, c in infos]
+    kinds = [l.kind for l in wl.layers]
+    uses_img = kinds[0] in (W.LAYER_VIT, W.LAYER_PROJECTOR)
+    uses_seq = W.LAYER_DECODER in kinds or W.LAYER_PROJECTOR in kinds
+    x_img = randn(wl.batch.img.total_tokens, wl.layers[0].d_model) if uses_img else None
+    d_seq = next((l.d_out if l.kind == W.LAYER_PROJECTOR else l.d_model) for l in wl.layers
+                 if l.kind != W.LAYER_VIT) if uses_seq else 0
+    x_seq = randn(wl.batch.seq.total_tokens, d_seq) if uses_seq else None
+    last = wl.layers[-1]
+    out_rows = wl.batch.img.total_tokens if last.kind == W.LAYER_VIT else wl.batch.seq.total_tokens
+    out_cols = last.d_out if last.kind == W.LAYER_PROJECTOR else last.d_model
+    dy = randn(out_rows, out_cols)
+    y = torch.empty(out_rows, out_cols, dtype=torch.bfloat16, device=dev)
+    dx_img = torch.empty_like(x_img) if uses_img else None
+    dx_seq = torch.empty_like(x_seq) if uses_seq else None
+    sb, wb = B.mllm_stage_sizes(h, wl.batch)
+    saved = torch.empty(sb, dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb, dtype=torch.uint8, device=dev)
+
+    def step(accumulate):
+        B.mllm_stage_fwd(h, wl.batch, params, x_img, x_seq, y, saved, ws)
+        B.mllm_stage_bwd(h, wl.batch, params, dy, saved, dx_img, dx_seq, dparams, accumulate, ws)
+
+    for _ in range(args.warmup):
+        step(0)
+    torch.cuda.synchronize()
+    # timed region: K steps; per-launch event pairs are recorded inside it on the launch stream
+    n_launch_guess = 64 * len(wl.layers) * args.steps + 64
+    B.mllm_profile_begin(n_launch_guess)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(1 if i else 0)        # microbatches of one optimizer step accumulate their gradients
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    prof, dropped = B.mllm_profile_end()
+
+    # forward-only timing (for the forward : backward ratio)
+    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    f0.record()
+    for _ in range(max(1, args.steps // 2)):
+        B.mllm_stage_fwd(h, wl.batch, params, x_img, x_seq, y, saved, ws)
+    f1.record()
+    torch.cuda.synchronize()
+    fwd_ms = f0.elapsed_time(f1) / max(1, args.steps // 2)
+    finite = bool(torch.isfinite(y.float()).all().item())
+    B.mllm_stage_destroy(h)
+    props = torch.cuda.get_device_properties(0)
+    return dict(gpu_ms=gpu_ms, wall_ms=wall_ms, prof=prof, dropped=dropped, fwd_ms=fwd_ms, finite=finite,
+                saved_gib=sb / 2 ** 30, workspace_gib=wb / 2 ** 30, device=props.name,
+                cus=props.multi_processor_count, clock_mhz=getattr(props, 'clock_rate', 0) / 1e3)
+
+
+def cpu_baseline(sample_tokens: int = 1152):
+    """Time the fp64 oracle on a bounded sample of the default workload: a microbatch drawn with the
+    same long-tailed mix at a `sample_tokens` budget, through ONE ViT-L layer, the connector and ONE
+    8B-GQA decoder layer, forward+backward.  The whole-stage rate follows by scaling to 24 and 8
+    layers (the oracle's layers are identical in cost)."""
+    from oracle import stage_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    samples = W.draw_samples_mix8b(414, sample_tokens)
+    if sum(k for k, _ in samples) == 0:
+        samples = [(1, sample_tokens - W.IMG_TOKENS)]
+    batch = W.batch_from_samples(samples)
+    vit = W.make_workload("vit", [W.vit_l_layer()], batch, 1)
+    dec = W.make_workload("dec", [W.projector_layer(1024, 4096), W.dec8b_layer()], batch, 2)
+
+    def timed(wl):
+        t0 = time.perf_counter()
+        y, caches = O.stage_fwd(wl.layers, wl.params, wl.batch, wl.x_img, wl.x_seq)
+        O.stage_bwd(wl.layers, wl.params, wl.batch, caches, wl.dy.astype(np.float64))
+        return time.perf_counter() - t0
+
+    t_vit, t_dec = timed(vit), timed(dec)
+    stage_s = 24 * t_vit + 8 * t_dec
+    return {"value": batch.seq.total_tokens / stage_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d-token microbatch (%d image tokens) of the same mix through 1 ViT-L layer (%.2f s) and "
+                      "connector + 1 8B-GQA decoder layer (%.2f s), fp64 NumPy; scaled to 24 + 8 layers"
+                      % (batch.seq.total_tokens, batch.img.total_tokens, t_vit, t_dec)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="full_stage_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build measures one GPU's stage; run with --gpus 1 "
+                         "(no collectives or sharding are part of it)")
+    wl, desc = build_workload(args.workload)
+    lin_f, attn_f = stage_fwd_flops(wl.layers, wl.batch)
+    step_flops = 3.0 * (lin_f + attn_f)
+    tokens = wl.batch.seq.total_tokens if wl.batch.seq is not None else wl.batch.img.total_tokens
+    r = run_gpu(args, wl)
+    ms_per_step = r["gpu_ms"] / args.steps
+    tok_s = tokens / (ms_per_step * 1e-3)
+    prof = r["prof"]
+    # dominant kernel = the GEMM class with the largest share of time
+    gemm_cls = max(("gemm_fwd", "gemm_dx", "gemm_dw"), key=lambda c: prof[c][1])
+    n, ms, work = prof[gemm_cls]
+    achieved = work / (ms * 1e-3) if ms > 0 else 0.0
+    all_gemm_ms = sum(prof[c][1] for c in ("gemm_fwd", "gemm_dx", "gemm_dw"))
+    all_gemm_work = sum(prof[c][2] for c in ("gemm_fwd", "gemm_dx", "gemm_dw"))
+    kernel_names = {"gemm_fwd": "gemm_kernel<A [M,K], B [K,N], bf16 out> (Y = X.W)",
+                    "gemm_dx": "gemm_kernel<A [M,K], B [N,K], bf16 out> (dX = dY.W^T)",
+                    "gemm_dw": "gemm_kernel<A [K,M], B [K,N], fp32 out> (dW = X^T.dY)"}
+    out = {
+        "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "description": desc, "packed_tokens": int(tokens),
+                   "image_tokens": int(wl.batch.img.total_tokens) if wl.batch.img is not None else 0,
+                   "n_samples": int(wl.batch.seq.n_segments) if wl.batch.seq is not None else 0,
+                   "longest_sample": int(wl.batch.seq.max_seqlen) if wl.batch.seq is not None else 0},
+        "model_tflop_per_step": step_flops / 1e12,
+        "model_tflops": step_flops / (ms_per_step * 1e-3) / 1e12,
+        "mfma_peak_frac": step_flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
+        "attention_flop_share": attn_f / (lin_f + attn_f),
+        "fwd_ms": r["fwd_ms"], "bwd_over_fwd": (ms_per_step - r["fwd_ms"]) / r["fwd_ms"],
+        "host_wall_ms_per_step": r["wall_ms"] / args.steps,
+        "roofline": {"bound": "mfma", "kernel": kernel_names[gemm_cls], "achieved": achieved / 1e12,
+                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+                     "traffic": None, "launches": n, "avg_launch_ms": ms / n if n else None,
+                     "all_gemm_tflops": all_gemm_work / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else None},
+        "breakdown_ms_per_step": {c: prof[c][1] / args.steps for c in prof},
+        "breakdown_rate": {
+            **{c: {"TFLOP/s": prof[c][2] / (prof[c][1] * 1e-3) / 1e12} for c in prof
+               if c != "elementwise" and prof[c][1] > 0},
+            **({"elementwise": {"GB/s": prof["elementwise"][2] / (prof["elementwise"][1] * 1e-3) / 1e9,
+                                "hbm_frac": prof["elementwise"][2] / (prof["elementwise"][1] * 1e-3) / HBM_PEAK}}
+               if prof["elementwise"][1] > 0 else {})},
+        "profile_records_dropped": r["dropped"], "outputs_finite": r["finite"],
+        "saved_GiB": r["saved_gib"], "workspace_GiB": r["workspace_gib"],
+        "device": r["device"], "compute_units": r["cus"], "clock_mhz": r["clock_mhz"],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+        out["cpu_baseline"]["gpu_over_cpu"] = tok_s / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -238,6 +238,20 @@ size_t mllm_op_colsum_partial_bytes(int64_t t, int64_t n);
 mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* partial, int64_t t,
                              int64_t n, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Per-launch timing, for measurement only (off by default; adds two event records per launch).
+ * mllm_profile_begin(max_records) creates the events and starts recording every kernel launch of
+ * the calling process' later mllm_* calls, bracketing each with HIP events on its launch stream.
+ * mllm_profile_end stops recording, waits for the recorded events, and sums per class
+ * (0 GEMM Y=X.W, 1 GEMM dX, 2 GEMM dW, 3 attention forward, 4 attention backward, 5 the
+ * norm / rotary / activation / reduction / copy kernels): launches[6], milliseconds[6] and
+ * work[6] (algorithmic FLOPs for classes 0-4, algorithmic bytes for class 5) are host arrays.
+ * Not thread-safe; records beyond max_records are dropped and counted in *dropped.
+ * ------------------------------------------------------------------------------------------ */
+mllm_status_t mllm_profile_begin(int32_t max_records);
+mllm_status_t mllm_profile_end(int64_t* launches, double* milliseconds, double* work,
+                               int64_t* dropped);
+
 #ifdef __cplusplus
 }
 #endif

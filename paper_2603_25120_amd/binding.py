@@ -24,7 +24,10 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
            "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
-           "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum"]
+           "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
+           "mllm_profile_end"]
+
+PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise"]
 
 
 class MllmError(RuntimeError):
@@ -63,6 +66,11 @@ def lib() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError("%s is missing: build it with `python -m paper_2603_25120_amd.build`" % LIB_PATH)
+    # One process, one HIP runtime: PyTorch (which owns the device memory handed to the library)
+    # ships its own libamdhip64 with the same soname as the system one this library links to.
+    # Loading PyTorch first makes the dynamic linker bind both to the same copy; the other order
+    # would put two runtimes in the process, and the second cannot see the GPU.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.mllm_last_error.restype = C.c_char_p
@@ -90,10 +98,10 @@ def lib() -> C.CDLL:
     L.mllm_op_colsum_partial_bytes.argtypes = [i64, i64]
     L.mllm_op_colsum_partial_bytes.restype = sz
     L.mllm_op_colsum.argtypes = [vp, vp, C.c_int, vp, i64, i64, vp]
+    L.mllm_profile_begin.argtypes = [i32]
+    L.mllm_profile_end.argtypes = [C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
     for name in EXPORTS:
-        fn = getattr(L, name)
-        if fn.restype is C.c_int and name not in ("mllm_last_error",):
-            fn.restype = C.c_int
+        getattr(L, name)          # every declared entry point must be exported
     _lib = L
     return L
 
@@ -288,3 +296,15 @@ def mllm_op_colsum_partial_bytes(t: int, n: int) -> int:
 
 def mllm_op_colsum(x, out, accumulate, partial, t, n, stream=None) -> None:
     _check(lib().mllm_op_colsum(_ptr(x), _ptr(out), int(accumulate), _ptr(partial), t, n, _stream(stream)))
+
+
+def mllm_profile_begin(max_records: int) -> None:
+    _check(lib().mllm_profile_begin(max_records))
+
+
+def mllm_profile_end():
+    """Returns {class: (launches, milliseconds, work)} and the number of dropped records."""
+    n = len(PROFILE_CLASSES)
+    launches, ms, work, dropped = (C.c_int64 * n)(), (C.c_double * n)(), (C.c_double * n)(), C.c_int64()
+    _check(lib().mllm_profile_end(launches, ms, work, C.byref(dropped)))
+    return {PROFILE_CLASSES[i]: (int(launches[i]), float(ms[i]), float(work[i])) for i in range(n)}, int(dropped.value)

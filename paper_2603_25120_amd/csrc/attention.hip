@@ -441,6 +441,7 @@ AttnParams make_params(const AttnArgs& a) {
 
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (a.n_q_tiles == 0) return hipSuccess;
+  ProfScope prof(PROF_ATTN_FWD, a.fwd_flops, s);
   AttnParams p = make_params(a);
   p.tiles = a.q_tiles;
   dim3 grid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles), block(256);  // heads fastest: heavy tiles first
@@ -452,6 +453,7 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   if (a.n_q_tiles == 0) return hipSuccess;
+  ProfScope prof(PROF_ATTN_BWD, 2.0 * a.fwd_flops, s);
   AttnParams p = make_params(a);
   const int64_t n = (int64_t)a.total_tokens * a.n_q_heads * (a.head_dim / 8);
   dim3 dgrid((unsigned)((n + 255) / 256)), block(256);

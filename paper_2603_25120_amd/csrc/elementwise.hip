@@ -356,6 +356,7 @@ hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const voi
                            float* stats, int64_t t, int64_t d, float eps, hipStream_t s) {
   if (t == 0) return hipSuccess;
   if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)t * (double)d, s);
   dim3 grid(blocks_for(t, ROWS_PER_BLOCK)), block(256);
 #define CALL(NV)                                                                                  \
   if (kind == 0) hipLaunchKernelGGL((norm_fwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)x, \
@@ -380,6 +381,7 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
                            hipStream_t s) {
   if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
   const int64_t W = norm_bwd_partial_rows(t);
+  ProfScope prof(PROF_ELEMENTWISE, (dres ? 8.0 : 6.0) * (double)t * (double)d, s);
   dim3 grid((unsigned)(W / ROWS_PER_BLOCK)), block(256);
 #define CALL(NV)                                                                                   \
   if (kind == 0) hipLaunchKernelGGL((norm_bwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
@@ -404,6 +406,7 @@ hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stri
   if (t == 0 || n_heads == 0) return hipSuccess;
   if (head_dim % 16 != 0 || row_stride % 8 != 0 || col0 % 8 != 0) return hipErrorInvalidValue;
   const int64_t n = t * (head_dim / 16);
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)t * (double)n_heads * (double)head_dim, s);
   hipLaunchKernelGGL(rope_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (bf16_t*)qk, pos, t,
                      row_stride, col0, (int)n_heads, (int)head_dim, log2((double)rope_base), inverse);
   return hipGetLastError();
@@ -413,6 +416,7 @@ hipError_t launch_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t 
   if (t == 0) return hipSuccess;
   if (f % 8 != 0) return hipErrorInvalidValue;
   const int64_t nvec = t * f / 8;
+  ProfScope prof(PROF_ELEMENTWISE, (act == 2 ? 6.0 : 4.0) * (double)t * (double)f, s);
   if (act == 2)
     hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s,
                        (const bf16_t*)pre, (bf16_t*)a, t, f);
@@ -427,6 +431,7 @@ hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, 
   if (t == 0) return hipSuccess;
   if (f % 8 != 0) return hipErrorInvalidValue;
   const int64_t nvec = t * f / 8;
+  ProfScope prof(PROF_ELEMENTWISE, (act == 2 ? 10.0 : 6.0) * (double)t * (double)f, s);
   if (act == 2)
     hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s,
                        (const bf16_t*)da, (const bf16_t*)pre, (bf16_t*)dpre, t, f);
@@ -445,6 +450,7 @@ hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate,
                          int64_t t, int64_t n, hipStream_t s) {
   if (n % 8 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
   const int64_t P = colsum_partial_rows(t);
+  ProfScope prof(PROF_ELEMENTWISE, 2.0 * (double)t * (double)n, s);
   hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks_for(n, 512), (unsigned)P), dim3(64), 0, s,
                      (const bf16_t*)x, ldx, partial, t, n);
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, partial,
@@ -457,6 +463,7 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, 
   if (n_rows == 0) return hipSuccess;
   if (d % 8 != 0) return hipErrorInvalidValue;
   const int64_t n = n_rows * (d / 8);
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n_rows * (double)d, s);
   hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s,
                      (const bf16_t*)src, (bf16_t*)dst, rows, n_rows, d / 8, gather);
   return hipGetLastError();
@@ -476,6 +483,7 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) 
   if (bytes == 0) return hipSuccess;
   if (bytes % 16 != 0) return hipErrorInvalidValue;
   const int64_t nvec = (int64_t)(bytes / 16);
+  ProfScope prof(PROF_ELEMENTWISE, 2.0 * (double)bytes, s);
   hipLaunchKernelGGL(copy_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, (const uint4*)src,
                      (uint4*)dst, nvec);
   return hipGetLastError();

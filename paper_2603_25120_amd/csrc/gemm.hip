@@ -223,6 +223,8 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  const int cls = g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
+  ProfScope prof(cls, 2.0 * (double)g.m * (double)g.n * (double)g.k, s);
   return launch_tile<128, 128, 64, 64>(g, s);
 }
 

@@ -36,6 +36,7 @@ struct AttnArgs {
   int32_t total_tokens, n_q_heads, n_kv_heads, head_dim;
   const AttnTile* q_tiles; int32_t n_q_tiles;     // device
   const AttnTile* kv_tiles; int32_t n_kv_tiles;   // device
+  double fwd_flops;                               // algorithmic forward FLOPs of this call (for timing reports)
 };
 constexpr int ATTN_FWD_Q_TILE = 128;   // query rows per workgroup, forward and dQ pass
 constexpr int ATTN_BWD_KV_TILE = 128;  // key rows per workgroup, dK/dV pass
@@ -66,5 +67,15 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, 
 hipError_t launch_zero_rows(void* dst, const int32_t* rows, int64_t n_rows, int64_t d,
                             hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
+// Optional per-launch timing with HIP events on the launch stream (off by default).  Classes:
+enum ProfClass { PROF_GEMM_FWD = 0, PROF_GEMM_DX = 1, PROF_GEMM_DW = 2, PROF_ATTN_FWD = 3,
+                 PROF_ATTN_BWD = 4, PROF_ELEMENTWISE = 5, PROF_N_CLASSES = 6 };
+struct ProfScope {   // records a start event now and a stop event when it goes out of scope
+  ProfScope(int cls, double work, hipStream_t s);
+  ~ProfScope();
+  int slot;
+  hipStream_t stream;
+};
 
 }  // namespace mllm

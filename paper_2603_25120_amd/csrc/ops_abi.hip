@@ -104,6 +104,12 @@ mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a) {
   a.kv_tiles = (const AttnTile*)(w + koff);
   a.n_q_tiles = (int)qt.size();
   a.n_kv_tiles = (int)kt.size();
+  double pairs = 0;
+  for (int s = 0; s < pack->n_segments; s++) {
+    const double len = pack->cu_seqlens_host[s + 1] - pack->cu_seqlens_host[s];
+    pairs += pack->mask_kind_host[s] == MLLM_MASK_CAUSAL ? 0.5 * len * len : len * len;
+  }
+  a.fwd_flops = 4.0 * pairs * a.n_q_heads * a.head_dim;
   return MLLM_OK;
 }
 

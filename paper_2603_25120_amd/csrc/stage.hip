@@ -180,7 +180,17 @@ struct Plan {
   size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
+  double img_pairs = 0, seq_pairs = 0;  // sum over segments of visible (query, key) pairs
 };
+
+double visible_pairs(const mllm_pack_t& p) {
+  double n = 0;
+  for (int s = 0; s < p.n_segments; s++) {
+    const double len = p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s];
+    n += p.mask_kind_host[s] == MLLM_MASK_CAUSAL ? 0.5 * len * len : len * len;
+  }
+  return n;
+}
 
 Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   Plan P;
@@ -188,6 +198,8 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   const bool need_seq = st->n_dec > 0 || st->proj >= 0;
   P.T_img = need_img ? b->img.total_tokens : 0;
   P.T_seq = need_seq ? b->seq.total_tokens : 0;
+  if (st->n_vit > 0) P.img_pairs = visible_pairs(b->img);
+  if (st->n_dec > 0) P.seq_pairs = visible_pairs(b->seq);
   Bump sv;
   P.saved.resize(st->layers.size());
   for (size_t i = 0; i < st->layers.size(); i++) {
@@ -347,7 +359,8 @@ hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t
   return gemm(x, k, 1, dy, n, 0, dw, n, k, n, T, 1, accumulate, nullptr, nullptr, 0, s);
 }
 
-AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char* ws, const Meta& M, bool img) {
+AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char* ws, const Plan& P, bool img) {
+  const Meta& M = P.meta;
   AttnArgs a;
   memset(&a, 0, sizeof a);
   const int64_t nq = nqkv_of(L);
@@ -362,6 +375,7 @@ AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char*
   a.kv_tiles = (const AttnTile*)(ws + (img ? M.img_kv_tiles : M.seq_kv_tiles));
   a.n_q_tiles = img ? M.n_img_q : M.n_seq_q;
   a.n_kv_tiles = img ? M.n_img_kv : M.n_seq_kv;
+  a.fwd_flops = 4.0 * (img ? P.img_pairs : P.seq_pairs) * L.n_q_heads * L.head_dim;
   return a;
 }
 
@@ -399,7 +413,7 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
   if (!vit)
     K_TRY(launch_rope(qkv, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 0, s));
-  AttnArgs a = attn_args(L, qkv, T, ws, P.meta, vit);
+  AttnArgs a = attn_args(L, qkv, T, ws, P, vit);
   a.o = o;
   a.lse = (float*)(saved + S.lse);
   K_TRY(launch_attn_fwd(a, s));
@@ -451,7 +465,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s));
   if (vit) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
   K_TRY(linear_dx(wd, prm[iwo], wc, T, d, d, s));
-  AttnArgs a = attn_args(L, qkv, T, ws, P.meta, vit);
+  AttnArgs a = attn_args(L, qkv, T, ws, P, vit);
   a.o = const_cast<char*>(o);
   a.lse = (float*)const_cast<char*>(saved + S.lse);
   a.d_o = wc;
