@@ -151,7 +151,7 @@ def run_gpu(args, wl):
                 cus=props.multi_processor_count, clock_mhz=getattr(props, 'clock_rate', 0) / 1e3)
 
 
-def cpu_baseline(sample_tokens: int = 1152):
+def cpu_baseline(sample_tokens: int = 6912):
     """Time the fp64 oracle on a bounded sample of the default workload: a microbatch drawn with the
     same long-tailed mix at a `sample_tokens` budget, through ONE ViT-L layer, the connector and ONE
     8B-GQA decoder layer, forward+backward.  The whole-stage rate follows by scaling to 24 and 8

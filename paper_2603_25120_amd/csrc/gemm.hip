@@ -24,36 +24,58 @@ namespace mllm {
 namespace {
 
 constexpr int BK = 64;
-constexpr int PAD = 8;  // elements; keeps 16-byte alignment and staggers LDS banks
+// Row padding (elements).  k-contiguous tiles: rows 144 B apart put any 8 consecutive rows' 16-byte
+// reads on distinct banks.  Tiles read with the transposing load: a row stride of 8 dwords mod 32
+// spreads the 4 rows x 32 B that 16 lanes touch over all banks.
+constexpr int PAD_K = 8;
+constexpr int PAD_T = 16;
 
-template <int ROWS, int COLS, int NT>
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t OOB = 0x80000000u;  // byte offset beyond any buffer this kernel accepts (< 2 GiB)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// Global -> register -> LDS staging of one operand tile through buffer loads: an out-of-range
+// offset returns zeros, so ragged edges need no branches.  K_ROWS: the tile's rows run along the
+// contraction index (operand stored [K, rows]); otherwise its columns do (stored [rows, K]).
+template <int ROWS, int COLS, int PADC, int NT, bool K_ROWS>
 struct TileLoader {
   static constexpr int VEC_PER_ROW = COLS / 8;
   static constexpr int NVEC = ROWS * COLS / 8;
   static constexpr int PER_THREAD = NVEC / NT;
-  static_assert(NVEC % NT == 0, "tile must divide among threads");
-  uint4 r[PER_THREAD];
+  static constexpr int STRIDE = COLS + PADC;
+  static_assert(NVEC % NT == 0 && NT % VEC_PER_ROW == 0, "tile must divide among threads");
+  u32x4 r[PER_THREAD];
+  uint32_t off[PER_THREAD];   // byte offset of this thread's vectors at k0 = 0, OOB if never valid
+  int klim[PER_THREAD];       // vector i is inside the matrix while k0 < klim[i]
+  uint32_t kstep;             // bytes per BK step
 
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, int64_t ld, int64_t row0,
-                                       int64_t col0, int64_t nrows, int64_t ncols, int tid) {
+  __device__ __forceinline__ void init(int64_t ld, int64_t fixed0, int64_t nfixed, int64_t K, int tid) {
+    kstep = (uint32_t)(K_ROWS ? BK * ld * 2 : BK * 2);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; i++) {
-      int v = tid + i * NT;
-      int rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
-      int64_t gr = row0 + rr, gc = col0 + cc;
-      if (gr < nrows && gc < ncols) {
-        r[i] = *reinterpret_cast<const uint4*>(g + gr * ld + gc);
-      } else {
-        r[i] = make_uint4(0, 0, 0, 0);
-      }
+      const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
+      const int64_t fx = fixed0 + (K_ROWS ? cc : rr);
+      const int64_t lin = K_ROWS ? (int64_t)rr * ld + fx : fx * ld + cc;
+      off[i] = fx < nfixed ? (uint32_t)(lin * 2) : OOB;
+      klim[i] = (int)(K - (K_ROWS ? rr : cc));
+    }
+  }
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int kt) {
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; i++) {
+      const uint32_t o = (off[i] != OOB && k0 < klim[i]) ? off[i] + (uint32_t)kt * kstep : OOB;
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o, 0, 0);
     }
   }
   __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; i++) {
-      int v = tid + i * NT;
-      int rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
-      *reinterpret_cast<uint4*>(lds + rr * (COLS + PAD) + cc) = r[i];
+      const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
+      *reinterpret_cast<u32x4*>(lds + rr * STRIDE + cc) = r[i];
     }
   }
 };
@@ -80,6 +102,7 @@ struct GemmParams {
   const bf16_t* bias;
   const bf16_t* res;
   int64_t M, N, K, lda, ldb, ldc, ldres;
+  uint32_t a_bytes, b_bytes;
   int accumulate;
   int tiles_m, tiles_n;
 };
@@ -107,11 +130,13 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = 64 * NWM * NWN;
   constexpr int TM = WM / 32, TN = WN / 32;
   // A tile: [BM][BK] (contraction contiguous) or [BK][BM] (as stored, transposing reads)
-  constexpr int A_ROWS = A_T ? BK : BM, A_COLS = A_T ? BM : BK;
-  constexpr int B_ROWS = B_T ? BK : BN, B_COLS = B_T ? BN : BK;
-  constexpr int A_STRIDE = A_COLS + PAD, B_STRIDE = B_COLS + PAD;
-  __shared__ __attribute__((aligned(16))) bf16_t As[A_ROWS * A_STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[B_ROWS * B_STRIDE];
+  constexpr int A_ROWS = A_T ? BK : BM, A_COLS = A_T ? BM : BK, A_PAD = A_T ? PAD_T : PAD_K;
+  constexpr int B_ROWS = B_T ? BK : BN, B_COLS = B_T ? BN : BK, B_PAD = B_T ? PAD_T : PAD_K;
+  constexpr int A_STRIDE = A_COLS + A_PAD, B_STRIDE = B_COLS + B_PAD;
+  constexpr int A_SIZE = A_ROWS * A_STRIDE, B_SIZE = B_ROWS * B_STRIDE;
+  // two LDS stages: tile kt+1 is written while tile kt is being multiplied
+  __shared__ __attribute__((aligned(16))) bf16_t As[2 * A_SIZE];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * B_SIZE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / NWN, wn = wave % NWN;
@@ -119,13 +144,14 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   tile_of_block(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-  TileLoader<A_ROWS, A_COLS, NT> la;
-  TileLoader<B_ROWS, B_COLS, NT> lb;
-  auto gload = [&](int64_t k0) {
-    if constexpr (A_T) la.load(p.a, p.lda, k0, m0, p.K, p.M, tid);
-    else la.load(p.a, p.lda, m0, k0, p.M, p.K, tid);
-    if constexpr (B_T) lb.load(p.b, p.ldb, k0, n0, p.K, p.N, tid);
-    else lb.load(p.b, p.ldb, n0, k0, p.N, p.K, tid);
+  TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T> la;
+  TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T> lb;
+  la.init(p.lda, m0, p.M, p.K, tid);
+  lb.init(p.ldb, n0, p.N, p.K, tid);
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes), rb = make_rsrc(p.b, p.b_bytes);
+  auto gload = [&](int kt) {
+    la.load(ra, kt);
+    lb.load(rb, kt);
   };
 
   f32x16 acc[TM][TN];
@@ -140,28 +166,55 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   gload(0);
   la.store(As, tid);
   lb.store(Bs, tid);
+  gload(1);
   __syncthreads();
+
+  // Fragments are double-buffered in registers: those of step kk+1 are fetched from LDS while
+  // the 16 MFMAs of step kk run; step 0 of the next tile is fetched right after the barrier.
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto fetch = [&](int buf, const bf16_t* at, const bf16_t* bt, int kk) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) af[buf][i] = fetch_frag<A_T, A_STRIDE>(at, wm * WM + 32 * i, kk, lane);
+#pragma unroll
+    for (int j = 0; j < TN; j++) bfr[buf][j] = fetch_frag<B_T, B_STRIDE>(bt, wn * WN + 32 * j, kk, lane);
+  };
+  fetch(0, As, Bs, 0);
+  // LDS reads issued per k-step of 16: one 16-byte read per k-contiguous fragment, two transposing
+  // reads per fragment of an operand stored along the other dimension.
+  constexpr int READS_PER_STEP = TM * (A_T ? 2 : 1) + TN * (B_T ? 2 : 1);
+  constexpr int MFMA_PER_STEP = TM * TN;
   for (int kt = 0; kt < nk; kt++) {
-    if (kt + 1 < nk) gload((int64_t)(kt + 1) * BK);
+    const int cur = kt & 1;
+    // Branch-free body (one scheduling region): the store of tile kt+1 and the prefetch of tile
+    // kt+2 always run; past the end the prefetch offsets are out of range (zeros, no traffic) and
+    // the stored stage is never read.
+    la.store(As + (cur ^ 1) * A_SIZE, tid);
+    lb.store(Bs + (cur ^ 1) * B_SIZE, tid);
+    gload(kt + 2);
+    const bf16_t* at = As + cur * A_SIZE;
+    const bf16_t* bt = Bs + cur * B_SIZE;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; kk++) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) af[i] = fetch_frag<A_T, A_STRIDE>(As, wm * WM + 32 * i, kk, lane);
-#pragma unroll
-      for (int j = 0; j < TN; j++) bfr[j] = fetch_frag<B_T, B_STRIDE>(Bs, wn * WN + 32 * j, kk, lane);
+      if (kk + 1 < BK / 16) fetch((kk + 1) & 1, at, bt, kk + 1);
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+    }
+    // Issue order for the region: every MFMA is followed by at most one LDS read of the next
+    // step's fragments, and every second MFMA by one LDS store or one global prefetch, so the
+    // memory instructions trickle out under the matrix pipeline instead of in bursts.
+#pragma unroll
+    for (int m = 0; m < MFMA_PER_STEP * (BK / 16); m++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (m < MFMA_PER_STEP * (BK / 16 - 1) && m % MFMA_PER_STEP < READS_PER_STEP)
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (m % 4 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      if (m % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
     __syncthreads();
-    if (kt + 1 < nk) {
-      la.store(As, tid);
-      lb.store(Bs, tid);
-      __syncthreads();
-    }
+    fetch(0, As + (cur ^ 1) * A_SIZE, Bs + (cur ^ 1) * B_SIZE, 0);
   }
 
   // Epilogue: acc[v] of a 32x32 block is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
@@ -198,6 +251,8 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
   p.bias = (const bf16_t*)g.bias; p.res = (const bf16_t*)g.residual;
   p.M = g.m; p.N = g.n; p.K = g.k; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldres = g.ldres;
   p.accumulate = g.accumulate;
+  p.a_bytes = (uint32_t)((g.a_layout ? g.k : g.m) * g.lda * 2);
+  p.b_bytes = (uint32_t)((g.b_layout ? g.n : g.k) * g.ldb * 2);
   p.tiles_m = (int)((g.m + BM - 1) / BM);
   p.tiles_n = (int)((g.n + BN - 1) / BN);
   dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(64 * (BM / WM) * (BN / WN));
@@ -223,8 +278,15 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  // operands are addressed through 32-bit buffer offsets
+  if ((g.a_layout ? g.k : g.m) * g.lda * 2 >= (int64_t)OOB || (g.b_layout ? g.n : g.k) * g.ldb * 2 >= (int64_t)OOB)
+    return hipErrorInvalidValue;
   const int cls = g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   ProfScope prof(cls, 2.0 * (double)g.m * (double)g.n * (double)g.k, s);
+  // 256x256 tiles (4 wavefronts of 128x128) once they fill the chip; smaller problems keep
+  // 128x128 tiles so that more workgroups exist.
+  const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
+  if (big_tiles >= 200) return launch_tile<256, 256, 128, 128>(g, s);
   return launch_tile<128, 128, 64, 64>(g, s);
 }
 
