@@ -200,7 +200,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
     }
     // Issue order for the region: every MFMA is followed by at most one LDS read of the next
     // step's fragments, and every second MFMA by one LDS store or one global prefetch, so the
@@ -217,28 +217,61 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
     fetch(0, As + (cur ^ 1) * A_SIZE, Bs + (cur ^ 1) * B_SIZE, 0);
   }
 
-  // Epilogue: acc[v] of a 32x32 block is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+  // Epilogue.  The MFMAs were issued with the operands swapped, so an accumulator block holds
+  // C transposed: a lane owns C row (lane%32) and acc[v] is column 8*(v/4) + 4*(lane/32) + v%4,
+  // i.e. runs of four consecutive columns.  One 32-row band at a time goes through a per-wavefront
+  // fp32 staging area in LDS and leaves as 16-byte chunks (256 or 512 contiguous bytes per row),
+  // with bias / residual / accumulate applied in fp32 and a single rounding on the way out.
+  constexpr int ST_STRIDE = WN + 4;  // floats
+  static_assert(NWM * NWN * 32 * ST_STRIDE * 4 <= 2 * A_SIZE * 2, "staging must fit in the A stages");
+  float* stage = reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE;
   const int h = lane >> 5, cl = lane & 31;
+  constexpr int EPC = OUT_F32 ? 4 : 8;  // output elements per 16-byte chunk
+  constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW;
 #pragma unroll
-  for (int j = 0; j < TN; j++) {
-    const int64_t col = n0 + wn * WN + 32 * j + cl;
-    if (col >= p.N) continue;
-    const float bias = p.bias ? bf16_to_f32(p.bias[col]) : 0.f;
+  for (int i = 0; i < TM; i++) {
+    __syncthreads();  // the band staged before (or the last tile's fragments) has been read
 #pragma unroll
-    for (int i = 0; i < TM; i++) {
+    for (int j = 0; j < TN; j++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int64_t row = m0 + wm * WM + 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
-        if (row >= p.M) continue;
-        float val = acc[i][j][v] + bias;
-        if constexpr (OUT_F32) {
-          float* c = reinterpret_cast<float*>(p.c) + row * p.ldc + col;
-          if (p.accumulate) val += *c;
-          *c = val;
-        } else {
-          if (p.res) val += bf16_to_f32(p.res[row * p.ldres + col]);
-          reinterpret_cast<bf16_t*>(p.c)[row * p.ldc + col] = f32_to_bf16(val);
+      for (int g4 = 0; g4 < 4; g4++)
+        *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
+            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < CHUNKS / 64; t++) {
+      const int c = lane + 64 * t, rr = c / CHUNKS_PER_ROW, cc = (c % CHUNKS_PER_ROW) * EPC;
+      const int64_t row = m0 + wm * WM + 32 * i + rr, col = n0 + wn * WN + cc;
+      if (row >= p.M || col >= p.N) continue;
+      float f[EPC];
+#pragma unroll
+      for (int q = 0; q < EPC / 4; q++) {
+        const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
+        f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
+      }
+      if (p.bias) {
+#pragma unroll
+        for (int q = 0; q < EPC / 2; q++) {
+          const uint32_t bb = *reinterpret_cast<const uint32_t*>(p.bias + col + 2 * q);
+          f[2 * q] += bf16lo(bb);
+          f[2 * q + 1] += bf16hi(bb);
         }
+      }
+      if constexpr (OUT_F32) {
+        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.c) + row * p.ldc + col);
+        if (p.accumulate) {
+          const float4 old = *dst;
+          f[0] += old.x; f[1] += old.y; f[2] += old.z; f[3] += old.w;
+        }
+        *dst = make_float4(f[0], f[1], f[2], f[3]);
+      } else {
+        if (p.res) {
+          const uint4 r = *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col);
+          f[0] += bf16lo(r.x); f[1] += bf16hi(r.x); f[2] += bf16lo(r.y); f[3] += bf16hi(r.y);
+          f[4] += bf16lo(r.z); f[5] += bf16hi(r.z); f[6] += bf16lo(r.w); f[7] += bf16hi(r.w);
+        }
+        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + row * p.ldc + col) =
+            make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
       }
     }
   }
