@@ -16,6 +16,8 @@
 // global -> registers (prefetch of the next tile, issued before the MFMAs of the current one)
 // -> LDS.  Tiles are visited in an order that keeps the workgroups resident on one XCD (they
 // share that XCD's L2) on neighbouring tiles of a GROUP_M-tall panel.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -63,17 +65,21 @@ struct TileLoader {
       klim[i] = (int)(K - (K_ROWS ? rr : cc));
     }
   }
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int kt) {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int kt) { load_part<0, PER_THREAD>(rsrc, kt); }
+  __device__ __forceinline__ void store(bf16_t* lds, int tid) const { store_part<0, PER_THREAD>(lds, tid); }
+  template <int I0, int I1>
+  __device__ __forceinline__ void load_part(__amdgpu_buffer_rsrc_t rsrc, int kt) {
     const int k0 = kt * BK;
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; i++) {
+    for (int i = I0; i < I1; i++) {
       const uint32_t o = (off[i] != OOB && k0 < klim[i]) ? off[i] + (uint32_t)kt * kstep : OOB;
       r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o, 0, 0);
     }
   }
-  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+  template <int I0, int I1>
+  __device__ __forceinline__ void store_part(bf16_t* lds, int tid) const {
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; i++) {
+    for (int i = I0; i < I1; i++) {
       const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
       *reinterpret_cast<u32x4*>(lds + rr * STRIDE + cc) = r[i];
     }
@@ -179,42 +185,42 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
     for (int j = 0; j < TN; j++) bfr[buf][j] = fetch_frag<B_T, B_STRIDE>(bt, wn * WN + 32 * j, kk, lane);
   };
   fetch(0, As, Bs, 0);
-  // LDS reads issued per k-step of 16: one 16-byte read per k-contiguous fragment, two transposing
-  // reads per fragment of an operand stored along the other dimension.
-  constexpr int READS_PER_STEP = TM * (A_T ? 2 : 1) + TN * (B_T ? 2 : 1);
-  constexpr int MFMA_PER_STEP = TM * TN;
+  constexpr int STEPS = BK / 16;
+  constexpr int A_PER = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T>::PER_THREAD / STEPS;
+  constexpr int B_PER = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T>::PER_THREAD / STEPS;
+  static_assert(A_PER >= 1 && B_PER >= 1, "each k-step must move at least one vector per operand");
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
-    // Branch-free body (one scheduling region): the store of tile kt+1 and the prefetch of tile
-    // kt+2 always run; past the end the prefetch offsets are out of range (zeros, no traffic) and
-    // the stored stage is never read.
-    la.store(As + (cur ^ 1) * A_SIZE, tid);
-    lb.store(Bs + (cur ^ 1) * B_SIZE, tid);
-    gload(kt + 2);
+    bf16_t* an = As + (cur ^ 1) * A_SIZE;
+    bf16_t* bn = Bs + (cur ^ 1) * B_SIZE;
     const bf16_t* at = As + cur * A_SIZE;
     const bf16_t* bt = Bs + cur * B_SIZE;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      if (kk + 1 < BK / 16) fetch((kk + 1) & 1, at, bt, kk + 1);
+    // Branch-free body.  Each of the four k-steps first moves a quarter of tile kt+1 from the
+    // staging registers into the other LDS stage and at once refills those registers with the
+    // same quarter of tile kt+2 (so every prefetch has a whole iteration to land), then fetches
+    // the next step's fragments and issues its 16 MFMAs.  Past the end the prefetch offsets are
+    // out of range (zeros, no traffic) and the stored stage is never read.
+    auto step = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      la.template store_part<kk * A_PER, (kk + 1) * A_PER>(an, tid);
+      lb.template store_part<kk * B_PER, (kk + 1) * B_PER>(bn, tid);
+      la.template load_part<kk * A_PER, (kk + 1) * A_PER>(ra, kt + 2);
+      lb.template load_part<kk * B_PER, (kk + 1) * B_PER>(rb, kt + 2);
+      if constexpr (kk + 1 < STEPS) fetch((kk + 1) & 1, at, bt, kk + 1);
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-    }
-    // Issue order for the region: every MFMA is followed by at most one LDS read of the next
-    // step's fragments, and every second MFMA by one LDS store or one global prefetch, so the
-    // memory instructions trickle out under the matrix pipeline instead of in bursts.
-#pragma unroll
-    for (int m = 0; m < MFMA_PER_STEP * (BK / 16); m++) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (m < MFMA_PER_STEP * (BK / 16 - 1) && m % MFMA_PER_STEP < READS_PER_STEP)
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      if (m % 4 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-      if (m % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+    static_assert(STEPS == 4, "four k-steps per tile");
     __syncthreads();
-    fetch(0, As + (cur ^ 1) * A_SIZE, Bs + (cur ^ 1) * B_SIZE, 0);
+    fetch(0, an, bn, 0);
   }
 
   // Epilogue.  The MFMAs were issued with the operands swapped, so an accumulator block holds
@@ -319,7 +325,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   // 256x256 tiles (4 wavefronts of 128x128) once they fill the chip; smaller problems keep
   // 128x128 tiles so that more workgroups exist.
   const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
-  if (big_tiles >= 200) return launch_tile<256, 256, 128, 128>(g, s);
+  if (big_tiles >= 200) return launch_tile<256, 256, 128, 64>(g, s);
   return launch_tile<128, 128, 64, 64>(g, s);
 }
 
