@@ -103,8 +103,8 @@ __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 *
 // forward
 // ---------------------------------------------------------------------------------------------
 template <int HD>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnParams p) {
-  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
+  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32, NB = BKV / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
   const AttnTile t = p.tiles[blockIdx.y];
@@ -120,14 +120,16 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnParams p) {
   const bf16_t* kbase = p.k + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
   const bf16_t* vbase = p.v + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
   const int kv_end = t.causal ? min(t.seg_len, t.tile0 + ATTN_FWD_Q_TILE) : t.seg_len;
-  const int wave_last_q = t.tile0 + 32 * wave + 31;
+  const int wave_first_q = t.tile0 + 32 * wave, wave_last_q = wave_first_q + 31;
 
   f32x16 oacc[ND];
 #pragma unroll
   for (int d = 0; d < ND; d++)
 #pragma unroll
     for (int v = 0; v < 16; v++) oacc[d][v] = 0.f;
+  // Running maximum in units of log2: m = max(score) * scale * log2(e); l = sum of exp2(...).
   float m = -INFINITY, l = 0.f;
+  const float c2 = p.scale_log2e;
 
   RowTile<BKV, HD> lk, lv;
   lk.load(kbase, p.kv_stride, 0, t.seg_len, tid);
@@ -142,45 +144,55 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnParams p) {
       lv.load(vbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
     }
     if (t.causal && kv0 > wave_last_q) continue;  // wavefront-uniform
-    f32x16 s[BKV / 32];
+    f32x16 s[NB];
 #pragma unroll
-    for (int b = 0; b < BKV / 32; b++) {
+    for (int b = 0; b < NB; b++)
 #pragma unroll
       for (int v = 0; v < 16; v++) s[b][v] = 0.f;
 #pragma unroll
-      for (int c = 0; c < NC; c++)
+    for (int c = 0; c < NC; c++)
+#pragma unroll
+      for (int b = 0; b < NB; b++)
         s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s[b], 0, 0, 0);
+    // Only tiles that cross the segment end or the diagonal need the mask (wavefront-uniform).
+    const bool need_mask = (kv0 + BKV > t.seg_len) || (t.causal && kv0 + BKV - 1 > wave_first_q);
+    if (need_mask) {
+#pragma unroll
+      for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int kv = kv0 + 32 * b + acc_row(v, h);
+          const bool vis = kv < t.seg_len && (!t.causal || kv <= qrow);
+          s[b][v] = vis ? s[b][v] : -INFINITY;
+        }
     }
-    float mx = -INFINITY;
+    float mx = s[0][0];
 #pragma unroll
-    for (int b = 0; b < BKV / 32; b++)
+    for (int b = 0; b < NB; b++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int kv = kv0 + 32 * b + acc_row(v, h);
-        const bool vis = kv < t.seg_len && (!t.causal || kv <= qrow);
-        s[b][v] = vis ? s[b][v] * p.scale_log2e : -INFINITY;
-        mx = fmaxf(mx, s[b][v]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[b][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
     const float m_new = fmaxf(m, mx);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = fast_exp2(m - m_use);
     float rs = 0.f;
 #pragma unroll
-    for (int b = 0; b < BKV / 32; b++)
+    for (int b = 0; b < NB; b++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        s[b][v] = fast_exp2(s[b][v] - m_use);
+        s[b][v] = fast_exp2(fmaf(s[b][v], c2, -m_use));
         rs += s[b][v];
       }
     l = l * alpha + rs;
+    if (__any(m_new != m)) {  // the accumulator only needs rescaling when some row's maximum moved
+#pragma unroll
+      for (int d = 0; d < ND; d++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) oacc[d][v] *= alpha;
+    }
     m = m_new;
 #pragma unroll
-    for (int d = 0; d < ND; d++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) oacc[d][v] *= alpha;
-#pragma unroll
-    for (int b = 0; b < BKV / 32; b++)
+    for (int b = 0; b < NB; b++)
 #pragma unroll
       for (int cc = 0; cc < 2; cc++) {
         const bf16x8 pf = acc_to_frag(s[b], cc);
@@ -236,7 +248,7 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
 // dQ pass: one workgroup per (query tile of 128, head), looping over key tiles.
 // ---------------------------------------------------------------------------------------------
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
   constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
@@ -254,8 +266,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnParams p) {
     qf[c] = global_frag(qp + 16 * c, qok);
     dof[c] = global_frag(dop + 16 * c, qok);
   }
-  const float lse2 = qok ? p.lse[(int64_t)head * p.T + grow] * LOG2E : 0.f;
+  // Rows beyond the segment get lse = +inf, so their probabilities are exp2(-inf) = 0.
+  const float lse2 = qok ? p.lse[(int64_t)head * p.T + grow] * LOG2E : INFINITY;
   const float delta = qok ? p.delta[(int64_t)head * p.T + grow] : 0.f;
+  const int wave_first_q = t.tile0 + 32 * wave;
 
   const bf16_t* kbase = p.k + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
   const bf16_t* vbase = p.v + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
@@ -291,13 +305,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnParams p) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Vs, 32 * b, c, lane), dof[c], dp, 0, 0, 0);
       }
+      const bool need_mask = (kv0 + 32 * b + 32 > t.seg_len) || (t.causal && kv0 + 32 * b + 31 > wave_first_q);
+      if (need_mask) {
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int kv = kv0 + 32 * b + acc_row(v, h);
-        const bool vis = qok && kv < t.seg_len && (!t.causal || kv <= qrow);
-        const float pr = vis ? fast_exp2(s[v] * p.scale_log2e - lse2) : 0.f;
-        s[v] = pr * (dp[v] - delta);   // dS^T
+        for (int v = 0; v < 16; v++) {
+          const int kv = kv0 + 32 * b + acc_row(v, h);
+          const bool vis = kv < t.seg_len && (!t.causal || kv <= qrow);
+          s[v] = vis ? s[v] : -INFINITY;
+        }
       }
+#pragma unroll
+      for (int v = 0; v < 16; v++) s[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse2)) * (dp[v] - delta);   // dS^T
 #pragma unroll
       for (int cc = 0; cc < 2; cc++) {
         const bf16x8 dsf = acc_to_frag(s, cc);
@@ -363,7 +381,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
     for (int q0 = q_begin; q0 < t.seg_len; q0 += BQ) {
       lq.load(qbase, p.q_stride, q0, t.seg_len, tid);
       ldo.load(dobase, p.o_stride, q0, t.seg_len, tid);
-      float my_lse = 0.f, my_delta = 0.f;
+      float my_lse = INFINITY, my_delta = 0.f;   // +inf: probabilities of rows past the segment are 0
       if (tid < BQ && q0 + tid < t.seg_len) {
         my_lse = lse_h[q0 + tid] * LOG2E;
         my_delta = delta_h[q0 + tid];
@@ -385,12 +403,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
         }
         f32x16 pr;
+        if (t.causal && q0 + 32 * b <= wave_first_k + 31) {   // block touches the diagonal
+#pragma unroll
+          for (int v = 0; v < 16; v++) s[v] = (krow <= q0 + 32 * b + acc_row(v, h)) ? s[v] : -INFINITY;
+        }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const int qi = 32 * b + acc_row(v, h);
-          const int qrow = q0 + qi;
-          const bool vis = kok && qrow < t.seg_len && (!t.causal || krow <= qrow);
-          pr[v] = vis ? fast_exp2(s[v] * p.scale_log2e - lse_s[qi]) : 0.f;
+          pr[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse_s[qi]));
           s[v] = pr[v] * (dp[v] - delta_s[qi]);   // dS
         }
 #pragma unroll
