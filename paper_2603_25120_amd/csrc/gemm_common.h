@@ -1,0 +1,128 @@
+// Pieces shared by the GEMM kernels: launch parameters, buffer resources, the XCD-aware tile
+// order and the LDS-staged epilogue.
+#pragma once
+#include <type_traits>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace mllm {
+
+constexpr int BK = 64;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t OOB = 0x80000000u;  // byte offset beyond any buffer these kernels accept (< 2 GiB)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+struct GemmParams {
+  const bf16_t* a;
+  const bf16_t* b;
+  void* c;
+  const bf16_t* bias;
+  const bf16_t* res;
+  int64_t M, N, K, lda, ldb, ldc, ldres;
+  uint32_t a_bytes, b_bytes;
+  int accumulate;
+  int tiles_m, tiles_n;
+};
+
+inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
+  GemmParams p;
+  p.a = (const bf16_t*)g.a; p.b = (const bf16_t*)g.b; p.c = g.c;
+  p.bias = (const bf16_t*)g.bias; p.res = (const bf16_t*)g.residual;
+  p.M = g.m; p.N = g.n; p.K = g.k; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldres = g.ldres;
+  p.accumulate = g.accumulate;
+  p.a_bytes = (uint32_t)((g.a_layout ? g.k : g.m) * g.lda * 2);
+  p.b_bytes = (uint32_t)((g.b_layout ? g.n : g.k) * g.ldb * 2);
+  p.tiles_m = (int)((g.m + bm - 1) / bm);
+  p.tiles_n = (int)((g.n + bn - 1) / bn);
+  return p;
+}
+
+constexpr int GROUP_M = 8;
+
+// Workgroups are dealt round-robin to the 8 XCDs.  Renumber so that each XCD gets a contiguous
+// range of tile ids, then walk the tile grid in panels of GROUP_M tile-rows.
+__device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, int tiles_n,
+                                              int& tm, int& tn) {
+  const int per = (nblk + 7) >> 3, r = nblk & 7;
+  const int x = pid & 7, local = pid >> 3;
+  int off = (r == 0 || x <= r) ? x * per : r * per + (x - r) * (per - 1);
+  int t = off + local;
+  const int in_group = GROUP_M * tiles_n;
+  const int gid = t / in_group;
+  const int first_m = gid * GROUP_M;
+  const int gsz = min(tiles_m - first_m, GROUP_M);
+  tm = first_m + (t % in_group) % gsz;
+  tn = (t % in_group) / gsz;
+}
+
+// Epilogue.  The MFMAs are issued with the operands swapped, so an accumulator block holds C
+// transposed: a lane owns C row (lane%32) and acc[v] is column 8*(v/4) + 4*(lane/32) + v%4, i.e.
+// runs of four consecutive columns.  One 32-row band at a time goes through a per-wavefront fp32
+// staging area in LDS (32 x (WN+4) floats at `stage`) and leaves as 16-byte chunks (256 or 512
+// contiguous bytes per row), with bias / residual / accumulate applied in fp32 and a single
+// rounding on the way out.  Every wavefront of the workgroup must call it (it synchronises).
+template <int TM, int TN, bool OUT_F32>
+__device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM][TN], float* stage,
+                                           int64_t row0, int64_t col0, int lane) {
+  constexpr int WN = 32 * TN, ST_STRIDE = WN + 4;
+  const int h = lane >> 5, cl = lane & 31;
+  constexpr int EPC = OUT_F32 ? 4 : 8;  // output elements per 16-byte chunk
+  constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    __syncthreads();  // the band staged before (or the last tile's fragments) has been read
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++)
+        *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
+            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < CHUNKS / 64; t++) {
+      const int c = lane + 64 * t, rr = c / CHUNKS_PER_ROW, cc = (c % CHUNKS_PER_ROW) * EPC;
+      const int64_t row = row0 + 32 * i + rr, col = col0 + cc;
+      if (row >= p.M || col >= p.N) continue;
+      float f[EPC];
+#pragma unroll
+      for (int q = 0; q < EPC / 4; q++) {
+        const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
+        f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
+      }
+      if (p.bias) {
+#pragma unroll
+        for (int q = 0; q < EPC / 2; q++) {
+          const uint32_t bb = *reinterpret_cast<const uint32_t*>(p.bias + col + 2 * q);
+          f[2 * q] += bf16lo(bb);
+          f[2 * q + 1] += bf16hi(bb);
+        }
+      }
+      if constexpr (OUT_F32) {
+        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.c) + row * p.ldc + col);
+        if (p.accumulate) {
+          const float4 old = *dst;
+          f[0] += old.x; f[1] += old.y; f[2] += old.z; f[3] += old.w;
+        }
+        *dst = make_float4(f[0], f[1], f[2], f[3]);
+      } else {
+        if (p.res) {
+          const uint4 r = *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col);
+          f[0] += bf16lo(r.x); f[1] += bf16hi(r.x); f[2] += bf16lo(r.y); f[3] += bf16hi(r.y);
+          f[4] += bf16lo(r.z); f[5] += bf16hi(r.z); f[6] += bf16lo(r.w); f[7] += bf16hi(r.w);
+        }
+        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + row * p.ldc + col) =
+            make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+      }
+    }
+  }
+}
+
+// Implemented in gemm_dma.hip: 256x256 tiles fed by direct-to-LDS loads.
+hipError_t launch_gemm_dma(const GemmArgs& g, hipStream_t s);
+
+}  // namespace mllm

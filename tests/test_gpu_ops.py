@@ -47,6 +47,28 @@ def test_gemm_layouts(B, m, n, k, a_layout, b_layout):
     assert nmax_err(host_f64(c32), ref) < 2e-3
 
 
+@pytest.mark.parametrize("a_layout,b_layout,f32", [(0, 0, 0), (0, 1, 0), (1, 0, 1), (1, 1, 0), (0, 0, 1)])
+def test_gemm_large_ragged(B, a_layout, b_layout, f32):
+    """Enough 256x256 tiles to take the large-tile kernel, with ragged M, N and K edges."""
+    m, n, k = 3512, 4104, 264
+    a = W.draw_tensor(61, m, k)
+    b = W.bf16_round(W.draw_tensor(62, k, n) * np.float32(0.125))
+    a_st = np.ascontiguousarray(a.T) if a_layout else a
+    b_st = np.ascontiguousarray(b.T) if b_layout else b
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    bias = W.draw_tensor(63, 1, n)
+    c = torch.zeros(m, n, dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout, out_fp32=f32, bias=dev_bf16(bias))
+    assert nmax_err(host_f64(c), ref + bias) < (2e-3 if f32 else 1e-2)
+    # second call with a different K so that stale LDS contents would show
+    k2 = 72
+    ref2 = a[:, :k2].astype(np.float64) @ b[:k2].astype(np.float64)
+    a2 = np.ascontiguousarray(a[:, :k2].T) if a_layout else np.ascontiguousarray(a[:, :k2])
+    b2 = np.ascontiguousarray(b[:k2].T) if b_layout else np.ascontiguousarray(b[:k2])
+    B.mllm_op_gemm(dev_bf16(a2), dev_bf16(b2), c, m, n, k2, a_layout, b_layout, out_fp32=f32)
+    assert nmax_err(host_f64(c), ref2) < (2e-3 if f32 else 1e-2)
+
+
 def test_gemm_epilogues(B):
     m, n, k = 333, 192, 256
     a, b = W.draw_tensor(3, m, k), W.bf16_round(W.draw_tensor(4, k, n) * np.float32(0.1))
