@@ -15,6 +15,8 @@
 //     swz(k) = 4 * (k & 3); fragments are read with the LDS transposing read.
 // Two stages per operand in separate LDS arrays; the K loop is unrolled by two so that every
 // access names its stage statically.
+#include <cstdlib>
+
 #include "gemm_common.h"
 
 namespace mllm {
@@ -61,11 +63,11 @@ struct DmaTile {
       klim[i] = (int)(K - (K_ROWS ? r : 8 * c));
     }
     // One lane per 128-byte line of the tile: ROWS * ROWELEMS * 2 / 128 lines = 64 * NW lanes.
-    static_assert(ROWS * ROWELEMS * 2 / 128 == 64 * NW, "one prefetch instruction per wavefront");
-    constexpr int LINES_PER_ROW = ROWELEMS * 2 / 128;
+    constexpr int LINES_PER_ROW = ROWELEMS * 2 / 128, N_LINES = ROWS * LINES_PER_ROW;
+    static_assert(N_LINES <= 64 * NW, "at most one prefetch instruction per wavefront");
     const int line = wave * 64 + lane, r = line / LINES_PER_ROW, e = (line % LINES_PER_ROW) * 64;
     const int64_t fx = fixed0 + (K_ROWS ? e : r);
-    pf_off = fx < nfixed ? (uint32_t)((K_ROWS ? (int64_t)r * ld + fx : fx * ld + e) * 2) : OOB;
+    pf_off = (fx < nfixed && line < N_LINES) ? (uint32_t)((K_ROWS ? (int64_t)r * ld + fx : fx * ld + e) * 2) : OOB;
     pf_klim = (int)(K - (K_ROWS ? r : e));
   }
   // Touch every line of tile kt so that it is in L2 by the time the real load asks for it.  The
@@ -216,6 +218,8 @@ hipError_t launch_dma_tile(const GemmArgs& g, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_gemm_dma(const GemmArgs& g, hipStream_t s) {
+  static const char* impl = getenv("MLLM_GEMM_IMPL");
+  if (impl && impl[0] == '8') return launch_dma_tile<256, 256, 128, 64>(g, s);
   return launch_dma_tile<256, 256, 128, 128>(g, s);
 }
 

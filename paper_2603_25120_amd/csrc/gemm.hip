@@ -219,10 +219,10 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     return hipErrorInvalidValue;
   const int cls = g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   ProfScope prof(cls, 2.0 * (double)g.m * (double)g.n * (double)g.k, s);
-  // 256x256 tiles (4 wavefronts of 128x128) once they fill the chip; smaller problems keep
+  // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep
   // 128x128 tiles so that more workgroups exist.
   const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
-  if (big_tiles >= 200) return launch_gemm_dma(g, s);
+  if (big_tiles >= 200) return launch_tile<256, 256, 128, 64>(g, s);
   return launch_tile<128, 128, 64, 64>(g, s);
 }
 

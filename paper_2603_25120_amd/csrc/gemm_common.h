@@ -122,7 +122,4 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   }
 }
 
-// Implemented in gemm_dma.hip: 256x256 tiles fed by direct-to-LDS loads.
-hipError_t launch_gemm_dma(const GemmArgs& g, hipStream_t s);
-
 }  // namespace mllm
