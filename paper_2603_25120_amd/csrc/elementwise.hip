@@ -359,6 +359,21 @@ __global__ void zero_rows_kernel(bf16_t* __restrict__ dst, const int32_t* __rest
   const int64_t r = rows[i / vec_per_row], c = i % vec_per_row;
   reinterpret_cast<uint4*>(dst)[r * vec_per_row + c] = make_uint4(0, 0, 0, 0);
 }
+__global__ void splitk_reduce_kernel(const float4* __restrict__ partial, float4* __restrict__ out,
+                                     int splits, int64_t nvec, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float4 t = partial[i];
+  for (int sp = 1; sp < splits; sp++) {
+    const float4 v = partial[(int64_t)sp * nvec + i];
+    t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+  }
+  if (accumulate) {
+    const float4 o = out[i];
+    t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
+  }
+  out[i] = t;
+}
 __global__ void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t nvec) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nvec) dst[i] = src[i];
@@ -499,6 +514,16 @@ hipError_t launch_zero_rows(void* dst, const int32_t* rows, int64_t n_rows, int6
   const int64_t n = n_rows * (d / 8);
   hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (bf16_t*)dst,
                      rows, n_rows, d / 8);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* partial, float* out, int splits, int64_t n, int accumulate,
+                                hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (n % 4 != 0) return hipErrorInvalidValue;
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n * (splits + 1 + (accumulate ? 1 : 0)), s);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(n / 4, 256)), dim3(256), 0, s,
+                     (const float4*)partial, (float4*)out, splits, n / 4, accumulate);
   return hipGetLastError();
 }
 

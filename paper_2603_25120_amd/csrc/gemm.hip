@@ -16,6 +16,8 @@
 // global -> registers (prefetch of the next tile, issued before the MFMAs of the current one)
 // -> LDS.  Tiles are visited in an order that keeps the workgroups resident on one XCD (they
 // share that XCD's L2) on neighbouring tiles of a GROUP_M-tall panel.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 namespace mllm {
@@ -127,11 +129,13 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  const int nk = (int)((p.K + BK - 1) / BK);
-  gload(0);
+  // Split-K: workgroup row blockIdx.y owns k-tiles [kt0, kt0 + nk) and writes its own partial C.
+  const int kt0 = blockIdx.y * p.kt_per_split;
+  const int nk = min(p.kt_per_split, (int)((p.K + BK - 1) / BK) - kt0);
+  gload(kt0);
   la.store(As, tid);
   lb.store(Bs, tid);
-  gload(1);
+  gload(kt0 + 1);
   __syncthreads();
 
   // Fragments are double-buffered in registers: those of step kk+1 are fetched from LDS while
@@ -163,8 +167,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
       constexpr int kk = decltype(kk_c)::value;
       la.template store_part<kk * A_PER, (kk + 1) * A_PER>(an, tid);
       lb.template store_part<kk * B_PER, (kk + 1) * B_PER>(bn, tid);
-      la.template load_part<kk * A_PER, (kk + 1) * A_PER>(ra, kt + 2);
-      lb.template load_part<kk * B_PER, (kk + 1) * B_PER>(rb, kt + 2);
+      la.template load_part<kk * A_PER, (kk + 1) * A_PER>(ra, kt0 + kt + 2);
+      lb.template load_part<kk * B_PER, (kk + 1) * B_PER>(rb, kt0 + kt + 2);
       if constexpr (kk + 1 < STEPS) fetch((kk + 1) & 1, at, bt, kk + 1);
 #pragma unroll
       for (int i = 0; i < TM; i++)
@@ -184,14 +188,19 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
 
   constexpr int ST_STRIDE = WN + 4;  // floats
   static_assert(NWM * NWN * 32 * ST_STRIDE * 4 <= 2 * A_SIZE * 2, "staging must fit in the A stages");
+  if constexpr (OUT_F32) p.c = reinterpret_cast<float*>(p.c) + blockIdx.y * p.c_split_stride;
   store_tile<TM, TN, OUT_F32>(p, acc, reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE,
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int BM, int BN, int WM, int WN>
-hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   GemmParams p = make_gemm_params(g, BM, BN);
-  dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(64 * (BM / WM) * (BN / WN));
+  if (splits > 1) {
+    p.kt_per_split = (p.kt_per_split + splits - 1) / splits;
+    p.c_split_stride = g.m * g.n;
+  }
+  dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits), block(64 * (BM / WM) * (BN / WN));
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
 #define MLLM_GEMM_CASE(AT, BT, F32)                                                      \
   if (at == AT && bt == BT && (g.out_fp32 != 0) == F32) {                                \
@@ -212,6 +221,28 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
+// Weight-gradient GEMMs of narrow layers (M x N small, K = tokens large) have too few output tiles
+// to fill 256 CUs.  They are cut along K into `splits` partial products (fp32, in a scratch
+// buffer), summed afterwards in a fixed order.  Returns 1 when the plain launch is used.
+namespace {
+struct SplitPlan { int splits; bool big_tile; };
+SplitPlan plan_split(int64_t m, int64_t n, int64_t k) {
+  const int64_t t256 = ((m + 255) / 256) * ((n + 255) / 256), t128 = ((m + 127) / 128) * ((n + 127) / 128);
+  const int64_t nk = (k + BK - 1) / BK;
+  if (t256 >= 200) return {1, true};
+  const bool big = t256 >= 24;
+  int64_t want = big ? (320 + t256 - 1) / t256 : (512 + t128 - 1) / t128;
+  want = std::min<int64_t>(want, 16);
+  want = std::min<int64_t>(want, nk / 8);   // at least 8 k-tiles per split
+  return {(int)std::max<int64_t>(want, 1), big};
+}
+}  // namespace
+
+size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k) {
+  const SplitPlan sp = plan_split(m, n, k);
+  return sp.splits > 1 ? (size_t)sp.splits * (size_t)m * (size_t)n * 4 : 0;
+}
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
   // operands are addressed through 32-bit buffer offsets
@@ -223,6 +254,17 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   // 128x128 tiles so that more workgroups exist.
   const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
   if (big_tiles >= 200) return launch_tile<256, 256, 128, 64>(g, s);
+  const SplitPlan sp = plan_split(g.m, g.n, g.k);
+  if (sp.splits > 1 && g.out_fp32 && !g.bias && g.ldc == g.n && g.splitk_ws &&
+      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4) {
+    GemmArgs part = g;
+    part.c = g.splitk_ws;
+    part.accumulate = 0;
+    hipError_t e = sp.big_tile ? launch_tile<256, 256, 128, 64>(part, s, sp.splits)
+                               : launch_tile<128, 128, 64, 64>(part, s, sp.splits);
+    if (e != hipSuccess) return e;
+    return launch_splitk_reduce((const float*)g.splitk_ws, (float*)g.c, sp.splits, g.m * g.n, g.accumulate, s);
+  }
   return launch_tile<128, 128, 64, 64>(g, s);
 }
 

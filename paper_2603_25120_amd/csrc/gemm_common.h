@@ -27,6 +27,8 @@ struct GemmParams {
   uint32_t a_bytes, b_bytes;
   int accumulate;
   int tiles_m, tiles_n;
+  int kt_per_split;         // k-tiles handled by one workgroup row (gridDim.y splits of the K loop)
+  int64_t c_split_stride;   // elements between the partial outputs of consecutive splits
 };
 
 inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
@@ -39,6 +41,8 @@ inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
   p.b_bytes = (uint32_t)((g.b_layout ? g.n : g.k) * g.ldb * 2);
   p.tiles_m = (int)((g.m + bm - 1) / bm);
   p.tiles_n = (int)((g.n + bn - 1) / bn);
+  p.kt_per_split = (int)((g.k + BK - 1) / BK);
+  p.c_split_stride = 0;
   return p;
 }
 

@@ -19,8 +19,15 @@ struct GemmArgs {
   const void* bias;        // bf16 [N] or null
   const void* residual;    // bf16 [M,N] (ld = ldres) or null; bf16 C only
   int64_t ldres;
+  void* splitk_ws;         // optional fp32 scratch for split-K partial products (null: never split)
+  size_t splitk_ws_bytes;
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+// Scratch bytes launch_gemm wants for an fp32-output product of this shape (0: it will not split).
+size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k);
+// out[i] (+)= sum over s of partial[s][i], s ascending.
+hipError_t launch_splitk_reduce(const float* partial, float* out, int splits, int64_t n, int accumulate,
+                                hipStream_t s);
 
 // One entry per (segment, query tile) or (segment, key tile); built on the host, longest first.
 struct AttnTile {

@@ -131,6 +131,7 @@ mllm_status_t mllm_op_gemm(const void* a, const void* b, void* c, int64_t m, int
   g.a = a; g.b = b; g.c = c; g.m = m; g.n = n; g.k = k; g.lda = lda; g.ldb = ldb; g.ldc = n;
   g.a_layout = a_layout; g.b_layout = b_layout; g.out_fp32 = out_fp32; g.accumulate = accumulate;
   g.bias = bias; g.residual = residual; g.ldres = n;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
   OP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
   return MLLM_OK;
 }

@@ -177,7 +177,8 @@ struct Plan {
   Meta meta;
   // workspace offsets (after the metadata)
   size_t w_partial = 0;           // fp32 partial sums of norm / bias gradients
-  size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0;
+  size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0, w_split = 0;
+  size_t split_bytes = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
   double img_pairs = 0, seq_pairs = 0;  // sum over segments of visible (query, key) pairs
@@ -244,10 +245,11 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   if (st->proj >= 0) M.i2s = ws.take(sizeof(int32_t) * P.T_img);
   M.bytes = ws.off;
 
-  size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0;
+  size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0, split = 0;
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       proj = (size_t)P.T_img * L.d_out * 2;
+      split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_img));
       part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * L.d_out * 4);
       g = std::max(g, (size_t)P.T_img * L.d_model * 2);
       g = std::max(g, (size_t)P.T_seq * L.d_out * 2);
@@ -264,7 +266,14 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     e = std::max(e, T * nq * 2);
     delta = std::max(delta, T * L.n_q_heads * 4);
     g = std::max(g, T * d * 2);
+    const int64_t fup = L.kind == MLLM_LAYER_VIT ? f : 2 * f;
+    split = std::max(split, gemm_splitk_ws_bytes(f, d, T));
+    split = std::max(split, gemm_splitk_ws_bytes(d, fup, T));
+    split = std::max(split, gemm_splitk_ws_bytes(d, d, T));
+    split = std::max(split, gemm_splitk_ws_bytes(d, nq, T));
   }
+  P.split_bytes = split;
+  P.w_split = ws.take(split);
   P.w_partial = ws.take(part);
   P.w_a = ws.take(a);
   P.w_b = ws.take(bb);
@@ -338,8 +347,10 @@ mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, 
 
 hipError_t gemm(const void* a, int64_t lda, int a_layout, const void* b, int64_t ldb, int b_layout,
                 void* c, int64_t ldc, int64_t m, int64_t n, int64_t k, int out_fp32, int accumulate,
-                const void* bias, const void* res, int64_t ldres, hipStream_t s) {
+                const void* bias, const void* res, int64_t ldres, hipStream_t s,
+                void* splitk_ws = nullptr, size_t splitk_ws_bytes = 0) {
   GemmArgs g;
+  g.splitk_ws = splitk_ws; g.splitk_ws_bytes = splitk_ws_bytes;
   g.a = a; g.b = b; g.c = c; g.m = m; g.n = n; g.k = k; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.a_layout = a_layout; g.b_layout = b_layout; g.out_fp32 = out_fp32; g.accumulate = accumulate;
   g.bias = bias; g.residual = res; g.ldres = ldres;
@@ -355,8 +366,10 @@ hipError_t linear_dx(const void* dy, const void* w, void* dx, int64_t T, int64_t
   return gemm(dy, n, 0, w, n, 1, dx, k, T, k, n, 0, 0, nullptr, nullptr, 0, s);
 }
 // dW[k,n] (+)= X[T,k]^T.dY[T,n]
-hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t k, int64_t n, int accumulate, hipStream_t s) {
-  return gemm(x, k, 1, dy, n, 0, dw, n, k, n, T, 1, accumulate, nullptr, nullptr, 0, s);
+struct SplitWs { void* p; size_t bytes; };
+hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t k, int64_t n, int accumulate,
+                     hipStream_t s, SplitWs ws) {
+  return gemm(x, k, 1, dy, n, 0, dw, n, k, n, T, 1, accumulate, nullptr, nullptr, 0, s, ws.p, ws.bytes);
 }
 
 AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char* ws, const Plan& P, bool img) {
@@ -440,6 +453,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   const char* pre = saved + S.pre;
   const char* act = saved + S.act;
   float* partial = (float*)(ws + P.w_partial);
+  const SplitWs split{ws + P.w_split, P.split_bytes};
   char* wa = ws + P.w_a;      // d act            [T, f]
   char* wb = ws + P.w_b;      // d (gate|up)      [T, 2f]  (decoder)
   char* wc = ws + P.w_c;      // d n2 / d o / d n1 [T, d]
@@ -451,18 +465,18 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   const int64_t fup = vit ? f : 2 * f;
 
   // MLP
-  K_TRY(linear_dw(act, dy, dprm[iwdn], T, f, d, accumulate, s));
+  K_TRY(linear_dw(act, dy, dprm[iwdn], T, f, d, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(dy, d, (float*)dprm[ibdn], accumulate, partial, T, d, s));
   K_TRY(linear_dx(dy, prm[iwdn], wa, T, f, d, s));
   char* dpre = vit ? wa : wb;
   K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
-  K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s));
+  K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(dpre, fup, (float*)dprm[ibup], accumulate, partial, T, fup, s));
   K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x1, prm[ig2], (const float*)(saved + S.stats2), dy, wd,
                         (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, s));
   // attention block
-  K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s));
+  K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
   K_TRY(linear_dx(wd, prm[iwo], wc, T, d, d, s));
   AttnArgs a = attn_args(L, qkv, T, ws, P, vit);
@@ -477,7 +491,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   if (!vit)
     K_TRY(launch_rope(we, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 1, s));
-  K_TRY(linear_dw(n1, we, dprm[iwqkv], T, d, nq, accumulate, s));
+  K_TRY(linear_dw(n1, we, dprm[iwqkv], T, d, nq, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
   K_TRY(linear_dx(we, prm[iwqkv], wc, T, d, nq, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x, prm[ig1], (const float*)(saved + S.stats1), wd, dx,
@@ -662,7 +676,8 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
         K_TRY(launch_copy(cur, dx_seq, (size_t)P.T_seq * L.d_out * 2, s));
         K_TRY(launch_zero_rows(dx_seq, i2s, P.T_img, L.d_out, s));
       }
-      K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s));
+      K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s,
+                      SplitWs{ws + P.w_split, P.split_bytes}));
       K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, (float*)(ws + P.w_partial), P.T_img, L.d_out, s));
       void* out = (i == 0 && dx_img) ? dx_img : (void*)pp[flip];
       K_TRY(linear_dx(dproj, prm[0], out, P.T_img, L.d_model, L.d_out, s));
