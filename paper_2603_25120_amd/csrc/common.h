@@ -46,6 +46,25 @@ __device__ __forceinline__ s16x4 lds_read_tr4(const bf16_t* tile, int stride, in
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)p);
 }
 
+// GELU (act 0: exact erf form, 1: tanh form) and its derivative.
+__device__ __forceinline__ float gelu_f(int act, float z) {
+  if (act == 1) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    return 0.5f * z * (1.f + tanhf(u));
+  }
+  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_grad_f(int act, float z) {
+  if (act == 1) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    float t = tanhf(u);
+    return 0.5f * (1.f + t) +
+           0.5f * z * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * z * z);
+  }
+  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) +
+         z * expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

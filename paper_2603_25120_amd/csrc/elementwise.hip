@@ -90,68 +90,67 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
 // normalisation backward.  With xhat = (x - mean) * rstd and dxh = dy * gamma:
 //   LayerNorm: dx = (dxh - mean(dxh) - xhat * mean(dxh * xhat)) * rstd
 //   RMSNorm:   dx = (dxh - xhat * mean(dxh * xhat)) * rstd
-// plus the residual branch's gradient dres.  Each wavefront walks rows w, w + W, ... and keeps
-// its column sums of dy * xhat (and of dy) in registers; they go to partial[w][*].
+// plus the residual branch's gradient dres.  A workgroup of 256 threads owns one row at a time
+// (rows b, b + B, ...); a thread keeps NV 16-byte vectors of the row and its own column sums of
+// dy * xhat (and of dy) in registers; they go to partial[b][*] at the end.
 // ---------------------------------------------------------------------------------------------
 template <int KIND, int NV>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(
     const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
     float* __restrict__ partial, int64_t T, int d) {
-  const int lane = threadIdx.x & 63;
-  const int W = gridDim.x * ROWS_PER_BLOCK;
-  const int w = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  __shared__ float red[2][2][4];  // [row parity][which sum][wavefront]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int B = gridDim.x, b = blockIdx.x;
   const int nvec = d >> 3;
-  uint4 graw[NV];           // gamma, packed
-  float dg[NV][8], db[NV][8];
+  float g[NV][8], dg[NV][8], db[NV][8];
 #pragma unroll
   for (int j = 0; j < NV; j++) {
-    int c = lane + 64 * j;
-    graw[j] = c < nvec ? *reinterpret_cast<const uint4*>(gamma + 8 * c) : make_uint4(0, 0, 0, 0);
+    const int c = tid + 256 * j;
+    if (c < nvec) unpack8(*reinterpret_cast<const uint4*>(gamma + 8 * c), g[j]);
 #pragma unroll
-    for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; }
+    for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; if (c >= nvec) g[j][e] = 0.f; }
   }
-  for (int64_t row = w; row < T; row += W) {
+  int parity = 0;
+  for (int64_t row = b; row < T; row += B, parity ^= 1) {
     const float rstd = stats[row];
     const float mean = KIND == 0 ? stats[T + row] : 0.f;
-    uint4 xraw[NV], dyraw[NV];  // the row stays packed between the two passes
+    float xh[NV][8], dxh[NV][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; j++) {
-      int c = lane + 64 * j;
+      const int c = tid + 256 * j;
       if (c < nvec) {
-        xraw[j] = *reinterpret_cast<const uint4*>(x + row * d + 8 * c);
-        dyraw[j] = *reinterpret_cast<const uint4*>(dy + row * d + 8 * c);
-        float xv[8], dv[8], g[8];
-        unpack8(xraw[j], xv);
-        unpack8(dyraw[j], dv);
-        unpack8(graw[j], g);
+        float xv[8], dv[8];
+        unpack8(*reinterpret_cast<const uint4*>(x + row * d + 8 * c), xv);
+        unpack8(*reinterpret_cast<const uint4*>(dy + row * d + 8 * c), dv);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-          float xh = (xv[e] - mean) * rstd;
-          float dxh = dv[e] * g[e];
-          s1 += dxh;
-          s2 += dxh * xh;
-          dg[j][e] += dv[e] * xh;
+          xh[j][e] = (xv[e] - mean) * rstd;
+          dxh[j][e] = dv[e] * g[j][e];
+          s1 += dxh[j][e];
+          s2 += dxh[j][e] * xh[j][e];
+          dg[j][e] += dv[e] * xh[j][e];
           db[j][e] += dv[e];
         }
       }
     }
-    const float m2 = wave_sum(s2) / (float)d;
-    const float m1 = KIND == 0 ? wave_sum(s1) / (float)d : 0.f;
+    s2 = wave_sum(s2);
+    if (KIND == 0) s1 = wave_sum(s1);
+    if (lane == 0) { red[parity][0][wave] = s1; red[parity][1][wave] = s2; }
+    __syncthreads();  // one barrier per row: the two parities alternate, so a slot is rewritten
+                      // only after every wavefront has passed the barrier of the row in between
+    const float m2 = (red[parity][1][0] + red[parity][1][1] + red[parity][1][2] + red[parity][1][3]) / (float)d;
+    const float m1 = KIND == 0 ? (red[parity][0][0] + red[parity][0][1] + red[parity][0][2] + red[parity][0][3]) / (float)d : 0.f;
 #pragma unroll
     for (int j = 0; j < NV; j++) {
-      int c = lane + 64 * j;
+      const int c = tid + 256 * j;
       if (c < nvec) {
-        float xv[8], dv[8], g[8], o[8], r[8];
-        unpack8(xraw[j], xv);
-        unpack8(dyraw[j], dv);
-        unpack8(graw[j], g);
+        float o[8], r[8];
         if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * d + 8 * c), r);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-          float xh = (xv[e] - mean) * rstd;
-          o[e] = (dv[e] * g[e] - m1 - xh * m2) * rstd;
+          o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd;
           if (dres) o[e] += r[e];
         }
         *reinterpret_cast<uint4*>(dx + row * d + 8 * c) = pack8(o);
@@ -160,13 +159,13 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
   }
 #pragma unroll
   for (int j = 0; j < NV; j++) {
-    int c = lane + 64 * j;
+    const int c = tid + 256 * j;
     if (c < nvec) {
-      float* pg = partial + (int64_t)w * d + 8 * c;
+      float* pg = partial + (int64_t)b * d + 8 * c;
       *reinterpret_cast<float4*>(pg) = make_float4(dg[j][0], dg[j][1], dg[j][2], dg[j][3]);
       *reinterpret_cast<float4*>(pg + 4) = make_float4(dg[j][4], dg[j][5], dg[j][6], dg[j][7]);
       if (KIND == 0) {
-        float* pb = partial + (int64_t)(W + w) * d + 8 * c;
+        float* pb = partial + (int64_t)(B + b) * d + 8 * c;
         *reinterpret_cast<float4*>(pb) = make_float4(db[j][0], db[j][1], db[j][2], db[j][3]);
         *reinterpret_cast<float4*>(pb + 4) = make_float4(db[j][4], db[j][5], db[j][6], db[j][7]);
       }
@@ -250,24 +249,6 @@ __global__ void rope_kernel(bf16_t* __restrict__ qk, const int32_t* __restrict__
 // ---------------------------------------------------------------------------------------------
 // activations
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float gelu_f(int act, float z) {
-  if (act == 1) {
-    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    return 0.5f * z * (1.f + tanhf(u));
-  }
-  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
-}
-__device__ __forceinline__ float gelu_grad_f(int act, float z) {
-  if (act == 1) {
-    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    float t = tanhf(u);
-    return 0.5f * (1.f + t) +
-           0.5f * z * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * z * z);
-  }
-  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) +
-         z * expf(-0.5f * z * z) * 0.3989422804014327f;
-}
-
 __global__ void gelu_fwd_kernel(int act, const bf16_t* __restrict__ h, bf16_t* __restrict__ a, int64_t nvec) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= nvec) return;
@@ -407,10 +388,7 @@ hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const voi
 }
 
 int64_t norm_bwd_partial_rows(int64_t t) {
-  int64_t blocks = (t + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
-  if (blocks > 256) blocks = 256;
-  if (blocks < 1) blocks = 1;
-  return blocks * ROWS_PER_BLOCK;
+  return t < 1 ? 1 : (t > 1024 ? 1024 : t);
 }
 
 hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
@@ -420,13 +398,14 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
   if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
   const int64_t W = norm_bwd_partial_rows(t);
   ProfScope prof(PROF_ELEMENTWISE, (dres ? 8.0 : 6.0) * (double)t * (double)d, s);
-  dim3 grid((unsigned)(W / ROWS_PER_BLOCK)), block(256);
+  dim3 grid((unsigned)W), block(256);
 #define CALL(NV)                                                                                   \
   if (kind == 0) hipLaunchKernelGGL((norm_bwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d); \
   else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
-  MLLM_NV_DISPATCH(d / 8, CALL)
+  const int64_t nvec = d / 8;
+  if (nvec <= 256) { CALL(1) } else if (nvec <= 512) { CALL(2) } else { CALL(4) }
 #undef CALL
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
