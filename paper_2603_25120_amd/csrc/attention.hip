@@ -26,7 +26,19 @@ namespace {
 
 constexpr int BKV = 64;   // key rows staged per step (forward, dQ)
 constexpr int BQ = 64;    // query rows staged per step (dK/dV)
-constexpr int APAD = 8;
+
+// LDS tiles are [rows][HD] bf16 without padding; 16-byte chunk c of row r lives at chunk position
+// c ^ swz<HD>(r).  LDS serves 256 B per clock: a 16-byte read is processed 16 lanes at a time (16
+// consecutive rows, same logical chunk) and a transposing 8-byte read 32 lanes at a time (4
+// consecutive rows x 64 B).  The permutations below make both patterns conflict-free on the same
+// tile: HD = 128 (256-byte rows) maps the 16 rows to 16 different chunks and the 4 rows of a
+// transposing read to the 4 quarters of the row; HD = 64 (128-byte rows, two rows per 256-byte
+// window) does the same over row pairs.
+template <int HD>
+__device__ __forceinline__ int swz(int r) {
+  if constexpr (HD == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  else { const int t = (r >> 1) & 7; return ((t & 1) << 2) | (t >> 1); }
+}
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -61,27 +73,33 @@ struct RowTile {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; i++) {
       int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
-      *reinterpret_cast<uint4*>(lds + rr * (HD + APAD) + cc) = r[i];
+      *reinterpret_cast<uint4*>(lds + rr * HD + 8 * ((cc >> 3) ^ swz<HD>(rr))) = r[i];
     }
   }
 };
 
 // Natural-layout operand: row (r0 + lane%32), contraction values 16c + 8*(lane/32) .. +7.
-template <int STRIDE>
+template <int HD>
 __device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int r0, int c, int lane) {
   Frag8 f;
-  f.u = *reinterpret_cast<const uint4*>(tile + (r0 + (lane & 31)) * STRIDE + 16 * c + 8 * (lane >> 5));
+  const int r = r0 + (lane & 31);
+  f.u = *reinterpret_cast<const uint4*>(tile + r * HD + 8 * ((2 * c + (lane >> 5)) ^ swz<HD>(r)));
   return f.v;
 }
 // Transposed operand for the register-resident B operand built from a 32x32 accumulator:
 // output row (n0 + lane%32) of the tile's columns, contraction slots e = 0..7 standing for tile
-// rows k16 + 8*(e/4) + 4*(lane/32) + e%4.
-template <int STRIDE>
+// rows k16 + 8*(e/4) + 4*(lane/32) + e%4.  Each transposing read returns tile[k0 + e][n] for
+// e = 0..3 when lane i of a 16-lane group addresses tile[k0 + i/4][n0' + 4*(i%4)].
+template <int HD>
 __device__ __forceinline__ bf16x8 frag_cols_permuted(const bf16_t* tile, int k16, int n0, int lane) {
   Frag8 f;
-  const int h = lane >> 5, nn = n0 + 16 * ((lane >> 4) & 1);
-  f.h[0] = lds_read_tr4(tile, STRIDE, k16 + 4 * h, nn, lane & 15);
-  f.h[1] = lds_read_tr4(tile, STRIDE, k16 + 8 + 4 * h, nn, lane & 15);
+  const int h = lane >> 5, i16 = lane & 15;
+  const int n = n0 + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+  const int k = k16 + 4 * h + (i16 >> 2);
+  const bf16_t* p0 = tile + k * HD + 8 * ((n >> 3) ^ swz<HD>(k)) + (n & 7);
+  const bf16_t* p1 = tile + (k + 8) * HD + 8 * ((n >> 3) ^ swz<HD>(k + 8)) + (n & 7);
+  f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)p0);
+  f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)p1);
   return f.v;
 }
 // Accumulator values 8*cc .. 8*cc+7 of a 32x32 block as a bf16 B operand.
@@ -104,7 +122,7 @@ __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 *
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
-  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32, NB = BKV / 32;
+  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32, NB = BKV / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
   const AttnTile t = p.tiles[blockIdx.y];
@@ -153,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
     for (int c = 0; c < NC; c++)
 #pragma unroll
       for (int b = 0; b < NB; b++)
-        s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s[b], 0, 0, 0);
+        s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Ks, 32 * b, c, lane), qf[c], s[b], 0, 0, 0);
     // Only tiles that cross the segment end or the diagonal need the mask (wavefront-uniform).
     const bool need_mask = (kv0 + BKV > t.seg_len) || (t.causal && kv0 + BKV - 1 > wave_first_q);
     if (need_mask) {
@@ -199,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
 #pragma unroll
         for (int d = 0; d < ND; d++)
           oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<STRIDE>(Vs, 32 * b + 16 * cc, 32 * d, lane), pf, oacc[d], 0, 0, 0);
+              frag_cols_permuted<HD>(Vs, 32 * b + 16 * cc, 32 * d, lane), pf, oacc[d], 0, 0, 0);
       }
   }
   l += __shfl_xor(l, 32, 64);
@@ -249,7 +267,7 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
-  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
   const AttnTile t = p.tiles[blockIdx.y];
@@ -302,8 +320,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
       for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
       for (int c = 0; c < NC; c++) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Ks, 32 * b, c, lane), qf[c], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Vs, 32 * b, c, lane), dof[c], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Ks, 32 * b, c, lane), qf[c], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Vs, 32 * b, c, lane), dof[c], dp, 0, 0, 0);
       }
       const bool need_mask = (kv0 + 32 * b + 32 > t.seg_len) || (t.causal && kv0 + 32 * b + 31 > wave_first_q);
       if (need_mask) {
@@ -322,7 +340,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 #pragma unroll
         for (int d = 0; d < ND; d++)
           dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<STRIDE>(Ks, 32 * b + 16 * cc, 32 * d, lane), dsf, dqacc[d], 0, 0, 0);
+              frag_cols_permuted<HD>(Ks, 32 * b + 16 * cc, 32 * d, lane), dsf, dqacc[d], 0, 0, 0);
       }
     }
   }
@@ -345,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
-  constexpr int STRIDE = HD + APAD, NC = HD / 16, ND = HD / 32;
+  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * STRIDE];
   __shared__ float lse_s[BQ], delta_s[BQ];
@@ -399,8 +417,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
         for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<STRIDE>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
         }
         f32x16 pr;
         if (t.causal && q0 + 32 * b <= wave_first_k + 31) {   // block touches the diagonal
@@ -419,9 +437,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
 #pragma unroll
           for (int d = 0; d < ND; d++) {
             dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols_permuted<STRIDE>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
+                frag_cols_permuted<HD>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
             dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols_permuted<STRIDE>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
+                frag_cols_permuted<HD>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
           }
         }
       }
