@@ -1,0 +1,142 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+* ViT-L layer and 7B decoder layer: the whole layer, forward and backward, every output and every
+  gradient against the fp64 oracle (the oracle finishes these in seconds on the host cores).
+* 8B-GQA decoder layer at 32768 packed tokens: the GPU runs the full microbatch; the oracle runs
+  the shortest, the longest and one middle sample ALONE.  Rows of a sample do not depend on what
+  it is packed with (per-instance attention, row-wise linear maps: Model Profiler, "Throughput
+  Profiling"), so y and dx rows of those samples must match the per-sample oracle.
+* The kernels at the full shapes on sampled outputs: GEMM entries (all three layouts of the 8B
+  layer, including the weight-gradient contraction over 32768 tokens) against fp64 dot products,
+  attention rows of sampled (segment, head) pairs against the oracle run on that pair only.
+
+Tolerances as everywhere: normalised max error 2e-2 on outputs, 3e-2 on gradients; fp32 GEMM
+outputs 2e-3.
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import stage_oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from tests.gpu_util import GpuStage, compare, dev_bf16, host_f64, nmax_err, oracle_run, scratch  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_25120_amd import binding
+    binding.lib()
+    return binding
+
+
+def test_vit_l_layer_full(B):
+    wl = W.workload_vit_l(100)                       # 16 samples x 1..4 images of 576 tokens
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+def test_dec7b_layer_full(B):
+    wl = W.workload_dec7b(200)                       # 8192 packed tokens, d = 4096, MHA, SwiGLU 11008
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+def test_dec8b_layer_sampled_samples(B):
+    wl = W.workload_dec8b(300)                       # 32768 packed tokens, GQA 32/8, SwiGLU 14336
+    st = GpuStage(B, wl.layers)
+    try:
+        y, _, dx_seq, _ = st.run(wl)
+        y, dx_seq = host_f64(y), host_f64(dx_seq)
+    finally:
+        st.close()
+    cu = wl.batch.seq.cu_seqlens
+    lens = np.diff(cu)
+    order = np.argsort(lens)
+    picks = sorted({int(order[0]), int(order[len(order) // 2]), int(order[-1])})
+    for s in picks:
+        a, b = int(cu[s]), int(cu[s + 1])
+        one = W.Workload("one", wl.layers, W.Batch(None, W.make_pack([b - a], W.MASK_CAUSAL), None, []),
+                         wl.params, None, wl.x_seq[a:b], wl.dy[a:b])
+        y_ref, caches = O.stage_fwd(one.layers, one.params, one.batch, None, one.x_seq)
+        _, dx_ref, _ = O.stage_bwd(one.layers, one.params, one.batch, caches, one.dy.astype(np.float64))
+        assert nmax_err(y[a:b], y_ref) <= 2e-2, ("y", s, b - a)
+        assert nmax_err(dx_seq[a:b], dx_ref) <= 3e-2, ("dx", s, b - a)
+
+
+@pytest.mark.parametrize("what", ["fwd_up", "dx_down", "dw_up", "dw_qkv"])
+def test_gemm_full_shapes_sampled(B, what):
+    T, d, f, nq = 32768, 4096, 14336, 6144
+    rng = np.random.default_rng(7)
+    if what == "fwd_up":       # [T,d] . [d,2f]
+        m, n, k, al, bl, f32 = T, 2 * f, d, 0, 0, 0
+    elif what == "dx_down":    # dY[T,d] . W_d[f,d]^T
+        m, n, k, al, bl, f32 = T, f, d, 0, 1, 0
+    elif what == "dw_up":      # X[T,d]^T . dY[T,2f], fp32
+        m, n, k, al, bl, f32 = d, 2 * f, T, 1, 0, 1
+    else:                      # X[T,d]^T . dY[T,nq], fp32
+        m, n, k, al, bl, f32 = d, nq, T, 1, 0, 1
+    a = W.draw_tensor(71, *( (k, m) if al else (m, k) ))
+    b = W.draw_tensor(72, *( (n, k) if bl else (k, n) ))
+    c = torch.empty(m, n, dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    B.mllm_op_gemm(dev_bf16(a), dev_bf16(b), c, m, n, k, al, bl, f32)
+    rows = np.unique(np.concatenate([rng.integers(0, m, 24), [0, m - 1, 255, 256]]))
+    cols = np.unique(np.concatenate([rng.integers(0, n, 48), [0, n - 1, 255, 256]]))
+    got = host_f64(c[torch.as_tensor(rows, device="cuda")][:, torch.as_tensor(cols, device="cuda")])
+    A = (a[:, rows].T if al else a[rows]).astype(np.float64)          # [rows, k]
+    Bm = (b[cols].T if bl else b[:, cols]).astype(np.float64)         # [k, cols]
+    ref = A @ Bm
+    assert nmax_err(got, ref) < (2e-3 if f32 else 1e-2)
+
+
+def test_attention_full_shape_sampled(B):
+    """The 8B-GQA attention at 32768 packed tokens; oracle on sampled (segment, head) pairs."""
+    hq, hkv, hd = 32, 8, 128
+    pack = W.workload_dec8b(300, with_data=False).batch.seq
+    T = pack.total_tokens
+    nq = (hq + 2 * hkv) * hd
+    qkv = W.draw_tensor(81, T, nq)
+    do = W.draw_tensor(82, T, hq * hd)
+    dq_ = dev_bf16(qkv)
+    o = torch.zeros(T, hq * hd, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    delta = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    dqkv = torch.zeros(T, nq, dtype=torch.bfloat16, device="cuda")
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    qp = dq_.data_ptr()
+    kp, vp = qp + hq * hd * 2, qp + (hq + hkv) * hd * 2
+    gp = dqkv.data_ptr()
+    B.mllm_op_attn_fwd(qp, kp, vp, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    B.mllm_op_attn_bwd(qp, kp, vp, o, lse, dev_bf16(do), gp, gp + hq * hd * 2, gp + (hq + hkv) * hd * 2, delta,
+                       pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    o_h, g_h, lse_h = host_f64(o), host_f64(dqkv), host_f64(lse)
+    cu = pack.cu_seqlens
+    lens = np.diff(cu)
+    order = np.argsort(lens)
+    for s, g in ((int(order[-1]), 3), (int(order[len(order) // 2]), 0), (int(order[0]), 7)):
+        a, b = int(cu[s]), int(cu[s + 1])
+        heads = list(range(4 * g, 4 * g + 4))       # the whole GQA group, so that dk / dv can be checked
+        q = qkv[a:b, :hq * hd].reshape(b - a, hq, hd)[:, heads].astype(np.float64)
+        k = qkv[a:b, hq * hd:(hq + hkv) * hd].reshape(b - a, hkv, hd)[:, g:g + 1].astype(np.float64)
+        v = qkv[a:b, (hq + hkv) * hd:].reshape(b - a, hkv, hd)[:, g:g + 1].astype(np.float64)
+        d_o = do[a:b].reshape(b - a, hq, hd)[:, heads].astype(np.float64)
+        one = W.make_pack([b - a], W.MASK_CAUSAL)
+        o_ref, lse_ref = O.attention_fwd(q, k, v, one.cu_seqlens, one.mask_kind, return_lse=True)
+        dq_ref, dk_ref, dv_ref = O.attention_bwd(d_o, q, k, v, one.cu_seqlens, one.mask_kind)
+        got_o = o_h[a:b].reshape(b - a, hq, hd)[:, heads]
+        assert nmax_err(got_o, o_ref) < 2e-2, (s, g)
+        assert np.max(np.abs(lse_h[heads, a:b] - lse_ref)) < 2e-2
+        got_dq = g_h[a:b, :hq * hd].reshape(b - a, hq, hd)[:, heads]
+        got_dk = g_h[a:b, hq * hd:(hq + hkv) * hd].reshape(b - a, hkv, hd)[:, g:g + 1]
+        got_dv = g_h[a:b, (hq + hkv) * hd:].reshape(b - a, hkv, hd)[:, g:g + 1]
+        assert nmax_err(got_dq, dq_ref) < 3e-2, (s, g)
+        assert nmax_err(got_dk, dk_ref) < 3e-2, (s, g)
+        assert nmax_err(got_dv, dv_ref) < 3e-2, (s, g)
