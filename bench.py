@@ -183,6 +183,34 @@ def cpu_baseline(sample_tokens: int = 6912):
                       % (batch.seq.total_tokens, batch.img.total_tokens, t_vit, t_dec)}
 
 
+def sweep(args):
+    """Stage time versus microbatch shape: the 16 seeded full-stage microbatches (4 token budgets x
+    2 length mixes x 2 seeds) and, for one 8B-GQA decoder layer at 32768 tokens, equal-length
+    partitions from 256 x 128 to 1 x 32768.  Prints a markdown table (not the one-line JSON)."""
+    print("| workload | tokens | image tokens | samples | longest | sum L^2 / 1e6 | ms/step | tokens/s | % MFMA peak |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    cases = []
+    for seed, budget, mix in W.full_stage_sweep():
+        wl = W.workload_full_stage(seed, budget, mix, with_data=False)
+        cases.append(("full stage, mix %s, seed %d" % (mix, seed), wl))
+    for nseg in (256, 64, 16, 4, 1):
+        batch = W.equal_partition_batch(32768, nseg)
+        cases.append(("8B-GQA layer, %d x %d" % (nseg, 32768 // nseg),
+                      W.make_workload("eq", [W.dec8b_layer()], batch, 1, with_data=False)))
+    for seed in (300, 301, 302, 303):
+        cases.append(("8B-GQA layer, long-tailed mix, seed %d" % seed, W.workload_dec8b(seed, with_data=False)))
+    for name, wl in cases:
+        lin_f, attn_f = stage_fwd_flops(wl.layers, wl.batch)
+        r = run_gpu(args, wl)
+        ms = r["gpu_ms"] / args.steps
+        seq = wl.batch.seq
+        lens = np.diff(seq.cu_seqlens).astype(np.float64)
+        print("| %s | %d | %d | %d | %d | %.1f | %.2f | %.0f | %.1f |" % (
+            name, seq.total_tokens, wl.batch.img.total_tokens if wl.batch.img is not None else 0, seq.n_segments,
+            seq.max_seqlen, float(np.sum(lens * lens)) / 1e6, ms, seq.total_tokens / (ms * 1e-3),
+            100 * 3.0 * (lin_f + attn_f) / (ms * 1e-3) / MFMA_BF16_PEAK), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -190,10 +218,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="full_stage_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="print stage time versus microbatch shape instead")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU's stage; run with --gpus 1 "
                          "(no collectives or sharding are part of it)")
+    if args.sweep:
+        return sweep(args)
     wl, desc = build_workload(args.workload)
     lin_f, attn_f = stage_fwd_flops(wl.layers, wl.batch)
     step_flops = 3.0 * (lin_f + attn_f)
@@ -202,15 +233,21 @@ def main():
     ms_per_step = r["gpu_ms"] / args.steps
     tok_s = tokens / (ms_per_step * 1e-3)
     prof = r["prof"]
-    # dominant kernel = the GEMM class with the largest share of time
+    # dominant kernel = the 256x256-tile GEMM instantiation with the largest share of time
     gemm_cls = max(("gemm_fwd", "gemm_dx", "gemm_dw"), key=lambda c: prof[c][1])
     n, ms, work = prof[gemm_cls]
     achieved = work / (ms * 1e-3) if ms > 0 else 0.0
-    all_gemm_ms = sum(prof[c][1] for c in ("gemm_fwd", "gemm_dx", "gemm_dw"))
-    all_gemm_work = sum(prof[c][2] for c in ("gemm_fwd", "gemm_dx", "gemm_dw"))
-    kernel_names = {"gemm_fwd": "gemm_kernel<A [M,K], B [K,N], bf16 out> (Y = X.W)",
-                    "gemm_dx": "gemm_kernel<A [M,K], B [N,K], bf16 out> (dX = dY.W^T)",
-                    "gemm_dw": "gemm_kernel<A [K,M], B [K,N], fp32 out> (dW = X^T.dY)"}
+    gemm_all = ("gemm_fwd", "gemm_dx", "gemm_dw", "gemm_small")
+    all_gemm_ms = sum(prof[c][1] for c in gemm_all)
+    all_gemm_work = sum(prof[c][2] for c in gemm_all)
+    kernel_names = {"gemm_fwd": "gemm_kernel<256, 256, 128, 64, false, true, false> (Y = X.W)",
+                    "gemm_dx": "gemm_kernel<256, 256, 128, 64, false, false, false> (dX = dY.W^T)",
+                    "gemm_dw": "gemm_kernel<256, 256, 128, 64, true, true, true> (dW = X^T.dY, fp32)"}
+    # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+    # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
+    traffic_table = {"gemm_fwd": (767764 * 2.0 + 247320) * 1024, "gemm_dx": (752706 * 2.0 + 164530) * 1024,
+                     "gemm_dw": (1295630 * 2.0 + 122802) * 1024}
+    traffic = traffic_table[gemm_cls] if args.workload == "full_stage_32k" else None
     out = {
         "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -228,7 +265,7 @@ def main():
         "host_wall_ms_per_step": r["wall_ms"] / args.steps,
         "roofline": {"bound": "mfma", "kernel": kernel_names[gemm_cls], "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
-                     "traffic": None, "launches": n, "avg_launch_ms": ms / n if n else None,
+                     "traffic": traffic, "traffic_unit": "bytes per launch (L2 <-> fabric)", "launches": n, "avg_launch_ms": ms / n if n else None,
                      "all_gemm_tflops": all_gemm_work / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else None},
         "breakdown_ms_per_step": {c: prof[c][1] / args.steps for c in prof},
         "breakdown_rate": {

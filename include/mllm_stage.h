@@ -243,9 +243,10 @@ mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* p
  * mllm_profile_begin(max_records) creates the events and starts recording every kernel launch of
  * the calling process' later mllm_* calls, bracketing each with HIP events on its launch stream.
  * mllm_profile_end stops recording, waits for the recorded events, and sums per class
- * (0 GEMM Y=X.W, 1 GEMM dX, 2 GEMM dW, 3 attention forward, 4 attention backward, 5 the
- * norm / rotary / activation / reduction / copy kernels): launches[6], milliseconds[6] and
- * work[6] (algorithmic FLOPs for classes 0-4, algorithmic bytes for class 5) are host arrays.
+ * (0 / 1 / 2: the 256x256-tile GEMM kernel in its Y=X.W / dX / dW layouts, 3 attention forward,
+ * 4 attention backward, 5 the norm / rotary / activation / reduction / copy kernels, 6 the
+ * 128x128-tile GEMM kernel in any layout): launches[7], milliseconds[7] and work[7] (algorithmic
+ * FLOPs for the GEMM and attention classes, algorithmic bytes for class 5) are host arrays.
  * Not thread-safe; records beyond max_records are dropped and counted in *dropped.
  * ------------------------------------------------------------------------------------------ */
 mllm_status_t mllm_profile_begin(int32_t max_records);

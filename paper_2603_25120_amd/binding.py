@@ -27,7 +27,7 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
            "mllm_profile_end"]
 
-PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise"]
+PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise", "gemm_small"]
 
 
 class MllmError(RuntimeError):

@@ -248,24 +248,31 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   // operands are addressed through 32-bit buffer offsets
   if ((g.a_layout ? g.k : g.m) * g.lda * 2 >= (int64_t)OOB || (g.b_layout ? g.n : g.k) * g.ldb * 2 >= (int64_t)OOB)
     return hipErrorInvalidValue;
-  const int cls = g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
-  ProfScope prof(cls, 2.0 * (double)g.m * (double)g.n * (double)g.k, s);
+  const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
+  const SplitPlan sp = plan_split(g.m, g.n, g.k);
+  const bool split = sp.splits > 1 && g.out_fp32 && !g.bias && g.ldc == g.n && g.splitk_ws &&
+                     g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4;
+  const bool large = big_tiles >= 200 || (split && sp.big_tile);
+  // timing classes: the three layouts of the 256x256 kernel, and the 128x128 kernel
+  const int cls = !large ? PROF_GEMM_SMALL : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
+  const double flops = 2.0 * (double)g.m * (double)g.n * (double)g.k;
   // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep
   // 128x128 tiles so that more workgroups exist.
-  const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
-  if (big_tiles >= 200) return launch_tile<256, 256, 128, 64>(g, s);
-  const SplitPlan sp = plan_split(g.m, g.n, g.k);
-  if (sp.splits > 1 && g.out_fp32 && !g.bias && g.ldc == g.n && g.splitk_ws &&
-      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4) {
-    GemmArgs part = g;
-    part.c = g.splitk_ws;
-    part.accumulate = 0;
-    hipError_t e = sp.big_tile ? launch_tile<256, 256, 128, 64>(part, s, sp.splits)
-                               : launch_tile<128, 128, 64, 64>(part, s, sp.splits);
-    if (e != hipSuccess) return e;
-    return launch_splitk_reduce((const float*)g.splitk_ws, (float*)g.c, sp.splits, g.m * g.n, g.accumulate, s);
+  if (!split) {
+    ProfScope prof(cls, flops, s);
+    return big_tiles >= 200 ? launch_tile<256, 256, 128, 64>(g, s) : launch_tile<128, 128, 64, 64>(g, s);
   }
-  return launch_tile<128, 128, 64, 64>(g, s);
+  GemmArgs part = g;
+  part.c = g.splitk_ws;
+  part.accumulate = 0;
+  hipError_t e;
+  {
+    ProfScope prof(cls, flops, s);
+    e = sp.big_tile ? launch_tile<256, 256, 128, 64>(part, s, sp.splits)
+                    : launch_tile<128, 128, 64, 64>(part, s, sp.splits);
+  }
+  if (e != hipSuccess) return e;
+  return launch_splitk_reduce((const float*)g.splitk_ws, (float*)g.c, sp.splits, g.m * g.n, g.accumulate, s);
 }
 
 }  // namespace mllm
