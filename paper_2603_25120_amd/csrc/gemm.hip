@@ -33,7 +33,7 @@ constexpr int PAD_T = 16;
 // Global -> register -> LDS staging of one operand tile through buffer loads: an out-of-range
 // offset returns zeros, so ragged edges need no branches.  K_ROWS: the tile's rows run along the
 // contraction index (operand stored [K, rows]); otherwise its columns do (stored [rows, K]).
-template <int ROWS, int COLS, int PADC, int NT, bool K_ROWS>
+template <int ROWS, int COLS, int PADC, int NT, bool K_ROWS, int BKT>
 struct TileLoader {
   static constexpr int VEC_PER_ROW = COLS / 8;
   static constexpr int NVEC = ROWS * COLS / 8;
@@ -46,7 +46,7 @@ struct TileLoader {
   uint32_t kstep;             // bytes per BK step
 
   __device__ __forceinline__ void init(int64_t ld, int64_t fixed0, int64_t nfixed, int64_t K, int tid) {
-    kstep = (uint32_t)(K_ROWS ? BK * ld * 2 : BK * 2);
+    kstep = (uint32_t)(K_ROWS ? BKT * ld * 2 : BKT * 2);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; i++) {
       const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
@@ -60,7 +60,7 @@ struct TileLoader {
   __device__ __forceinline__ void store(bf16_t* lds, int tid) const { store_part<0, PER_THREAD>(lds, tid); }
   template <int I0, int I1>
   __device__ __forceinline__ void load_part(__amdgpu_buffer_rsrc_t rsrc, int kt) {
-    const int k0 = kt * BK;
+    const int k0 = kt * BKT;
 #pragma unroll
     for (int i = I0; i < I1; i++) {
       const uint32_t o = (off[i] != OOB && k0 < klim[i]) ? off[i] + (uint32_t)kt * kstep : OOB;
@@ -92,13 +92,13 @@ __device__ __forceinline__ bf16x8 fetch_frag(const bf16_t* tile, int r0, int kk,
   return f.v;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool OUT_F32>
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool OUT_F32, int BKT>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmParams p) {
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = 64 * NWM * NWN;
   constexpr int TM = WM / 32, TN = WN / 32;
   // A tile: [BM][BK] (contraction contiguous) or [BK][BM] (as stored, transposing reads)
-  constexpr int A_ROWS = A_T ? BK : BM, A_COLS = A_T ? BM : BK, A_PAD = A_T ? PAD_T : PAD_K;
-  constexpr int B_ROWS = B_T ? BK : BN, B_COLS = B_T ? BN : BK, B_PAD = B_T ? PAD_T : PAD_K;
+  constexpr int A_ROWS = A_T ? BKT : BM, A_COLS = A_T ? BM : BKT, A_PAD = A_T ? PAD_T : PAD_K;
+  constexpr int B_ROWS = B_T ? BKT : BN, B_COLS = B_T ? BN : BKT, B_PAD = B_T ? PAD_T : PAD_K;
   constexpr int A_STRIDE = A_COLS + A_PAD, B_STRIDE = B_COLS + B_PAD;
   constexpr int A_SIZE = A_ROWS * A_STRIDE, B_SIZE = B_ROWS * B_STRIDE;
   // two LDS stages: tile kt+1 is written while tile kt is being multiplied
@@ -111,8 +111,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   tile_of_block(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-  TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T> la;
-  TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T> lb;
+  TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T, BKT> la;
+  TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T, BKT> lb;
   la.init(p.lda, m0, p.M, p.K, tid);
   lb.init(p.ldb, n0, p.N, p.K, tid);
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes), rb = make_rsrc(p.b, p.b_bytes);
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
 
   // Split-K: workgroup row blockIdx.y owns k-tiles [kt0, kt0 + nk) and writes its own partial C.
   const int kt0 = blockIdx.y * p.kt_per_split;
-  const int nk = min(p.kt_per_split, (int)((p.K + BK - 1) / BK) - kt0);
+  const int nk = min(p.kt_per_split, (int)((p.K + BKT - 1) / BKT) - kt0);
   gload(kt0);
   la.store(As, tid);
   lb.store(Bs, tid);
@@ -148,9 +148,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
     for (int j = 0; j < TN; j++) bfr[buf][j] = fetch_frag<B_T, B_STRIDE>(bt, wn * WN + 32 * j, kk, lane);
   };
   fetch(0, As, Bs, 0);
-  constexpr int STEPS = BK / 16;
-  constexpr int A_PER = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T>::PER_THREAD / STEPS;
-  constexpr int B_PER = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T>::PER_THREAD / STEPS;
+  constexpr int STEPS = BKT / 16;
+  constexpr int A_PER = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T, BKT>::PER_THREAD / STEPS;
+  constexpr int B_PER = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T, BKT>::PER_THREAD / STEPS;
   static_assert(A_PER >= 1 && B_PER >= 1, "each k-step must move at least one vector per operand");
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
@@ -179,9 +179,11 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
     };
     step(std::integral_constant<int, 0>{});
     step(std::integral_constant<int, 1>{});
-    step(std::integral_constant<int, 2>{});
-    step(std::integral_constant<int, 3>{});
-    static_assert(STEPS == 4, "four k-steps per tile");
+    if constexpr (STEPS == 4) {
+      step(std::integral_constant<int, 2>{});
+      step(std::integral_constant<int, 3>{});
+    }
+    static_assert(STEPS == 2 || STEPS == 4, "two or four k-steps per tile");
     __syncthreads();
     fetch(0, an, bn, 0);
   }
@@ -193,9 +195,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BKT = 64>
 hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   GemmParams p = make_gemm_params(g, BM, BN);
+  p.kt_per_split = (int)((g.k + BKT - 1) / BKT);
   if (splits > 1) {
     p.kt_per_split = (p.kt_per_split + splits - 1) / splits;
     p.c_split_stride = g.m * g.n;
@@ -204,7 +207,7 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
 #define MLLM_GEMM_CASE(AT, BT, F32)                                                      \
   if (at == AT && bt == BT && (g.out_fp32 != 0) == F32) {                                \
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AT, BT, F32>), grid, block, 0, s, p); \
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AT, BT, F32, BKT>), grid, block, 0, s, p); \
     return hipGetLastError();                                                            \
   }
   MLLM_GEMM_CASE(false, true, false)   // Y = X.W
