@@ -149,27 +149,45 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   };
   fetch(0, As, Bs, 0);
   constexpr int STEPS = BKT / 16;
-  constexpr int A_PER = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T, BKT>::PER_THREAD / STEPS;
-  constexpr int B_PER = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T, BKT>::PER_THREAD / STEPS;
-  static_assert(A_PER >= 1 && B_PER >= 1, "each k-step must move at least one vector per operand");
+  using LA = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T, BKT>;
+  using LB = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T, BKT>;
+  // EARLY (weight-gradient layout, where it measured faster): the tile is moved in the first half
+  // of the k-steps and the barrier sits before the last step's MFMAs, so the next tile's first
+  // fragments are fetched under them.  Otherwise the move is spread over all k-steps and the
+  // barrier closes the iteration.
+  constexpr bool EARLY = A_T && STEPS == 4;
+  constexpr int MOVE_STEPS = EARLY ? STEPS / 2 : STEPS;
+  constexpr int A_PER = LA::PER_THREAD / MOVE_STEPS, B_PER = LB::PER_THREAD / MOVE_STEPS;
+  static_assert(A_PER * MOVE_STEPS == LA::PER_THREAD && B_PER * MOVE_STEPS == LB::PER_THREAD && A_PER >= 1 && B_PER >= 1,
+                "the moving k-steps must split the tile evenly");
+  static_assert(STEPS == 2 || STEPS == 4, "two or four k-steps per tile");
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
     bf16_t* an = As + (cur ^ 1) * A_SIZE;
     bf16_t* bn = Bs + (cur ^ 1) * B_SIZE;
     const bf16_t* at = As + cur * A_SIZE;
     const bf16_t* bt = Bs + cur * B_SIZE;
-    // Branch-free body.  Each of the four k-steps first moves a quarter of tile kt+1 from the
-    // staging registers into the other LDS stage and at once refills those registers with the
-    // same quarter of tile kt+2 (so every prefetch has a whole iteration to land), then fetches
-    // the next step's fragments and issues its 16 MFMAs.  Past the end the prefetch offsets are
-    // out of range (zeros, no traffic) and the stored stage is never read.
+    // Branch-free body.  The moving k-steps each put a share of tile kt+1 from the staging
+    // registers into the other LDS stage and at once refill those registers with the same share
+    // of tile kt+2 (every prefetch has a whole iteration to land); every step but the last
+    // fetches the next step's fragments before issuing its MFMAs.  With EARLY the barrier comes
+    // before the last step's MFMAs: by then every fragment of this stage is in registers and
+    // every store to the other stage has been issued.  Past the end the prefetch offsets are out
+    // of range (zeros, no traffic) and the stored stage is never read.
     auto step = [&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value;
-      la.template store_part<kk * A_PER, (kk + 1) * A_PER>(an, tid);
-      lb.template store_part<kk * B_PER, (kk + 1) * B_PER>(bn, tid);
-      la.template load_part<kk * A_PER, (kk + 1) * A_PER>(ra, kt0 + kt + 2);
-      lb.template load_part<kk * B_PER, (kk + 1) * B_PER>(rb, kt0 + kt + 2);
-      if constexpr (kk + 1 < STEPS) fetch((kk + 1) & 1, at, bt, kk + 1);
+      if constexpr (kk < MOVE_STEPS) {
+        la.template store_part<kk * A_PER, (kk + 1) * A_PER>(an, tid);
+        lb.template store_part<kk * B_PER, (kk + 1) * B_PER>(bn, tid);
+        la.template load_part<kk * A_PER, (kk + 1) * A_PER>(ra, kt0 + kt + 2);
+        lb.template load_part<kk * B_PER, (kk + 1) * B_PER>(rb, kt0 + kt + 2);
+      }
+      if constexpr (kk + 1 < STEPS) {
+        fetch((kk + 1) & 1, at, bt, kk + 1);
+      } else if constexpr (EARLY) {
+        __syncthreads();
+        fetch(0, an, bn, 0);
+      }
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -183,9 +201,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
       step(std::integral_constant<int, 2>{});
       step(std::integral_constant<int, 3>{});
     }
-    static_assert(STEPS == 2 || STEPS == 4, "two or four k-steps per tile");
-    __syncthreads();
-    fetch(0, an, bn, 0);
+    if constexpr (!EARLY) {
+      __syncthreads();
+      fetch(0, an, bn, 0);
+    }
   }
 
   constexpr int ST_STRIDE = WN + 4;  // floats
