@@ -173,18 +173,19 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
   }
 }
 
-// out[c] (+)= sum_p partial[p][c].  A workgroup owns 64 columns: 16 row slices x 16 float4 column
-// groups; slice s adds rows s, s+16, ... in order, then the 16 slice sums are added in order:
+// out[c] (+)= sum_p partial[p][c].  A workgroup owns 16 columns: 64 row slices x 4 float4 column
+// groups; slice s adds rows s, s+64, ... in order, then the 64 slice sums are added in order:
 // a fixed association, so the result is bitwise reproducible.
+constexpr int RED_COLS = 16, RED_SLICES = 64;
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
                                                               float* __restrict__ out, int P,
                                                               int64_t n, int accumulate) {
-  __shared__ float4 part[16][16];
-  const int cg = threadIdx.x & 15, slice = threadIdx.x >> 4;
-  const int64_t c = ((int64_t)blockIdx.x * 16 + cg) * 4;
+  __shared__ float4 part[RED_SLICES][RED_COLS / 4];
+  const int cg = threadIdx.x & 3, slice = threadIdx.x >> 2;
+  const int64_t c = ((int64_t)blockIdx.x * (RED_COLS / 4) + cg) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (c < n) {
-    for (int p = slice; p < P; p += 16) {
+    for (int p = slice; p < P; p += RED_SLICES) {
       const float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * n + c);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   __syncthreads();
   if (slice == 0 && c < n) {
     float4 t = part[0][cg];
-    for (int i = 1; i < 16; i++) {
+    for (int i = 1; i < RED_SLICES; i++) {
       const float4 v = part[i][cg];
       t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
     }
@@ -409,10 +410,10 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
 #undef CALL
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, 64)), dim3(256), 0, s, partial,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS)), dim3(256), 0, s, partial,
                      dgamma, (int)W, d, accumulate);
   if (kind == 0)
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, 64)), dim3(256), 0, s,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS)), dim3(256), 0, s,
                        partial + W * d, dbeta, (int)W, d, accumulate);
   return hipGetLastError();
 }
@@ -470,7 +471,7 @@ hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate,
   ProfScope prof(PROF_ELEMENTWISE, 2.0 * (double)t * (double)n, s);
   hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks_for(n, 512), (unsigned)P), dim3(64), 0, s,
                      (const bf16_t*)x, ldx, partial, t, n);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(n, 64)), dim3(256), 0, s, partial,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(n, RED_COLS)), dim3(256), 0, s, partial,
                      out, (int)P, n, accumulate);
   return hipGetLastError();
 }
