@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // loops over the query heads of the group and the query tiles that can see its keys.
 // ---------------------------------------------------------------------------------------------
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(AttnParams p) {
   constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * STRIDE];
