@@ -180,3 +180,18 @@ def test_workload_recipes():
     assert r[2] == 1.0 and r[3] == np.float32(1.015625)         # ties go to the even mantissa
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
     assert len(W.full_stage_sweep()) == 16
+
+
+def test_product_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing in the package may import, read or run it."""
+    pkg = os.path.join(ROOT, "paper_2603_25120_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+    assert "oracle" not in open(os.path.join(ROOT, "workloads.py")).read().replace("oracle's tests", "")
+    # and the oracle never imports the product
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2603_25120_amd" not in open(os.path.join(ROOT, "oracle", f)).read()

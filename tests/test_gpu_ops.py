@@ -244,3 +244,35 @@ def test_colsum(B, t, n):
     B.mllm_op_colsum(xd, out, 1, part, t, n)
     ref = x.astype(np.float64).sum(axis=0) + 2.0
     assert np.max(np.abs(host_f64(out) - ref)) < 1e-3 * max(1.0, math.sqrt(t))
+
+
+def test_attention_longest_possible_sample(B):
+    """One causal sample of 13312 tokens (16 images + 4096 text tokens, the cap of the long-tailed
+    mix), one GQA group: many key tiles per query tile, ragged last tile (13312 = 104 * 128)."""
+    hd, hq, hkv, L = 128, 4, 1, 13312 - 57
+    pack = W.make_pack([L], 1)
+    nq = (hq + 2 * hkv) * hd
+    qkv = W.draw_tensor(91, L, nq)
+    do = W.draw_tensor(92, L, hq * hd)
+    q = qkv[:, :hq * hd].reshape(L, hq, hd).astype(np.float64)
+    k = qkv[:, hq * hd:(hq + hkv) * hd].reshape(L, hkv, hd).astype(np.float64)
+    v = qkv[:, (hq + hkv) * hd:].reshape(L, hkv, hd).astype(np.float64)
+    o_ref = O.attention_fwd(q, k, v, pack.cu_seqlens, pack.mask_kind)
+    dq_ref, dk_ref, dv_ref = O.attention_bwd(do.reshape(L, hq, hd).astype(np.float64), q, k, v,
+                                             pack.cu_seqlens, pack.mask_kind)
+    d = dev_bf16(qkv)
+    o = torch.zeros(L, hq * hd, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(hq, L, dtype=torch.float32, device="cuda")
+    delta = torch.zeros(hq, L, dtype=torch.float32, device="cuda")
+    g = torch.zeros(L, nq, dtype=torch.bfloat16, device="cuda")
+    ws = scratch(B.mllm_op_attn_workspace_bytes(1, L))
+    qp = d.data_ptr()
+    B.mllm_op_attn_fwd(qp, qp + hq * hd * 2, qp + (hq + hkv) * hd * 2, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    gp = g.data_ptr()
+    B.mllm_op_attn_bwd(qp, qp + hq * hd * 2, qp + (hq + hkv) * hd * 2, o, lse, dev_bf16(do), gp, gp + hq * hd * 2,
+                       gp + (hq + hkv) * hd * 2, delta, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    gh = host_f64(g)
+    assert nmax_err(host_f64(o), o_ref.reshape(L, -1)) < 2e-2
+    assert nmax_err(gh[:, :hq * hd], dq_ref.reshape(L, -1)) < 3e-2
+    assert nmax_err(gh[:, hq * hd:(hq + hkv) * hd], dk_ref.reshape(L, -1)) < 3e-2
+    assert nmax_err(gh[:, (hq + hkv) * hd:], dv_ref.reshape(L, -1)) < 3e-2

@@ -150,3 +150,39 @@ def test_error_statuses_touch_nothing(B):
         assert float((y.float() - 7.0).abs().max()) == 0.0
     finally:
         st.close()
+
+
+def test_empty_microbatch(B):
+    """No tokens at all: every call succeeds, launches nothing that reads data, and an overwrite
+    backward leaves zero parameter gradients."""
+    layers = [W.vit_layer(192, 3, 64, 768), W.projector_layer(192, 256), W.decoder_layer(256, 4, 4, 64, 1024, 10000.0)]
+    batch = W.Batch(W.make_pack([], W.MASK_BIDIR), W.make_pack([0, 0], W.MASK_CAUSAL), np.zeros(0, np.int32), [])
+    h = B.mllm_stage_create(layers)
+    try:
+        infos = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
+        params = [dev_bf16(p) for p in W.draw_params(layers, 3)]
+        dparams = [torch.full((r, c), 5.0, dtype=torch.float32, device="cuda") for _, _, r, c in infos]
+        sb, wb = B.mllm_stage_sizes(h, batch)
+        saved, ws = scratch(sb), scratch(wb)
+        one = empty_bf16(1, 256)
+        B.mllm_stage_fwd(h, batch, params, one, one, one, saved, ws)
+        B.mllm_stage_bwd(h, batch, params, one, saved, one, one, dparams, 0, ws)
+        torch.cuda.synchronize()
+        for g in dparams:
+            assert float(g.abs().max()) == 0.0
+    finally:
+        B.mllm_stage_destroy(h)
+
+
+def test_decoder_layer_rerun_is_bitwise_identical(B):
+    layer = W.decoder_layer(1024, 8, 2, 128, 1792, 500000.0)
+    batch = W.batch_from_samples(W.draw_samples_mix8b(31, budget=3000), with_images=False)
+    wl = W.make_workload("det", [layer], batch, 31)
+    st = GpuStage(B, [layer])
+    try:
+        a, b = st.run(wl), st.run(wl)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[2], b[2])
+        for ga, gb in zip(a[3], b[3]):
+            assert torch.equal(ga, gb)
+    finally:
+        st.close()
