@@ -251,7 +251,19 @@ struct SplitPlan { int splits; bool big_tile; };
 SplitPlan plan_split(int64_t m, int64_t n, int64_t k) {
   const int64_t t256 = ((m + 255) / 256) * ((n + 255) / 256), t128 = ((m + 127) / 128) * ((n + 127) / 128);
   const int64_t nk = (k + BK - 1) / BK;
-  if (t256 >= 200) return {1, true};
+  if (t256 >= 200) {
+    // Enough tiles to fill the chip, but a last partial round of workgroups can leave most CUs
+    // idle (1.5 rounds cost 2).  Cutting K in S parts makes S times as many, S times shorter
+    // workgroups: pick the S <= 4 with the fewest rounds per unit of work, charging the
+    // reduction pass about a twentieth of a round.
+    int best = 1;
+    double best_cost = (double)((t256 + 255) / 256);
+    for (int sp = 2; sp <= 4 && nk / sp >= 64; sp++) {
+      const double cost = (double)((t256 * sp + 255) / 256) / sp + 0.05 * sp;
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = sp; }
+    }
+    return {best, true};
+  }
   const bool big = t256 >= 24;
   int64_t want = big ? (320 + t256 - 1) / t256 : (512 + t128 - 1) / t128;
   want = std::min<int64_t>(want, 16);
