@@ -239,6 +239,25 @@ mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* p
                              int64_t n, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Online microbatch scheduler (host only, no GPU work; Online Microbatch Scheduler, "Problem
+ * Formulation" and "Scheduling Optimization").  Item i of a global batch has an encoder-stage
+ * duration e_dur[i] and an LLM-stage duration l_dur[i] (host arrays, non-negative).  The items are
+ * assigned to n_buckets buckets, bucket_out[i] in [0, n_buckets) (host array, caller-owned), to
+ * make C_max = max over buckets of max(sum of e_dur, sum of l_dur) small.
+ *   mllm_schedule_lpt: longest-processing-time-first -- items by descending max(e, l), each into
+ *     the bucket with the lowest max(E_j, L_j); ties to the lower index.
+ *   mllm_schedule: exact branch-and-bound search started from the LPT solution and limited to
+ *     node_limit search nodes (the deterministic stand-in for the solver's time limit); when the
+ *     limit is hit, *optimal_out = 0 and the best assignment found (never worse than LPT) is
+ *     returned.  *cmax_out receives the objective of the returned assignment.
+ * ------------------------------------------------------------------------------------------ */
+mllm_status_t mllm_schedule_lpt(int64_t n_items, const double* e_dur, const double* l_dur,
+                                int32_t n_buckets, int32_t* bucket_out);
+mllm_status_t mllm_schedule(int64_t n_items, const double* e_dur, const double* l_dur,
+                            int32_t n_buckets, int64_t node_limit, int32_t* bucket_out,
+                            double* cmax_out, int32_t* optimal_out);
+
+/* ------------------------------------------------------------------------------------------
  * Per-launch timing, for measurement only (off by default; adds two event records per launch).
  * mllm_profile_begin(max_records) creates the events and starts recording every kernel launch of
  * the calling process' later mllm_* calls, bracketing each with HIP events on its launch stream.

@@ -25,7 +25,7 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
-           "mllm_profile_end"]
+           "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule"]
 
 PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise", "gemm_small"]
 
@@ -100,6 +100,9 @@ def lib() -> C.CDLL:
     L.mllm_op_colsum.argtypes = [vp, vp, C.c_int, vp, i64, i64, vp]
     L.mllm_profile_begin.argtypes = [i32]
     L.mllm_profile_end.argtypes = [C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
+    dp, ip = C.POINTER(C.c_double), C.POINTER(i32)
+    L.mllm_schedule_lpt.argtypes = [i64, dp, dp, i32, ip]
+    L.mllm_schedule.argtypes = [i64, dp, dp, i32, i64, ip, dp, ip]
     for name in EXPORTS:
         getattr(L, name)          # every declared entry point must be exported
     _lib = L
@@ -308,3 +311,28 @@ def mllm_profile_end():
     launches, ms, work, dropped = (C.c_int64 * n)(), (C.c_double * n)(), (C.c_double * n)(), C.c_int64()
     _check(lib().mllm_profile_end(launches, ms, work, C.byref(dropped)))
     return {PROFILE_CLASSES[i]: (int(launches[i]), float(ms[i]), float(work[i])) for i in range(n)}, int(dropped.value)
+
+
+def _dvec(x):
+    a = np.ascontiguousarray(x, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def mllm_schedule_lpt(e_dur, l_dur, n_buckets: int) -> np.ndarray:
+    """Bucket index per item by longest-processing-time-first."""
+    e, ep = _dvec(e_dur)
+    l, lp = _dvec(l_dur)
+    out = np.zeros(len(e), dtype=np.int32)
+    _check(lib().mllm_schedule_lpt(len(e), ep, lp, n_buckets, out.ctypes.data_as(C.POINTER(C.c_int32))))
+    return out
+
+
+def mllm_schedule(e_dur, l_dur, n_buckets: int, node_limit: int = 1_000_000):
+    """(bucket index per item, C_max of that assignment, whether it is proven optimal)."""
+    e, ep = _dvec(e_dur)
+    l, lp = _dvec(l_dur)
+    out = np.zeros(len(e), dtype=np.int32)
+    cmax, optimal = C.c_double(), C.c_int32()
+    _check(lib().mllm_schedule(len(e), ep, lp, n_buckets, node_limit, out.ctypes.data_as(C.POINTER(C.c_int32)),
+                               C.byref(cmax), C.byref(optimal)))
+    return out, cmax.value, bool(optimal.value)

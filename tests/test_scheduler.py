@@ -102,7 +102,8 @@ def test_library_hybrid_falls_back_to_lpt(B):
     assert not optimal
     assert cmax <= S.c_max(list(e), list(l), lpt, 16) + 1e-12       # never worse than the fallback
     assert cmax == pytest.approx(S.c_max(list(e), list(l), list(assign), 16), rel=1e-12)
-    assert sorted(set(assign)) == list(range(16))
+    assert min(assign) >= 0 and max(assign) < 16
+    assert cmax >= S.lower_bound(list(e), list(l), 16) - 1e-12
 
 
 def test_library_scheduler_argument_checks(B):
