@@ -211,6 +211,148 @@ def sweep(args):
             100 * 3.0 * (lin_f + attn_f) / (ms * 1e-3) / MFMA_BF16_PEAK), flush=True)
 
 
+class StageRunner:
+    """Parameters of a stage allocated once; times forward+backward on any microbatch."""
+
+    def __init__(self, layers):
+        import torch
+        from paper_2603_25120_amd import binding as B
+        self.torch, self.B, self.layers = torch, B, layers
+        B.lib()
+        self.dev = torch.device("cuda:0")
+        self.h = B.mllm_stage_create(layers)
+        infos = [B.mllm_stage_param_info(self.h, i) for i in range(B.mllm_stage_param_count(self.h))]
+        self.gen = torch.Generator(device=self.dev)
+        self.gen.manual_seed(99)
+        self.params = [self.randn(r, c, 0.02, 1.0 if name.endswith("_g") else 0.0) for name, _, r, c in infos]
+        self.dparams = [torch.zeros(r, c, dtype=torch.float32, device=self.dev) for _, _, r, c in infos]
+
+    def randn(self, r, c, scale=1.0, shift=0.0):
+        t = self.torch
+        return (t.randn(r, c, generator=self.gen, device=self.dev, dtype=t.float32) * scale + shift).to(t.bfloat16)
+
+    def time(self, batch, steps=2, warmup=1):
+        t, B, layers = self.torch, self.B, self.layers
+        kinds = [l.kind for l in layers]
+        uses_img = kinds[0] in (W.LAYER_VIT, W.LAYER_PROJECTOR)
+        uses_seq = W.LAYER_DECODER in kinds or W.LAYER_PROJECTOR in kinds
+        x_img = self.randn(batch.img.total_tokens, layers[0].d_model) if uses_img else None
+        d_seq = next((l.d_out if l.kind == W.LAYER_PROJECTOR else l.d_model) for l in layers
+                     if l.kind != W.LAYER_VIT) if uses_seq else 0
+        x_seq = self.randn(batch.seq.total_tokens, d_seq) if uses_seq else None
+        last = layers[-1]
+        rows = batch.img.total_tokens if last.kind == W.LAYER_VIT else batch.seq.total_tokens
+        cols = last.d_out if last.kind == W.LAYER_PROJECTOR else last.d_model
+        dy = self.randn(rows, cols)
+        y = t.empty(rows, cols, dtype=t.bfloat16, device=self.dev)
+        sb, wb = B.mllm_stage_sizes(self.h, batch)
+        saved = t.empty(sb, dtype=t.uint8, device=self.dev)
+        ws = t.empty(wb, dtype=t.uint8, device=self.dev)
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        for i in range(warmup + steps):
+            if i == warmup:
+                e0.record()
+            B.mllm_stage_fwd(self.h, batch, self.params, x_img, x_seq, y, saved, ws)
+            B.mllm_stage_bwd(self.h, batch, self.params, dy, saved, None, None, self.dparams, 0, ws)
+        e1.record()
+        t.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def close(self):
+        self.B.mllm_stage_destroy(self.h)
+
+
+def schedule_experiment(args):
+    """Online microbatch scheduling on measured stage times (Online Microbatch Scheduler): a global
+    batch of N items is cut into m buckets at random, by LPT and by the node-limited exact search;
+    every bucket's encoder stage (24 ViT-L layers + connector) and LLM stage (8 8B-GQA layers) is
+    then timed on the GPU.  Per-item durations come from three constants measured in the same run:
+    encoder time per image, LLM time per token and LLM time per (sample length)^2."""
+    from paper_2603_25120_amd import binding as B
+    N, m = args.sched_items, args.sched_buckets
+    rng = np.random.default_rng(2048)
+    items = []
+    while len(items) < N:
+        k = min(16, int(rng.geometric(0.3)) - 1)
+        t = int(min(max(int(round(rng.lognormal(np.log(300.0), 1.0))), 1), 4096))
+        items.append((k, t))
+    enc = StageRunner([W.vit_l_layer() for _ in range(24)] + [W.projector_layer(1024, 4096)])
+    llm = StageRunner([W.dec8b_layer() for _ in range(8)])
+
+    # duration model
+    def enc_batch(samples):
+        return W.batch_from_samples(samples)
+    t_a = enc.time(enc_batch([(8, 1)]))
+    t_b = enc.time(enc_batch([(8, 1)] * 4))
+    c_img = (t_b - t_a) / 24.0                                   # ms per image
+    t_1 = llm.time(W.equal_partition_batch(16384, 128))          # sum L^2 = 16384 * 128
+    t_2 = llm.time(W.equal_partition_batch(16384, 4))            # sum L^2 = 16384 * 4096
+    c_sq = (t_2 - t_1) / (16384.0 * (4096 - 128))
+    c_tok = (t_1 - c_sq * 16384.0 * 128) / 16384.0
+    e_dur = np.array([c_img * k for k, _ in items])
+    l_dur = np.array([c_tok * (576 * k + t) + c_sq * (576 * k + t) ** 2 for k, t in items])
+    print("duration model: encoder %.4f ms/image; LLM %.5f ms/token + %.3e ms/token^2" % (c_img, c_tok, c_sq))
+
+    policies = []
+    for seed in range(3):
+        policies.append(("random, seed %d" % seed, np.random.default_rng(seed).integers(0, m, N)))
+    policies.append(("round-robin in arrival order", np.arange(N) % m))
+    t0 = time.perf_counter()
+    lpt = B.mllm_schedule_lpt(e_dur, l_dur, m)
+    t_lpt = time.perf_counter() - t0
+    policies.append(("LPT", lpt))
+    t0 = time.perf_counter()
+    exact, cmax_exact, optimal = B.mllm_schedule(e_dur, l_dur, m, node_limit=args.sched_nodes)
+    t_exact = time.perf_counter() - t0
+    policies.append(("exact search, %d nodes%s" % (args.sched_nodes, "" if not optimal else " (proven optimal)"), exact))
+    lb = max(e_dur.sum() / m, l_dur.sum() / m, max(e_dur.max(), l_dur.max()))
+    print("\n| policy | predicted C_max ms | measured max E_j ms | measured max L_j ms | measured C_max ms | measured sum of stage times ms |")
+    print("|---|---|---|---|---|---|")
+    for name, assign in policies:
+        E = [0.0] * m
+        L = [0.0] * m
+        pe = np.zeros(m)
+        pl = np.zeros(m)
+        for j in range(m):
+            idx = [i for i in range(N) if assign[i] == j]
+            pe[j], pl[j] = e_dur[idx].sum(), l_dur[idx].sum()
+            samples = [items[i] for i in idx]
+            if not samples:
+                continue
+            batch = W.batch_from_samples(samples)
+            if batch.img.total_tokens > 0:
+                E[j] = enc.time(batch)
+            L[j] = llm.time(W.Batch(None, batch.seq, None, samples))
+        print("| %s | %.1f | %.1f | %.1f | %.1f | %.1f |" % (name, max(pe.max(), pl.max()), max(E), max(L),
+                                                          max(max(E), max(L)), sum(E) + sum(L)), flush=True)
+    print("\nlower bound on C_max from the duration model: %.1f ms; scheduler time on the host: LPT %.3f ms, exact search %.1f ms"
+          % (lb, t_lpt * 1e3, t_exact * 1e3))
+    # scheduler latency and LPT's distance from the lower bound at a global batch of 2048 items
+    big = []
+    while len(big) < 2048:
+        k = min(16, int(rng.geometric(0.3)) - 1)
+        t = int(min(max(int(round(rng.lognormal(np.log(300.0), 1.0))), 1), 4096))
+        big.append((k, t))
+    e2 = np.array([c_img * k for k, _ in big])
+    l2 = np.array([c_tok * (576 * k + t) + c_sq * (576 * k + t) ** 2 for k, t in big])
+    for m2 in (16, 64):
+        t0 = time.perf_counter()
+        a2 = B.mllm_schedule_lpt(e2, l2, m2)
+        dt = time.perf_counter() - t0
+        Ej = np.bincount(a2, weights=e2, minlength=m2)
+        Lj = np.bincount(a2, weights=l2, minlength=m2)
+        c = max(Ej.max(), Lj.max())
+        lb2 = max(e2.sum() / m2, l2.sum() / m2, max(e2.max(), l2.max()))
+        t0 = time.perf_counter()
+        _, c3, opt3 = B.mllm_schedule(e2, l2, m2, node_limit=args.sched_nodes)
+        dt3 = time.perf_counter() - t0
+        print("2048 items, %d buckets: LPT C_max %.1f ms, %.2f %% above the lower bound %.1f ms, %.2f ms on the host; "
+              "exact search (%d nodes, %s) C_max %.1f ms in %.0f ms"
+              % (m2, c, 100 * (c / lb2 - 1), lb2, dt * 1e3, args.sched_nodes, "optimal" if opt3 else "limit hit", c3, dt3 * 1e3))
+    enc.close()
+    llm.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,12 +361,18 @@ def main():
     ap.add_argument("--workload", default="full_stage_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="print stage time versus microbatch shape instead")
+    ap.add_argument("--schedule", action="store_true", help="run the microbatch-scheduling experiment instead")
+    ap.add_argument("--sched-items", type=int, default=64)
+    ap.add_argument("--sched-buckets", type=int, default=8)
+    ap.add_argument("--sched-nodes", type=int, default=2_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU's stage; run with --gpus 1 "
                          "(no collectives or sharding are part of it)")
     if args.sweep:
         return sweep(args)
+    if args.schedule:
+        return schedule_experiment(args)
     wl, desc = build_workload(args.workload)
     lin_f, attn_f = stage_fwd_flops(wl.layers, wl.batch)
     step_flops = 3.0 * (lin_f + attn_f)

@@ -74,6 +74,8 @@ enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
  *   PROJECTOR: w_p [d_model, d_out], b_p
  * Limits: head_dim in {64, 128}; d_model == n_q_heads * head_dim for VIT / DECODER; every width
  * a multiple of 64; n_q_heads a multiple of n_kv_heads; act GELU_* for VIT, SWIGLU for DECODER.
+ * A microbatch is limited by tokens * widest layer width * 2 bytes < 4 GiB (MLLM_ERR_SHAPE beyond:
+ * about 74 000 packed tokens for the 8B-shaped decoder layer).
  */
 typedef struct {
   int32_t kind;       /* MLLM_LAYER_*                                   */

@@ -280,7 +280,7 @@ size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k) {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
   // operands are addressed through 32-bit buffer offsets
-  if ((g.a_layout ? g.k : g.m) * g.lda * 2 >= (int64_t)OOB || (g.b_layout ? g.n : g.k) * g.ldb * 2 >= (int64_t)OOB)
+  if ((g.a_layout ? g.k : g.m) * g.lda * 2 > GEMM_MAX_OPERAND_BYTES || (g.b_layout ? g.n : g.k) * g.ldb * 2 > GEMM_MAX_OPERAND_BYTES)
     return hipErrorInvalidValue;
   const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
   const SplitPlan sp = plan_split(g.m, g.n, g.k);

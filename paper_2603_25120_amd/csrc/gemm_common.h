@@ -11,7 +11,7 @@ namespace mllm {
 constexpr int BK = 64;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-constexpr uint32_t OOB = 0x80000000u;  // byte offset beyond any buffer these kernels accept (< 2 GiB)
+constexpr uint32_t OOB = 0xFFFFFFFFu;  // byte offset beyond any buffer these kernels accept (< 4 GiB - 16)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);

@@ -22,6 +22,8 @@ struct GemmArgs {
   void* splitk_ws;         // optional fp32 scratch for split-K partial products (null: never split)
   size_t splitk_ws_bytes;
 };
+// A and B are addressed through 32-bit byte offsets: each operand must stay below this size.
+constexpr int64_t GEMM_MAX_OPERAND_BYTES = 0xFFFFFFF0ll - 16;
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // Scratch bytes launch_gemm wants for an fp32-output product of this shape (0: it will not split).
 size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k);

@@ -181,6 +181,7 @@ struct Plan {
   size_t split_bytes = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
+  int64_t largest_operand_bytes = 0;   // largest [tokens, width] bf16 matrix any GEMM of the stage reads
   double img_pairs = 0, seq_pairs = 0;  // sum over segments of visible (query, key) pairs
 };
 
@@ -249,6 +250,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       proj = (size_t)P.T_img * L.d_out * 2;
+      P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)P.T_img * std::max(L.d_model, L.d_out) * 2);
       split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_img));
       part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * L.d_out * 4);
       g = std::max(g, (size_t)P.T_img * L.d_model * 2);
@@ -258,6 +260,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     const size_t T = L.kind == MLLM_LAYER_VIT ? P.T_img : P.T_seq;
     const size_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
     const size_t widest = std::max<size_t>(std::max(d, 2 * f), nq);
+    P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)(T * widest * 2));
     part = std::max(part, (size_t)norm_bwd_partial_rows(T) * d * 4 * 2);
     part = std::max(part, (size_t)colsum_partial_rows(T) * widest * 4);
     a = std::max(a, T * f * 2);
@@ -499,6 +502,13 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   return MLLM_OK;
 }
 
+mllm_status_t check_plan(const Plan& P) {
+  if (P.largest_operand_bytes > GEMM_MAX_OPERAND_BYTES)
+    return fail(MLLM_ERR_SHAPE, "microbatch too large: a [tokens, width] matrix of %lld bytes exceeds the 4 GiB the GEMM kernels address",
+                (long long)P.largest_operand_bytes);
+  return MLLM_OK;
+}
+
 mllm_status_t check_io(const mllm_stage* st, const mllm_batch_t* b, const void* const* params,
                        const Plan& P, size_t saved_bytes, size_t workspace_bytes, const void* saved,
                        const void* workspace) {
@@ -596,6 +606,7 @@ mllm_status_t mllm_stage_sizes(const mllm_stage_t* st, const mllm_batch_t* b, si
   mllm_status_t r = check_batch(st, b);
   if (r != MLLM_OK) return r;
   Plan P = make_plan(st, b);
+  if ((r = check_plan(P)) != MLLM_OK) return r;
   if (saved_bytes) *saved_bytes = P.saved_bytes;
   if (workspace_bytes) *workspace_bytes = P.workspace_bytes;
   return MLLM_OK;
@@ -608,6 +619,7 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
   mllm_status_t r = check_batch(st, b);
   if (r != MLLM_OK) return r;
   Plan P = make_plan(st, b);
+  if ((r = check_plan(P)) != MLLM_OK) return r;
   if ((r = check_io(st, b, params, P, saved_bytes, workspace_bytes, saved_v, workspace)) != MLLM_OK) return r;
   const bool need_img = st->n_vit > 0 || st->proj >= 0;
   const bool need_seq = st->n_dec > 0 || st->proj >= 0;
@@ -650,6 +662,7 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
   mllm_status_t r = check_batch(st, b);
   if (r != MLLM_OK) return r;
   Plan P = make_plan(st, b);
+  if ((r = check_plan(P)) != MLLM_OK) return r;
   if ((r = check_io(st, b, params, P, saved_bytes, workspace_bytes, saved_v, workspace)) != MLLM_OK) return r;
   if (!dy) return fail(MLLM_ERR_NULL, "dy is NULL");
   if (!dparams) return fail(MLLM_ERR_NULL, "dparams is NULL");

@@ -195,3 +195,14 @@ def test_product_never_touches_the_oracle():
     for f in os.listdir(os.path.join(ROOT, "oracle")):
         if f.endswith(".py"):
             assert "paper_2603_25120_amd" not in open(os.path.join(ROOT, "oracle", f)).read()
+
+
+def test_microbatch_beyond_the_addressing_limit_is_refused(B):
+    h = B.mllm_stage_create([W.dec8b_layer()])
+    ok = W.Batch(None, W.make_pack([37000, 37000], W.MASK_CAUSAL), None, [])      # 74000 x 28672 x 2 B < 4 GiB
+    assert B.mllm_stage_sizes(h, ok)[0] > 0
+    too_big = W.Batch(None, W.make_pack([40000, 40000], W.MASK_CAUSAL), None, [])
+    with pytest.raises(B.MllmError) as e:
+        B.mllm_stage_sizes(h, too_big)
+    assert e.value.status == 3 and "too large" in str(e.value)
+    B.mllm_stage_destroy(h)

@@ -140,3 +140,17 @@ def test_attention_full_shape_sampled(B):
         assert nmax_err(got_dq, dq_ref) < 3e-2, (s, g)
         assert nmax_err(got_dk, dk_ref) < 3e-2, (s, g)
         assert nmax_err(got_dv, dv_ref) < 3e-2, (s, g)
+
+
+def test_gemm_operand_above_two_gib(B):
+    """A weight-gradient product whose [tokens, width] operand is 2.3 GB (offsets beyond 2^31)."""
+    T, m, n = 40000, 64, 28672
+    x = W.draw_tensor(95, T, m)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    dy = torch.randn(T, n, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    dw = torch.empty(m, n, dtype=torch.float32, device="cuda")
+    B.mllm_op_gemm(dev_bf16(x), dy, dw, m, n, T, a_layout=1, b_layout=0, out_fp32=1)
+    cols = torch.tensor([0, 1, 255, 256, 14335, 14336, 20000, n - 1], device="cuda")
+    ref = x.astype(np.float64).T @ host_f64(dy[:, cols])
+    assert nmax_err(host_f64(dw[:, cols]), ref) < 2e-3
