@@ -32,29 +32,9 @@ MFMA_BF16_PEAK = 2.5e15   # dense, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
 
 
-# ---------------------------------------------------------------------------------------------
-# model FLOPs: 2mnk per GEMM, backward = 2x forward, causal attention at half the square,
-# no credit for recomputation
-# ---------------------------------------------------------------------------------------------
-def visible_pairs(pack) -> float:
-    lens = np.diff(pack.cu_seqlens).astype(np.float64)
-    w = np.where(pack.mask_kind == W.MASK_CAUSAL, 0.5, 1.0)
-    return float(np.sum(w * lens * lens))
-
-
 def stage_fwd_flops(layers, batch):
-    lin = attn = 0.0
-    for L in layers:
-        if L.kind == W.LAYER_PROJECTOR:
-            lin += 2.0 * batch.img.total_tokens * L.d_model * L.d_out
-            continue
-        pack = batch.img if L.kind == W.LAYER_VIT else batch.seq
-        T = pack.total_tokens
-        nqkv = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim
-        fup = L.d_ff if L.kind == W.LAYER_VIT else 2 * L.d_ff
-        lin += 2.0 * T * L.d_model * (nqkv + L.d_model + fup) + 2.0 * T * L.d_ff * L.d_model
-        attn += 4.0 * visible_pairs(pack) * L.n_q_heads * L.head_dim
-    return lin, attn
+    from paper_2603_25120_amd.profiler import stage_fwd_flops as f
+    return f(layers, batch)
 
 
 def build_workload(name: str):
@@ -211,57 +191,6 @@ def sweep(args):
             100 * 3.0 * (lin_f + attn_f) / (ms * 1e-3) / MFMA_BF16_PEAK), flush=True)
 
 
-class StageRunner:
-    """Parameters of a stage allocated once; times forward+backward on any microbatch."""
-
-    def __init__(self, layers):
-        import torch
-        from paper_2603_25120_amd import binding as B
-        self.torch, self.B, self.layers = torch, B, layers
-        B.lib()
-        self.dev = torch.device("cuda:0")
-        self.h = B.mllm_stage_create(layers)
-        infos = [B.mllm_stage_param_info(self.h, i) for i in range(B.mllm_stage_param_count(self.h))]
-        self.gen = torch.Generator(device=self.dev)
-        self.gen.manual_seed(99)
-        self.params = [self.randn(r, c, 0.02, 1.0 if name.endswith("_g") else 0.0) for name, _, r, c in infos]
-        self.dparams = [torch.zeros(r, c, dtype=torch.float32, device=self.dev) for _, _, r, c in infos]
-
-    def randn(self, r, c, scale=1.0, shift=0.0):
-        t = self.torch
-        return (t.randn(r, c, generator=self.gen, device=self.dev, dtype=t.float32) * scale + shift).to(t.bfloat16)
-
-    def time(self, batch, steps=2, warmup=1):
-        t, B, layers = self.torch, self.B, self.layers
-        kinds = [l.kind for l in layers]
-        uses_img = kinds[0] in (W.LAYER_VIT, W.LAYER_PROJECTOR)
-        uses_seq = W.LAYER_DECODER in kinds or W.LAYER_PROJECTOR in kinds
-        x_img = self.randn(batch.img.total_tokens, layers[0].d_model) if uses_img else None
-        d_seq = next((l.d_out if l.kind == W.LAYER_PROJECTOR else l.d_model) for l in layers
-                     if l.kind != W.LAYER_VIT) if uses_seq else 0
-        x_seq = self.randn(batch.seq.total_tokens, d_seq) if uses_seq else None
-        last = layers[-1]
-        rows = batch.img.total_tokens if last.kind == W.LAYER_VIT else batch.seq.total_tokens
-        cols = last.d_out if last.kind == W.LAYER_PROJECTOR else last.d_model
-        dy = self.randn(rows, cols)
-        y = t.empty(rows, cols, dtype=t.bfloat16, device=self.dev)
-        sb, wb = B.mllm_stage_sizes(self.h, batch)
-        saved = t.empty(sb, dtype=t.uint8, device=self.dev)
-        ws = t.empty(wb, dtype=t.uint8, device=self.dev)
-        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
-        for i in range(warmup + steps):
-            if i == warmup:
-                e0.record()
-            B.mllm_stage_fwd(self.h, batch, self.params, x_img, x_seq, y, saved, ws)
-            B.mllm_stage_bwd(self.h, batch, self.params, dy, saved, None, None, self.dparams, 0, ws)
-        e1.record()
-        t.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
-
-    def close(self):
-        self.B.mllm_stage_destroy(self.h)
-
-
 def schedule_experiment(args):
     """Online microbatch scheduling on measured stage times (Online Microbatch Scheduler): a global
     batch of N items is cut into m buckets at random, by LPT and by the node-limited exact search;
@@ -269,6 +198,7 @@ def schedule_experiment(args):
     then timed on the GPU.  Per-item durations come from three constants measured in the same run:
     encoder time per image, LLM time per token and LLM time per (sample length)^2."""
     from paper_2603_25120_amd import binding as B
+    from paper_2603_25120_amd.profiler import StageRunner
     N, m = args.sched_items, args.sched_buckets
     rng = np.random.default_rng(2048)
     items = []
@@ -353,6 +283,126 @@ def schedule_experiment(args):
     llm.close()
 
 
+def draw_items(rng, n):
+    """Items of the long-tailed mix: (images, text tokens)."""
+    items = []
+    while len(items) < n:
+        k = min(16, int(rng.geometric(0.3)) - 1)
+        t = int(min(max(int(round(rng.lognormal(np.log(300.0), 1.0))), 1), 4096))
+        items.append((k, t))
+    return items
+
+
+def plan_experiment(args):
+    """Model Profiler + Data Profiler + Algorithm 1 on this GPU's measurements.
+
+    1. Throughput profiling: the encoder stage (24 ViT-L layers + connector) over the number of
+       images, the LLM stage (8 8B-GQA layers) over the length of one sample with attention and
+       linear operations separated.
+    2. Held-out check: stage times of the 16 seeded full-stage microbatches predicted from the
+       curves (the per-item rule of the paper, and a variant that reads the linear curve at the
+       packed length) against the measured times.
+    3. Memory tables from the library's size queries at 2 and 4 layers; Algorithm 1 on a 24-layer
+       encoder + 32-layer LLM for several cluster sizes (TP fixed at 1: the only degree one GPU can
+       profile), with its search time."""
+    from paper_2603_25120_amd import binding as B
+    from paper_2603_25120_amd import profiler as MP
+    enc_layers = [W.vit_l_layer() for _ in range(24)] + [W.projector_layer(1024, 4096)]
+    llm_layers = [W.dec8b_layer() for _ in range(8)]
+    enc, llm = MP.StageRunner(enc_layers), MP.StageRunner(llm_layers)
+    b_grid = [1, 2, 4, 8, 16, 32, 56]
+    s_grid = [128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768]
+    bx, e_thr, e_ms = MP.profile_encoder(enc, b_grid)
+    sx, lin_thr, attn_thr, l_ms, l_attn_ms, l_attn_packed_ms = MP.profile_llm(llm, s_grid)
+    print("## Throughput profiling (forward + backward, model FLOPs)\n")
+    print("| images | encoder stage ms | E_thr TFLOP/s |\n|---|---|---|")
+    for b, ms, thr in zip(b_grid, e_ms, e_thr):
+        print("| %d | %.2f | %.0f |" % (b, ms, thr / 1e12))
+    print("\n| sample length | LLM stage ms, one sample | of it attention ms | L_lin_thr TFLOP/s | attention ms, 16384 tokens of such samples | L_attn_thr TFLOP/s |\n|---|---|---|---|---|---|")
+    for sl, ms, ma, a, mp, c in zip(s_grid, l_ms, l_attn_ms, lin_thr, l_attn_packed_ms, attn_thr):
+        print("| %d | %.2f | %.2f | %.0f | %.2f | %.0f |" % (sl, ms, ma, a / 1e12, mp, c / 1e12), flush=True)
+
+    # held-out microbatches
+    print("\n## Held-out check on the 16 seeded full-stage microbatches\n")
+    print("| microbatch | tokens | items | E measured ms | E predicted ms | L measured ms | L per-item rule ms | L packed-length rule ms |")
+    print("|---|---|---|---|---|---|---|---|")
+    err_e, err_item, err_packed = [], [], []
+    one_img = W.batch_from_samples([(1, 1)])
+    e_lin1, e_attn1 = MP.stage_fwd_flops(enc_layers, one_img)
+    e_flop_img = 3.0 * (e_lin1 + e_attn1)
+    tok = W.equal_partition_batch(1, 1)
+    l_lin_tok = 3.0 * MP.stage_fwd_flops(llm_layers, tok)[0]
+    l_attn_sq = 3.0 * MP.stage_fwd_flops(llm_layers, tok)[1]            # per (sample length)^2
+    for seed, budget, mix in W.full_stage_sweep():
+        wl = W.workload_full_stage(seed, budget, mix, with_data=False)
+        samples = wl.batch.samples
+        b = np.array([k for k, _ in samples], dtype=np.float64)
+        sl = np.array([W.IMG_TOKENS * k + t for k, t in samples], dtype=np.float64)
+        e_dur, l_dur = B.mllm_item_durations(b, sl, e_flop_img * b, l_lin_tok * sl, l_attn_sq * sl * sl,
+                                             (bx, e_thr), (sx, lin_thr), (sx, attn_thr))
+        # the encoder sees all images of the microbatch at once: its effective batch size is their sum
+        e_pred = 1e3 * e_flop_img * b.sum() / B.mllm_interp(bx, e_thr, [b.sum()])[0] if b.sum() else 0.0
+        l_item = 1e3 * l_dur.sum()
+        _, l_attn_only = B.mllm_item_durations(b, sl, 0 * b, 0 * sl, l_attn_sq * sl * sl, (bx, e_thr), (sx, lin_thr), (sx, attn_thr))
+        l_packed = 1e3 * (l_lin_tok * sl.sum() / B.mllm_interp(sx, lin_thr, [sl.sum()])[0] + l_attn_only.sum())
+        e_meas = enc.time(wl.batch) if wl.batch.img.total_tokens else 0.0
+        l_meas = llm.time(W.Batch(None, wl.batch.seq, None, samples))
+        if e_meas:
+            err_e.append(abs(e_pred / e_meas - 1))
+        err_item.append(abs(l_item / l_meas - 1))
+        err_packed.append(abs(l_packed / l_meas - 1))
+        print("| mix %s, seed %d | %d | %d | %.1f | %.1f | %.1f | %.1f | %.1f |" % (
+            mix, seed, budget, len(samples), e_meas, e_pred, l_meas, l_item, l_packed), flush=True)
+    print("\nrelative error of the prediction, mean / max: encoder %.1f %% / %.1f %%; LLM per-item rule %.1f %% / %.1f %%; "
+          "LLM packed-length rule %.1f %% / %.1f %%" % (
+              100 * np.mean(err_e), 100 * np.max(err_e), 100 * np.mean(err_item), 100 * np.max(err_item),
+              100 * np.mean(err_packed), 100 * np.max(err_packed)))
+    enc.close()
+    llm.close()
+
+    # memory tables and Algorithm 1
+    mem_b = [1.0, 8.0, 64.0, 256.0]
+    mem_s = [1024.0, 8192.0, 32768.0, 65536.0]
+    e_ms_tab, e_act = MP.memory_tables(lambda n: [W.vit_l_layer() for _ in range(n)],
+                                       lambda x: W.batch_from_samples([(int(x), 1)]), mem_b)
+    l_ms_tab, l_act = MP.memory_tables(lambda n: [W.dec8b_layer() for _ in range(n)],
+                                       lambda x: W.equal_partition_batch(int(x), 8), mem_s)
+    rng = np.random.default_rng(7)
+    items = draw_items(rng, 4096)                                          # the Data Profiler's sample
+    ib = np.array([k for k, _ in items], dtype=np.float64)
+    isl = np.array([W.IMG_TOKENS * k + t for k, t in items], dtype=np.float64)
+    layer_scale_e, layer_scale_l = 1.0, 32.0 / 8.0                           # profiled 8 LLM layers, the model has 32
+
+    def regrid(x, y, grid):          # one input grid per module: read the throughput curve on the memory grid too
+        g = np.unique(np.concatenate([x, grid]))
+        return g, B.mllm_interp(x, y, g)
+
+    eg, e_thr_g = regrid(bx, e_thr, mem_b)
+    lg, l_thr_all = regrid(sx, (l_lin_tok * sx + l_attn_sq * sx * sx) / (l_lin_tok * sx / lin_thr + l_attn_sq * sx * sx / attn_thr), mem_s)
+    enc_prof = dict(tp=[1], x=eg, thr=[e_thr_g], layers_lo=2, layers_hi=4,
+                    model_state=[e_ms_tab],
+                    act_state=[[B.mllm_interp(mem_b, e_act[0], eg, True), B.mllm_interp(mem_b, e_act[1], eg, True)]],
+                    n_layers=24, flop_per_item=float(np.mean(e_flop_img * ib)) * layer_scale_e)
+    llm_prof = dict(tp=[1], x=lg, thr=[l_thr_all], layers_lo=2, layers_hi=4,
+                    model_state=[l_ms_tab],
+                    act_state=[[B.mllm_interp(mem_s, l_act[0], lg, True), B.mllm_interp(mem_s, l_act[1], lg, True)]],
+                    n_layers=32, flop_per_item=float(np.mean(l_lin_tok * isl + l_attn_sq * isl * isl)) * layer_scale_l)
+    print("\n## Algorithm 1 on the measured tables (TP = 1 only, 288 GB per GPU)\n")
+    print("data profile: %.2f images and %.0f LLM tokens per item on average (4096 sampled items)\n" % (ib.mean(), isl.mean()))
+    print("| GPUs | global batch | E_tp E_pp E_dp | L_tp L_pp L_dp | N_mb | estimated makespan s | encoder GB | LLM GB | search ms |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for n_gpus, gbs in ((8, 64), (8, 256), (64, 256), (64, 2048), (512, 2048), (1024, 2048)):
+        t0 = time.perf_counter()
+        theta, t = B.mllm_optimize_parallelism(enc_prof, llm_prof, n_gpus, 1, 288e9, gbs, float(ib.mean()), float(isl.mean()))
+        dt = time.perf_counter() - t0
+        if theta is None:
+            print("| %d | %d | nothing fits | | | | | | %.1f |" % (n_gpus, gbs, dt * 1e3))
+            continue
+        _, em, lm, _ = B.mllm_evaluate_parallelism(enc_prof, llm_prof, theta, 288e9, gbs, float(ib.mean()), float(isl.mean()))
+        print("| %d | %d | %d %d %d | %d %d %d | %d | %.3f | %.1f | %.1f | %.1f |" % (
+            (n_gpus, gbs) + theta + (t, em / 1e9, lm / 1e9, dt * 1e3)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -362,6 +412,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="print stage time versus microbatch shape instead")
     ap.add_argument("--schedule", action="store_true", help="run the microbatch-scheduling experiment instead")
+    ap.add_argument("--plan", action="store_true", help="run the model profiler, its held-out check and Algorithm 1 instead")
     ap.add_argument("--sched-items", type=int, default=64)
     ap.add_argument("--sched-buckets", type=int, default=8)
     ap.add_argument("--sched-nodes", type=int, default=2_000_000)
@@ -373,6 +424,8 @@ def main():
         return sweep(args)
     if args.schedule:
         return schedule_experiment(args)
+    if args.plan:
+        return plan_experiment(args)
     wl, desc = build_workload(args.workload)
     lin_f, attn_f = stage_fwd_flops(wl.layers, wl.batch)
     step_flops = 3.0 * (lin_f + attn_f)

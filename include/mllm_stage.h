@@ -260,6 +260,82 @@ mllm_status_t mllm_schedule(int64_t n_items, const double* e_dur, const double* 
                             double* cmax_out, int32_t* optimal_out);
 
 /* ------------------------------------------------------------------------------------------
+ * Profiled performance model and parallelism search (host only, no GPU work).
+ *
+ * Model Profiler, "Throughput Profiling" / "Memory Profiling": throughput and memory are measured
+ * on a grid of input sizes and TP degrees and read off in between by linear interpolation.
+ *
+ * mllm_interp: out[j] = the piecewise-linear function through (x[k], y[k]), k < n (x strictly
+ *   ascending, n >= 1), at q[j], j < nq.  Outside [x[0], x[n-1]]: the end value when
+ *   extrapolate == 0 (used for throughput), the end segment's straight line otherwise (used for
+ *   memory).  All arrays are host memory, caller-owned.
+ *
+ * mllm_item_durations (Data-aware 3D Parallelism Optimizer, "Problem Formulation"; Online
+ *   Microbatch Scheduler, "Scheduling Optimization"): duration = load / throughput at the item's
+ *   own shape.  Item i has an effective batch size b[i] (its images), an LLM sequence length s[i],
+ *   encoder FLOPs e_flop[i], LLM linear-layer FLOPs l_lin_flop[i] and LLM attention FLOPs
+ *   l_attn_flop[i].  e_dur_out[i] = e_flop[i] / E_thr(b[i]); l_dur_out[i] = l_lin_flop[i] /
+ *   L_lin_thr(s[i]) + l_attn_flop[i] / L_attn_thr(s[i]); a zero load costs zero time.  Each
+ *   throughput curve is a grid (n, x, y) as in mllm_interp with extrapolate == 0, y > 0.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n;          /* grid points, >= 1                          */
+  const double* x;    /* [n] host, strictly ascending               */
+  const double* y;    /* [n] host                                   */
+} mllm_curve_t;
+
+mllm_status_t mllm_interp(const mllm_curve_t* curve, int64_t nq, const double* q, int32_t extrapolate,
+                          double* out);
+mllm_status_t mllm_item_durations(int64_t n_items, const double* b, const double* s,
+                                  const double* e_flop, const double* l_lin_flop,
+                                  const double* l_attn_flop, const mllm_curve_t* e_thr,
+                                  const mllm_curve_t* l_lin_thr, const mllm_curve_t* l_attn_thr,
+                                  double* e_dur_out, double* l_dur_out);
+
+/* What the Model Profiler and the Data Profiler hand to the parallelism search for one module
+ * (modality encoder or LLM).  x is the module's input dimension: effective batch size for the
+ * encoder, packed sequence length for the LLM.  A TP degree between two profiled ones interpolates
+ * linearly between their curves; memory is a straight line in the layer count through the two
+ * profiled layer counts.  All pointers are host memory. */
+typedef struct {
+  int32_t n_tp;               /* profiled TP degrees                                        */
+  const int32_t* tp;          /* [n_tp] strictly ascending                                  */
+  int32_t n_x;                /* grid points of the input dimension                         */
+  const double* x;            /* [n_x] strictly ascending                                   */
+  const double* thr;          /* [n_tp][n_x] FLOP/s per GPU, > 0                            */
+  double layers_lo, layers_hi;/* the two profiled layer counts, lo < hi                     */
+  const double* model_state;  /* [n_tp][2] bytes: parameters, gradients, optimizer states   */
+  const double* act_state;    /* [n_tp][2][n_x] bytes of activations kept for backward      */
+  int32_t n_layers;           /* E_l or L_l: layers of the module to be trained             */
+  double flop_per_item;       /* data-set average FLOPs of one item through the whole module */
+} mllm_module_profile_t;
+
+/* Algorithm 1, Phase 1 helper: all (tp, pp, dp) with tp * pp * dp == gpus, tp <= n_gpu_node
+ * (Eq. 2), pp <= max_pp, ordered by tp then pp.  Writes up to capacity triples to triples_out
+ * (host, [capacity][3], may be NULL when capacity == 0) and the full count to *count_out. */
+mllm_status_t mllm_find_combs(int32_t gpus, int32_t n_gpu_node, int32_t max_pp, int64_t capacity,
+                              int32_t* triples_out, int64_t* count_out);
+
+/* Eq. 1 with the stage durations of Algorithm 1 for ONE configuration theta = (E_tp, E_pp, E_dp,
+ * L_tp, L_pp, L_dp, N_mb): *makespan_out = (N_mb + E_pp + L_pp - 1) * max(E_dur, L_dur);
+ * *e_mem_out / *l_mem_out = Eq. 4 / Eq. 5 at the mean microbatch shape; *feasible_out = both
+ * fit in m_gpu.  Any of the four outputs may be NULL. */
+mllm_status_t mllm_evaluate_parallelism(const mllm_module_profile_t* enc, const mllm_module_profile_t* llm,
+                                        const int32_t theta[7], double m_gpu, int32_t gbs,
+                                        double mean_bsz, double mean_seq_len, double* makespan_out,
+                                        double* e_mem_out, double* l_mem_out, int32_t* feasible_out);
+
+/* Algorithm 1: the configuration with the smallest estimated makespan among all splits of n_gpus
+ * between the two modules (Eq. 3), all (tp, pp, dp) of each side and all microbatch counts
+ * 1 .. gbs / L_dp that fit in m_gpu bytes per GPU (Eq. 4, 5).  Enumeration order: encoder GPUs,
+ * encoder (tp, pp), LLM (tp, pp), microbatch count, all ascending; only a strictly smaller makespan
+ * replaces the incumbent.  *found_out = 0 (theta_out zeroed, *min_t_out = +inf) when nothing fits. */
+mllm_status_t mllm_optimize_parallelism(const mllm_module_profile_t* enc, const mllm_module_profile_t* llm,
+                                        int32_t n_gpus, int32_t n_gpu_node, double m_gpu, int32_t gbs,
+                                        double mean_bsz, double mean_seq_len, int32_t theta_out[7],
+                                        double* min_t_out, int32_t* found_out);
+
+/* ------------------------------------------------------------------------------------------
  * Per-launch timing, for measurement only (off by default; adds two event records per launch).
  * mllm_profile_begin(max_records) creates the events and starts recording every kernel launch of
  * the calling process' later mllm_* calls, bracketing each with HIP events on its launch stream.

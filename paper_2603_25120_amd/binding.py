@@ -25,7 +25,8 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
-           "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule"]
+           "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
+           "mllm_find_combs", "mllm_evaluate_parallelism", "mllm_optimize_parallelism"]
 
 PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise", "gemm_small"]
 
@@ -45,6 +46,18 @@ class LayerDescC(C.Structure):
 
 class StageDescC(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerDescC))]
+
+
+class CurveC(C.Structure):
+    _fields_ = [("n", C.c_int32), ("x", C.POINTER(C.c_double)), ("y", C.POINTER(C.c_double))]
+
+
+class ModuleProfileC(C.Structure):
+    _fields_ = [("n_tp", C.c_int32), ("tp", C.POINTER(C.c_int32)), ("n_x", C.c_int32),
+                ("x", C.POINTER(C.c_double)), ("thr", C.POINTER(C.c_double)),
+                ("layers_lo", C.c_double), ("layers_hi", C.c_double),
+                ("model_state", C.POINTER(C.c_double)), ("act_state", C.POINTER(C.c_double)),
+                ("n_layers", C.c_int32), ("flop_per_item", C.c_double)]
 
 
 class PackC(C.Structure):
@@ -103,6 +116,12 @@ def lib() -> C.CDLL:
     dp, ip = C.POINTER(C.c_double), C.POINTER(i32)
     L.mllm_schedule_lpt.argtypes = [i64, dp, dp, i32, ip]
     L.mllm_schedule.argtypes = [i64, dp, dp, i32, i64, ip, dp, ip]
+    cp, mp = C.POINTER(CurveC), C.POINTER(ModuleProfileC)
+    L.mllm_interp.argtypes = [cp, i64, dp, i32, dp]
+    L.mllm_item_durations.argtypes = [i64, dp, dp, dp, dp, dp, cp, cp, cp, dp, dp]
+    L.mllm_find_combs.argtypes = [i32, i32, i32, i64, ip, C.POINTER(i64)]
+    L.mllm_evaluate_parallelism.argtypes = [mp, mp, ip, C.c_double, i32, C.c_double, C.c_double, dp, dp, dp, ip]
+    L.mllm_optimize_parallelism.argtypes = [mp, mp, i32, i32, C.c_double, i32, C.c_double, C.c_double, ip, dp, ip]
     for name in EXPORTS:
         getattr(L, name)          # every declared entry point must be exported
     _lib = L
@@ -336,3 +355,85 @@ def mllm_schedule(e_dur, l_dur, n_buckets: int, node_limit: int = 1_000_000):
     _check(lib().mllm_schedule(len(e), ep, lp, n_buckets, node_limit, out.ctypes.data_as(C.POINTER(C.c_int32)),
                                C.byref(cmax), C.byref(optimal)))
     return out, cmax.value, bool(optimal.value)
+
+
+def _curve(xy):
+    """(x, y) -> CurveC plus the arrays that must outlive the call."""
+    x, xp = _dvec(xy[0])
+    y, yp = _dvec(xy[1])
+    if x.ndim != 1 or x.shape != y.shape:
+        raise ValueError("a curve is two equally long 1-d arrays")
+    return CurveC(len(x), xp, yp), (x, y)
+
+
+def mllm_interp(x, y, q, extrapolate: bool = False) -> np.ndarray:
+    """Piecewise-linear function through (x, y) at the points q."""
+    c, keep = _curve((x, y))
+    qa, qp = _dvec(np.atleast_1d(q))
+    out = np.zeros(len(qa), dtype=np.float64)
+    _check(lib().mllm_interp(C.byref(c), len(qa), qp, int(bool(extrapolate)), out.ctypes.data_as(C.POINTER(C.c_double))))
+    return out
+
+
+def mllm_item_durations(b, s, e_flop, l_lin_flop, l_attn_flop, e_thr, l_lin_thr, l_attn_thr):
+    """(e_dur, l_dur) per item from the three profiled throughput curves, each given as (x, y)."""
+    arrs = [_dvec(a) for a in (b, s, e_flop, l_lin_flop, l_attn_flop)]
+    n = len(arrs[0][0])
+    if any(len(a) != n for a, _ in arrs):
+        raise ValueError("item arrays differ in length")
+    curves = [_curve(c) for c in (e_thr, l_lin_thr, l_attn_thr)]
+    e_dur, l_dur = np.zeros(n), np.zeros(n)
+    _check(lib().mllm_item_durations(n, *[p for _, p in arrs], *[C.byref(c) for c, _ in curves],
+                                     e_dur.ctypes.data_as(C.POINTER(C.c_double)),
+                                     l_dur.ctypes.data_as(C.POINTER(C.c_double))))
+    return e_dur, l_dur
+
+
+def mllm_find_combs(gpus: int, n_gpu_node: int, max_pp: int) -> np.ndarray:
+    """All (tp, pp, dp) with product `gpus`, as an [n, 3] int32 array."""
+    count = C.c_int64()
+    _check(lib().mllm_find_combs(gpus, n_gpu_node, max_pp, 0, None, C.byref(count)))
+    out = np.zeros((count.value, 3), dtype=np.int32)
+    _check(lib().mllm_find_combs(gpus, n_gpu_node, max_pp, count.value,
+                                 out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(count)))
+    return out
+
+
+def _module_profile(prof: dict):
+    """dict with tp, x, thr [n_tp][n_x], layers_lo, layers_hi, model_state [n_tp][2],
+    act_state [n_tp][2][n_x], n_layers, flop_per_item -> ModuleProfileC plus its arrays."""
+    tp = np.ascontiguousarray(prof["tp"], dtype=np.int32)
+    x, xp = _dvec(prof["x"])
+    thr, tp_ = _dvec(prof["thr"])
+    ms, msp = _dvec(prof["model_state"])
+    act, actp = _dvec(prof["act_state"])
+    if thr.shape != (len(tp), len(x)) or ms.shape != (len(tp), 2) or act.shape != (len(tp), 2, len(x)):
+        raise ValueError("module profile tables have the wrong shape")
+    c = ModuleProfileC(len(tp), tp.ctypes.data_as(C.POINTER(C.c_int32)), len(x), xp, tp_,
+                       float(prof["layers_lo"]), float(prof["layers_hi"]), msp, actp,
+                       int(prof["n_layers"]), float(prof["flop_per_item"]))
+    return c, (tp, x, thr, ms, act)
+
+
+def mllm_evaluate_parallelism(enc: dict, llm: dict, theta, m_gpu: float, gbs: int, mean_bsz: float,
+                              mean_seq_len: float):
+    """(makespan, encoder memory, LLM memory, feasible) of one configuration theta."""
+    e, keep_e = _module_profile(enc)
+    l, keep_l = _module_profile(llm)
+    th = (C.c_int32 * 7)(*[int(v) for v in theta])
+    t, em, lm, ok = C.c_double(), C.c_double(), C.c_double(), C.c_int32()
+    _check(lib().mllm_evaluate_parallelism(C.byref(e), C.byref(l), th, m_gpu, gbs, mean_bsz, mean_seq_len,
+                                           C.byref(t), C.byref(em), C.byref(lm), C.byref(ok)))
+    return t.value, em.value, lm.value, bool(ok.value)
+
+
+def mllm_optimize_parallelism(enc: dict, llm: dict, n_gpus: int, n_gpu_node: int, m_gpu: float, gbs: int,
+                              mean_bsz: float, mean_seq_len: float):
+    """(theta*, min_T) or (None, inf); theta* = (E_tp, E_pp, E_dp, L_tp, L_pp, L_dp, N_mb)."""
+    e, keep_e = _module_profile(enc)
+    l, keep_l = _module_profile(llm)
+    th = (C.c_int32 * 7)()
+    t, found = C.c_double(), C.c_int32()
+    _check(lib().mllm_optimize_parallelism(C.byref(e), C.byref(l), n_gpus, n_gpu_node, m_gpu, gbs, mean_bsz,
+                                           mean_seq_len, th, C.byref(t), C.byref(found)))
+    return (tuple(int(v) for v in th) if found.value else None), t.value

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmllm_stage.so")
 BUILD = os.path.join(ROOT, "_build")
 
-SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ops_abi.hip", "profile.hip", "scheduler.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ops_abi.hip", "profile.hip", "scheduler.hip", "planner.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=fast",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -50,7 +50,7 @@ def build(force: bool = False, verbose: bool = False) -> str:
             if verbose and out.strip():
                 print(out)
     if jobs or force or not os.path.exists(OUT):
-        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs)
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", OUT] + objs)
     return OUT
 
 
