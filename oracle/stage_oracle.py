@@ -298,13 +298,18 @@ def vit_layer_bwd(L, P, C, dy, cu, mask_kind):
 
 
 def decoder_layer_fwd(L, P, x, cu, mask_kind):
-    """n = RMS1(x); q,k,v = n.[Wq|Wk|Wv]; q,k <- RoPE; o = causal GQA attention;
-    x1 = x + o.Wo; n2 = RMS2(x1); y = x1 + (SiLU(n2.Wg) * (n2.Wu)).Wd."""
-    g1, wqkv, wo, g2, wgu, wd = P
+    """n = RMS1(x); q,k,v = n.[Wq|Wk|Wv] (+ [bq|bk|bv] when the layer has a QKV bias);
+    q,k <- RoPE; o = causal GQA attention; x1 = x + o.Wo; n2 = RMS2(x1);
+    y = x1 + (SiLU(n2.Wg) * (n2.Wu)).Wd."""
+    if L.has_bias:
+        g1, wqkv, bqkv, wo, g2, wgu, wd = P
+    else:
+        g1, wqkv, wo, g2, wgu, wd = P
+        bqkv = 0.0
     Hq, Hkv, hd, f = L.n_q_heads, L.n_kv_heads, L.head_dim, L.d_ff
     T = x.shape[0]
     n1, c1 = rmsnorm_fwd(x, g1, L.norm_eps)
-    qkv = n1 @ wqkv
+    qkv = n1 @ wqkv + bqkv
     q = qkv[:, :Hq * hd].reshape(T, Hq, hd)
     k = qkv[:, Hq * hd:(Hq + Hkv) * hd].reshape(T, Hkv, hd)
     v = qkv[:, (Hq + Hkv) * hd:].reshape(T, Hkv, hd)
@@ -323,7 +328,10 @@ def decoder_layer_fwd(L, P, x, cu, mask_kind):
 
 
 def decoder_layer_bwd(L, P, C, dy, cu, mask_kind):
-    g1, wqkv, wo, g2, wgu, wd = P
+    if L.has_bias:
+        g1, wqkv, _bqkv, wo, g2, wgu, wd = P
+    else:
+        g1, wqkv, wo, g2, wgu, wd = P
     Hq, Hkv, hd, f = L.n_q_heads, L.n_kv_heads, L.head_dim, L.d_ff
     T = dy.shape[0]
     d_wd = C["a"].T @ dy
@@ -344,14 +352,41 @@ def decoder_layer_bwd(L, P, C, dy, cu, mask_kind):
     dn1 = dqkv @ wqkv.T
     dx_n, d_g1 = rmsnorm_bwd(dn1, C["c1"], g1)
     dx = dx1 + dx_n
+    if L.has_bias:
+        return dx, [d_g1, d_wqkv, dqkv.sum(axis=0, keepdims=True), d_wo, d_g2, d_wgu, d_wd]
     return dx, [d_g1, d_wqkv, d_wo, d_g2, d_wgu, d_wd]
+
+
+def projector_fwd(L, P, x):
+    """Connector (MLLM Architecture: a linear projector or a multi-layer perceptron):
+    p = x.Wp + bp, or p = act(x.W1 + b1).W2 + b2 when the layer has a hidden width."""
+    if L.d_ff:
+        w1, b1, w2, b2 = P
+        h = x @ w1 + b1
+        a = _act_fwd(L.act, h)
+        return a @ w2 + b2, dict(x=x, h=h, a=a)
+    return x @ P[0] + P[1], dict(x=x)
+
+
+def projector_bwd(L, P, C, dp):
+    if L.d_ff:
+        w1, _b1, w2, _b2 = P
+        da = dp @ w2.T
+        dh = da * _act_grad(L.act, C["h"])
+        g = [C["x"].T @ dh, dh.sum(axis=0, keepdims=True), C["a"].T @ dp, dp.sum(axis=0, keepdims=True)]
+        return dh @ w1.T, g
+    return dp @ P[0].T, [C["x"].T @ dp, dp.sum(axis=0, keepdims=True)]
 
 
 # ---------------------------------------------------------------------------
 # stage = ViT layers -> projector (+ scatter into the packed sequence) -> decoder layers
 # ---------------------------------------------------------------------------
 def n_params(layer) -> int:
-    return {LAYER_VIT: 12, LAYER_DECODER: 6, LAYER_PROJECTOR: 2}[layer.kind]
+    if layer.kind == LAYER_VIT:
+        return 12
+    if layer.kind == LAYER_DECODER:
+        return 7 if layer.has_bias else 6
+    return 4 if layer.d_ff else 2
 
 
 def stage_fwd(layers, params, batch, x_img=None, x_seq=None):
@@ -367,8 +402,7 @@ def stage_fwd(layers, params, batch, x_img=None, x_seq=None):
         if L.kind == LAYER_VIT:
             cur_img, c = vit_layer_fwd(L, P, cur_img, batch.img.cu_seqlens, batch.img.mask_kind)
         elif L.kind == LAYER_PROJECTOR:
-            c = dict(x=cur_img)
-            proj = cur_img @ P[0] + P[1]
+            proj, c = projector_fwd(L, P, cur_img)
             cur_seq[np.asarray(batch.img_to_seq_row, dtype=np.int64), :] = proj
             in_seq_space = True
         else:
@@ -401,8 +435,7 @@ def stage_bwd(layers, params, batch, caches, dy):
             dproj = d[rows, :]
             dx_seq = d.copy()
             dx_seq[rows, :] = 0.0
-            g = [C["x"].T @ dproj, dproj.sum(axis=0, keepdims=True)]
-            d = dproj @ P[0].T
+            d, g = projector_bwd(L, P, C, dproj)
         else:
             d, g = vit_layer_bwd(L, P, C, d, batch.img.cu_seqlens, batch.img.mask_kind)
         for j, gj in enumerate(g):

@@ -266,9 +266,9 @@ def _fwd(wl, params=None, x_img=None, x_seq=None):
                        wl.x_seq if x_seq is None else x_seq)
 
 
-@pytest.mark.parametrize("seed", [0, 3])
-def test_stage_gradients_by_central_differences(seed):
-    wl = _tiny(seed)
+@pytest.mark.parametrize("seed,variant", [(0, False), (3, False), (1, True)])
+def test_stage_gradients_by_central_differences(seed, variant):
+    wl = W.workload_tiny_variant(seed) if variant else _tiny(seed)
     y, caches = _fwd(wl)
     dy = wl.dy.astype(np.float64)
     dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, dy)
@@ -432,3 +432,79 @@ def test_stage_against_torch_cpu_autograd():
     assert rel(dx_seq, x_seq.grad.numpy()) < 1e-10
     for g, p in zip(dparams, P):
         assert rel(g, p.grad.numpy()) < 1e-10
+
+
+def test_variant_stage_against_torch_cpu_autograd():
+    """The variants (tanh-GELU encoder, two-layer MLP connector, grouped-query decoder with a QKV
+    bias) against PyTorch CPU fp64 autograd, sample by sample."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    wl = W.workload_tiny_variant(6)
+    t64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    P = [t64(p) for p in wl.params]
+    assert len(P) == 12 + 4 + 7
+    x_img, x_seq = t64(wl.x_img), t64(wl.x_seq)
+    vit, proj, dec = wl.layers
+    outs = []
+    cu = wl.batch.seq.cu_seqlens
+    for s, (k, t) in enumerate(wl.batch.samples):
+        xi = x_img[64 * s:64 * (s + 1)]
+        g1, b1, wqkv, bqkv, wo, bo, g2, b2, w1, bb1, w2, bb2 = P[:12]
+        n = F.layer_norm(xi, (192,), g1[0], b1[0], vit.norm_eps)
+        qkv = (n @ wqkv + bqkv).reshape(64, 3, 3, 64).permute(1, 2, 0, 3)
+        o = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2])
+        x1 = xi + o.permute(1, 0, 2).reshape(64, 192) @ wo + bo
+        n2 = F.layer_norm(x1, (192,), g2[0], b2[0], vit.norm_eps)
+        yv = x1 + F.gelu(n2 @ w1 + bb1, approximate="tanh") @ w2 + bb2
+        wp1, bp1, wp2, bp2 = P[12:16]
+        pr = F.gelu(yv @ wp1 + bp1) @ wp2 + bp2
+        xs = torch.cat([pr, x_seq[cu[s] + 64:cu[s + 1]]], dim=0)
+        Ls = xs.shape[0]
+        r1, wqkv, bqkv, wo, r2, wgu, wd = P[16:]
+        rms = lambda z, g: z * torch.rsqrt((z * z).mean(dim=1, keepdim=True) + dec.norm_eps) * g
+        n = rms(xs, r1)
+        qkv = n @ wqkv + bqkv
+        q = qkv[:, :256].reshape(Ls, 4, 64).permute(1, 0, 2)
+        kk = qkv[:, 256:384].reshape(Ls, 2, 64).permute(1, 0, 2)
+        v = qkv[:, 384:].reshape(Ls, 2, 64).permute(1, 0, 2)
+        inv = 10000.0 ** (-torch.arange(0, 32, dtype=torch.float64) * 2 / 64)
+        ang = torch.arange(Ls, dtype=torch.float64)[:, None] * inv[None, :]
+        cos, sin = torch.cos(ang), torch.sin(ang)
+        rot = lambda z: torch.cat([z[..., :32] * cos - z[..., 32:] * sin,
+                                   z[..., 32:] * cos + z[..., :32] * sin], dim=-1)
+        o = F.scaled_dot_product_attention(rot(q), rot(kk).repeat_interleave(2, dim=0),
+                                           v.repeat_interleave(2, dim=0), is_causal=True)
+        x1 = xs + o.permute(1, 0, 2).reshape(Ls, 256) @ wo
+        n2 = rms(x1, r2)
+        gu = n2 @ wgu
+        outs.append(x1 + (F.silu(gu[:, :1024]) * gu[:, 1024:]) @ wd)
+    y_t = torch.cat(outs, dim=0)
+    y_t.backward(torch.tensor(wl.dy.astype(np.float64)))
+    y, caches = _fwd(wl)
+    dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, wl.dy.astype(np.float64))
+    rel = lambda a, b: np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30)
+    assert rel(y, y_t.detach().numpy()) < 1e-11
+    assert rel(dx_img, x_img.grad.numpy()) < 1e-10
+    assert rel(dx_seq, x_seq.grad.numpy()) < 1e-10
+    for g, p in zip(dparams, P):
+        assert rel(g, p.grad.numpy()) < 1e-10
+
+
+def test_variant_reductions():
+    """A zero QKV bias gives the bias-free decoder layer; the MLP connector with an identity-like
+    second map reduces to its first map followed by the activation."""
+    wl = W.workload_tiny_variant(2)
+    vit, proj, dec = wl.layers
+    x = wl.x_seq.astype(np.float64)
+    cu, kinds = wl.batch.seq.cu_seqlens, wl.batch.seq.mask_kind
+    Pd = [p.astype(np.float64) for p in wl.params[16:]]
+    Pd[2] = np.zeros_like(Pd[2])
+    y_bias0, _ = O.decoder_layer_fwd(dec, Pd, x, cu, kinds)
+    plain = W.decoder_layer(256, 4, 2, 64, 1024, 10000.0)
+    y_plain, _ = O.decoder_layer_fwd(plain, Pd[:2] + Pd[3:], x, cu, kinds)
+    assert np.array_equal(y_bias0, y_plain)
+    xi = wl.x_img.astype(np.float64)
+    w1, b1 = wl.params[12].astype(np.float64), wl.params[13].astype(np.float64)
+    eye = np.eye(320, 256)
+    p, _ = O.projector_fwd(proj, [w1, b1, eye, np.zeros((1, 256))], xi)
+    assert np.allclose(p, O.gelu_erf(xi @ w1 + b1)[:, :256], rtol=0, atol=1e-15)

@@ -73,12 +73,15 @@ def vit_layer(d, heads, head_dim, d_ff, eps=1e-5, act=ACT_GELU_ERF) -> LayerDesc
     return LayerDesc(LAYER_VIT, d, heads, heads, head_dim, d_ff, 0, act, 1, eps, 0.0)
 
 
-def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5) -> LayerDesc:
-    return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, 0, eps, rope_base)
+def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5, qkv_bias=0) -> LayerDesc:
+    """has_bias = 1 on a decoder layer: the QKV projection (and only it) has a bias."""
+    return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, qkv_bias, eps, rope_base)
 
 
-def projector_layer(d_in, d_out) -> LayerDesc:
-    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, 0, d_out, 0, 1, 0.0, 0.0)
+def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF) -> LayerDesc:
+    """d_hidden = 0: one biased linear map; otherwise a two-layer MLP d_in -> d_hidden -> d_out
+    with a GELU in between (d_ff carries d_hidden)."""
+    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, d_hidden, d_out, act if d_hidden else 0, 1, 0.0, 0.0)
 
 
 def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
@@ -99,9 +102,12 @@ def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
         nqkv = (layer.n_q_heads + 2 * layer.n_kv_heads) * layer.head_dim
         no = layer.n_q_heads * layer.head_dim
         f = layer.d_ff
-        return [("rms1_g", 1, d), ("w_qkv", d, nqkv), ("w_o", no, d),
-                ("rms2_g", 1, d), ("w_gu", d, 2 * f), ("w_d", f, d)]
+        qkv = [("w_qkv", d, nqkv), ("b_qkv", 1, nqkv)] if layer.has_bias else [("w_qkv", d, nqkv)]
+        return [("rms1_g", 1, d)] + qkv + [("w_o", no, d), ("rms2_g", 1, d), ("w_gu", d, 2 * f), ("w_d", f, d)]
     if layer.kind == LAYER_PROJECTOR:
+        if layer.d_ff:
+            return [("w_p1", d, layer.d_ff), ("b_p1", 1, layer.d_ff), ("w_p2", layer.d_ff, layer.d_out),
+                    ("b_p2", 1, layer.d_out)]
         return [("w_p", d, layer.d_out), ("b_p", 1, layer.d_out)]
     raise ValueError("unknown layer kind")
 
@@ -288,6 +294,20 @@ def tiny_stage_layers() -> List[LayerDesc]:
             decoder_layer(256, 4, 4, 64, 1024, 10000.0)]
 
 
+def tiny_variant_layers() -> List[LayerDesc]:
+    """The tiny stage with the variants of the models the paper evaluates: tanh-GELU encoder,
+    two-layer MLP connector, grouped-query decoder with a QKV bias."""
+    return [vit_layer(192, 3, 64, 768, act=ACT_GELU_TANH), projector_layer(192, 256, d_hidden=320),
+            decoder_layer(256, 4, 2, 64, 1024, 10000.0, qkv_bias=1)]
+
+
+def workload_tiny_variant(seed: int) -> Workload:
+    rng = np.random.default_rng(seed)
+    samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
+    batch = batch_from_samples(samples, img_tokens=64)
+    return make_workload("tiny_variant", tiny_variant_layers(), batch, seed)
+
+
 def workload_tiny(seed: int) -> Workload:
     """2 samples x (64 image tokens + text uniform in 32..96); 1 ViT layer (d=192),
     projector 192->256, 1 decoder layer (d=256)."""
@@ -307,6 +327,12 @@ def dec7b_layer() -> LayerDesc:
 
 def dec8b_layer() -> LayerDesc:
     return decoder_layer(4096, 32, 8, 128, 14336, 500000.0)
+
+
+def dec_qkvbias_7b_layer() -> LayerDesc:
+    """Decoder layer shaped like the 7B LLM of the paper's evaluation (Table 4): d = 3584, 28 query
+    heads over 4 KV heads of 128, SwiGLU 18944, QKV bias, RoPE base 1e6."""
+    return decoder_layer(3584, 28, 4, 128, 18944, 1000000.0, eps=1e-6, qkv_bias=1)
 
 
 def workload_vit_l(seed: int, n_images: Optional[int] = None, with_data=True) -> Workload:
