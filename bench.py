@@ -50,6 +50,12 @@ def build_workload(name: str):
     elif name == "dec7b":
         wl = W.workload_dec7b(200, with_data=False)
         desc = "one 7B decoder layer, 8192-token microbatch, seed 200"
+    elif name == "dec_qkvbias_7b":
+        wl = W.workload_dec_qkvbias_7b(300, with_data=False)
+        desc = "one QKV-bias decoder layer of the 7B shape (d 3584, 28/4 heads, SwiGLU 18944), 32768-token microbatch, long-tailed mix, seed 300"
+    elif name == "variant_stage_16k":
+        wl = W.workload_variant_stage(410, 16384, with_data=False)
+        desc = "tanh-GELU ViT-L layer + MLP connector 1024->3584->3584 + QKV-bias 7B-shaped decoder layer, 16384-token microbatch, seed 410"
     elif name == "vit_l":
         wl = W.workload_vit_l(100, with_data=False)
         desc = "one ViT-L/14-336 layer, 16 samples x 1..4 images of 576 tokens, seed 100"

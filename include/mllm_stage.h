@@ -60,20 +60,24 @@ enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
  * arithmetic is the standard pre-norm transformer:
  *   VIT:       n = LayerNorm(x); [q|k|v] = n.W_qkv + b; o = attention (mask per segment);
  *              x1 = x + o.W_o + b_o; n2 = LayerNorm(x1); y = x1 + GELU(n2.W_1 + b_1).W_2 + b_2
- *   DECODER:   n = RMSNorm(x); [q|k|v] = n.W_qkv; rotary positions on q, k (half-split pairs
+ *   DECODER:   n = RMSNorm(x); [q|k|v] = n.W_qkv (+ b_qkv when has_bias = 1, the layout of the 7B
+ *              LLM of the paper's Table 4); rotary positions on q, k (half-split pairs
  *              (i, i + head_dim/2), angle pos * rope_base^(-2i/head_dim), pos restarting at 0 in
  *              every segment); grouped-query attention (kv head = q head / (n_q/n_kv));
  *              x1 = x + o.W_o; n2 = RMSNorm(x1); y = x1 + (SiLU(n2.W_g) * n2.W_u).W_d
- *   PROJECTOR: p = x.W_p + b_p, row i written to row img_to_seq_row[i] of the packed sequence
- *              (the learnable connector of Section 2.1).
+ *   PROJECTOR: p = x.W_p + b_p, or with a hidden width d_ff > 0 the two-layer perceptron
+ *              p = GELU(x.W_p1 + b_p1).W_p2 + b_p2; row i of p is written to row img_to_seq_row[i]
+ *              of the packed sequence (the learnable connector of Section 2.1, which names linear
+ *              projectors and multi-layer perceptrons).
  * Parameter tensors per layer, in order (all bf16, matrices [in, out], vectors [n]):
  *   VIT:       ln1_g, ln1_b, w_qkv [d, 3d], b_qkv, w_o [d, d], b_o, ln2_g, ln2_b,
  *              w_1 [d, f], b_1, w_2 [f, d], b_2
- *   DECODER:   rms1_g, w_qkv [d, (n_q + 2 n_kv) hd], w_o [n_q hd, d], rms2_g,
- *              w_gu [d, 2f] = [W_gate | W_up], w_d [f, d]
- *   PROJECTOR: w_p [d_model, d_out], b_p
+ *   DECODER:   rms1_g, w_qkv [d, (n_q + 2 n_kv) hd], (b_qkv when has_bias = 1,) w_o [n_q hd, d],
+ *              rms2_g, w_gu [d, 2f] = [W_gate | W_up], w_d [f, d]
+ *   PROJECTOR: w_p [d_model, d_out], b_p; or w_p1 [d_model, d_ff], b_p1, w_p2 [d_ff, d_out], b_p2
  * Limits: head_dim in {64, 128}; d_model == n_q_heads * head_dim for VIT / DECODER; every width
- * a multiple of 64; n_q_heads a multiple of n_kv_heads; act GELU_* for VIT, SWIGLU for DECODER.
+ * a multiple of 64; n_q_heads a multiple of n_kv_heads; act GELU_* for VIT and for a two-layer
+ * PROJECTOR, SWIGLU for DECODER.
  * A microbatch is limited by tokens * widest layer width * 2 bytes < 4 GiB (MLLM_ERR_SHAPE beyond:
  * about 74 000 packed tokens for the 8B-shaped decoder layer).
  */
@@ -83,10 +87,10 @@ typedef struct {
   int32_t n_q_heads;
   int32_t n_kv_heads;
   int32_t head_dim;
-  int32_t d_ff;       /* MLP width f                                    */
+  int32_t d_ff;       /* MLP width f; PROJECTOR: hidden width, 0 = linear */
   int32_t d_out;      /* PROJECTOR only: output width                   */
   int32_t act;        /* MLLM_ACT_*                                     */
-  int32_t has_bias;   /* must be 1 for VIT / PROJECTOR, 0 for DECODER   */
+  int32_t has_bias;   /* 1 for VIT / PROJECTOR; DECODER: 0, or 1 = QKV bias */
   float norm_eps;
   float rope_base;    /* DECODER only                                   */
 } mllm_layer_desc_t;

@@ -79,6 +79,10 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
   if (L.kind == MLLM_LAYER_PROJECTOR) {
     if (!m64(L.d_model) || !m64(L.d_out)) return fail(MLLM_ERR_DESC, "layer %d: projector widths must be positive multiples of 64", i);
     if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: projector needs has_bias = 1", i);
+    if (L.d_ff != 0) {
+      if (!m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: the connector's hidden width must be 0 or a positive multiple of 64", i);
+      if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: an MLP connector's activation must be GELU", i);
+    }
     return MLLM_OK;
   }
   if (L.kind != MLLM_LAYER_VIT && L.kind != MLLM_LAYER_DECODER) return fail(MLLM_ERR_DESC, "layer %d: unknown kind %d", i, L.kind);
@@ -94,7 +98,7 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
     if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: ViT activation must be GELU", i);
     if (L.n_q_heads != L.n_kv_heads) return fail(MLLM_ERR_DESC, "layer %d: ViT layer needs n_kv_heads == n_q_heads", i);
   } else {
-    if (L.has_bias != 0) return fail(MLLM_ERR_DESC, "layer %d: decoder layer needs has_bias = 0", i);
+    if (L.has_bias != 0 && L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: decoder layer needs has_bias = 0, or 1 for a QKV bias", i);
     if (L.act != MLLM_ACT_SWIGLU) return fail(MLLM_ERR_DESC, "layer %d: decoder activation must be SwiGLU", i);
     if (!(L.rope_base > 1.f)) return fail(MLLM_ERR_DESC, "layer %d: rope_base must exceed 1", i);
   }
@@ -210,6 +214,10 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     memset(&S, 0, sizeof S);
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       S.x = sv.take((size_t)P.T_img * L.d_model * 2);   // connector input
+      if (L.d_ff) {                                      // MLP connector: hidden pre-activation and activation
+        S.pre = sv.take((size_t)P.T_img * L.d_ff * 2);
+        S.act = sv.take((size_t)P.T_img * L.d_ff * 2);
+      }
       continue;
     }
     const size_t T = L.kind == MLLM_LAYER_VIT ? P.T_img : P.T_seq;
@@ -250,9 +258,15 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       proj = (size_t)P.T_img * L.d_out * 2;
-      P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)P.T_img * std::max(L.d_model, L.d_out) * 2);
-      split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_img));
-      part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * L.d_out * 4);
+      P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)P.T_img * std::max(std::max(L.d_model, L.d_out), L.d_ff) * 2);
+      if (L.d_ff) {
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_ff, P.T_img));
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_ff, L.d_out, P.T_img));
+        a = std::max(a, (size_t)P.T_img * L.d_ff * 2);
+      } else {
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_img));
+      }
+      part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * std::max(L.d_out, L.d_ff) * 4);
       g = std::max(g, (size_t)P.T_img * L.d_model * 2);
       g = std::max(g, (size_t)P.T_seq * L.d_out * 2);
       continue;
@@ -422,6 +436,7 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
              *wup, *bup = nullptr, *wdn, *bdn = nullptr;
   if (vit) { g1 = prm[0]; b1n = prm[1]; wqkv = prm[2]; bqkv = prm[3]; wo = prm[4]; bo = prm[5];
              g2 = prm[6]; b2n = prm[7]; wup = prm[8]; bup = prm[9]; wdn = prm[10]; bdn = prm[11]; }
+  else if (L.has_bias) { g1 = prm[0]; wqkv = prm[1]; bqkv = prm[2]; wo = prm[3]; g2 = prm[4]; wup = prm[5]; wdn = prm[6]; }
   else { g1 = prm[0]; wqkv = prm[1]; wo = prm[2]; g2 = prm[3]; wup = prm[4]; wdn = prm[5]; }
 
   K_TRY(launch_norm_fwd(vit ? 0 : 1, x, g1, b1n, n1, (float*)(saved + S.stats1), T, d, L.norm_eps, s));
@@ -464,6 +479,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   char* we = ws + P.w_e;      // d qkv            [T, nq]
   int ig1, ib1n = -1, iwqkv, ibqkv = -1, iwo, ibo = -1, ig2, ib2n = -1, iwup, ibup = -1, iwdn, ibdn = -1;
   if (vit) { ig1 = 0; ib1n = 1; iwqkv = 2; ibqkv = 3; iwo = 4; ibo = 5; ig2 = 6; ib2n = 7; iwup = 8; ibup = 9; iwdn = 10; ibdn = 11; }
+  else if (L.has_bias) { ig1 = 0; iwqkv = 1; ibqkv = 2; iwo = 3; ig2 = 4; iwup = 5; iwdn = 6; }
   else { ig1 = 0; iwqkv = 1; iwo = 2; ig2 = 3; iwup = 4; iwdn = 5; }
   const int64_t fup = vit ? f : 2 * f;
 
@@ -495,7 +511,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
     K_TRY(launch_rope(we, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 1, s));
   K_TRY(linear_dw(n1, we, dprm[iwqkv], T, d, nq, accumulate, s, split));
-  if (vit) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
+  if (ibqkv >= 0) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
   K_TRY(linear_dx(we, prm[iwqkv], wc, T, d, nq, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x, prm[ig1], (const float*)(saved + S.stats1), wd, dx,
                         (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, s));
@@ -568,8 +584,13 @@ mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** ou
                               {"w_1", i, d, f}, {"b_1", i, 1, f}, {"w_2", i, f, d}, {"b_2", i, 1, d}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
     } else if (L.kind == MLLM_LAYER_DECODER) {
-      const ParamInfo ps[] = {{"rms1_g", i, 1, d}, {"w_qkv", i, d, nq}, {"w_o", i, d, d},
-                              {"rms2_g", i, 1, d}, {"w_gu", i, d, 2 * f}, {"w_d", i, f, d}};
+      st->params.push_back({"rms1_g", i, 1, d});
+      st->params.push_back({"w_qkv", i, d, nq});
+      if (L.has_bias) st->params.push_back({"b_qkv", i, 1, nq});
+      const ParamInfo ps[] = {{"w_o", i, d, d}, {"rms2_g", i, 1, d}, {"w_gu", i, d, 2 * f}, {"w_d", i, f, d}};
+      st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
+    } else if (L.d_ff) {
+      const ParamInfo ps[] = {{"w_p1", i, d, f}, {"b_p1", i, 1, f}, {"w_p2", i, f, L.d_out}, {"b_p2", i, 1, L.d_out}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
     } else {
       const ParamInfo ps[] = {{"w_p", i, d, L.d_out}, {"b_p", i, 1, L.d_out}};
@@ -642,7 +663,15 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       if (i == 0) K_TRY(launch_copy(x_img, saved + P.saved[i].x, (size_t)P.T_img * L.d_model * 2, s));
       void* dst = last ? y : (void*)(saved + P.saved[i + 1].x);
       K_TRY(launch_copy(x_seq, dst, (size_t)P.T_seq * L.d_out * 2, s));
-      K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], ws + P.w_proj, P.T_img, L.d_model, L.d_out, prm[1], nullptr, s));
+      if (L.d_ff) {   // p = act(x.W1 + b1).W2 + b2
+        char* pre = saved + P.saved[i].pre;
+        char* act = saved + P.saved[i].act;
+        K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], pre, P.T_img, L.d_model, L.d_ff, prm[1], nullptr, s));
+        K_TRY(launch_act_fwd(L.act, pre, act, P.T_img, L.d_ff, s));
+        K_TRY(linear_fwd(act, prm[2], ws + P.w_proj, P.T_img, L.d_ff, L.d_out, prm[3], nullptr, s));
+      } else {
+        K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], ws + P.w_proj, P.T_img, L.d_model, L.d_out, prm[1], nullptr, s));
+      }
       K_TRY(launch_scatter_rows(ws + P.w_proj, dst, (const int32_t*)(ws + P.meta.i2s), P.T_img, L.d_out, 0, s));
       continue;
     }
@@ -689,11 +718,25 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
         K_TRY(launch_copy(cur, dx_seq, (size_t)P.T_seq * L.d_out * 2, s));
         K_TRY(launch_zero_rows(dx_seq, i2s, P.T_img, L.d_out, s));
       }
-      K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s,
-                      SplitWs{ws + P.w_split, P.split_bytes}));
-      K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, (float*)(ws + P.w_partial), P.T_img, L.d_out, s));
+      const SplitWs split{ws + P.w_split, P.split_bytes};
+      float* partial = (float*)(ws + P.w_partial);
       void* out = (i == 0 && dx_img) ? dx_img : (void*)pp[flip];
-      K_TRY(linear_dx(dproj, prm[0], out, P.T_img, L.d_model, L.d_out, s));
+      if (L.d_ff) {
+        const char* pre = saved + P.saved[i].pre;
+        const char* act = saved + P.saved[i].act;
+        char* dh = ws + P.w_a;     // d act, then d pre in place   [T_img, d_ff]
+        K_TRY(linear_dw(act, dproj, dprm[2], P.T_img, L.d_ff, L.d_out, accumulate, s, split));
+        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[3], accumulate, partial, P.T_img, L.d_out, s));
+        K_TRY(linear_dx(dproj, prm[2], dh, P.T_img, L.d_ff, L.d_out, s));
+        K_TRY(launch_act_bwd(L.act, dh, pre, dh, P.T_img, L.d_ff, s));
+        K_TRY(linear_dw(saved + P.saved[i].x, dh, dprm[0], P.T_img, L.d_model, L.d_ff, accumulate, s, split));
+        K_TRY(launch_colsum(dh, L.d_ff, (float*)dprm[1], accumulate, partial, P.T_img, L.d_ff, s));
+        K_TRY(linear_dx(dh, prm[0], out, P.T_img, L.d_model, L.d_ff, s));
+      } else {
+        K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s, split));
+        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, partial, P.T_img, L.d_out, s));
+        K_TRY(linear_dx(dproj, prm[0], out, P.T_img, L.d_model, L.d_out, s));
+      }
       cur = out;
       flip ^= 1;
       continue;

@@ -34,7 +34,8 @@ def test_library_exports_every_declared_symbol(B):
 
 
 def test_param_table_matches_the_generator(B):
-    for layers in (W.tiny_stage_layers(), W.full_stage_layers(2, 2), [W.dec7b_layer()], [W.vit_l_layer()]):
+    for layers in (W.tiny_stage_layers(), W.full_stage_layers(2, 2), [W.dec7b_layer()], [W.vit_l_layer()],
+                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()]):
         h = B.mllm_stage_create(layers)
         got = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
         want = [(n, li, r, c) for li, L in enumerate(layers) for n, r, c in W.param_specs(L)]
@@ -61,7 +62,9 @@ def test_descriptor_validation(B):
         [dec, vit],                                                # wrong order
         [vit, _bad(proj, d_model=256), dec],                       # widths do not chain
         [_bad(vit, act=W.ACT_SWIGLU)],
-        [_bad(dec, has_bias=1)],
+        [_bad(dec, has_bias=2)],                                   # decoder: 0, or 1 for a QKV bias
+        [vit, _bad(proj, d_ff=100), dec],                          # connector hidden width not a multiple of 64
+        [vit, _bad(proj, d_ff=128, act=W.ACT_SWIGLU), dec],        # MLP connector needs a GELU
         [],
     ]
     for layers in cases:

@@ -50,6 +50,17 @@ def test_dec7b_layer_full(B):
         st.close()
 
 
+def test_variant_stage_full_width(B):
+    """tanh-GELU ViT-L layer + MLP connector 1024 -> 3584 -> 3584 + QKV-bias decoder layer of the 7B
+    shape (d = 3584, 28/4 heads, SwiGLU 18944) on a 2048-token microbatch: every output and gradient."""
+    wl = W.workload_variant_stage(500, budget=2048)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec8b_layer_sampled_samples(B):
     wl = W.workload_dec8b(300)                       # 32768 packed tokens, GQA 32/8, SwiGLU 14336
     st = GpuStage(B, wl.layers)

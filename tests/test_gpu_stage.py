@@ -33,6 +33,17 @@ def test_tiny_stage_matches_oracle(B, seed):
         st.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_variant_stage_matches_oracle(B, seed):
+    """tanh-GELU encoder, two-layer MLP connector, grouped-query decoder with a QKV bias."""
+    wl = W.workload_tiny_variant(seed)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_tiny_stage_deterministic_and_accumulates(B):
     wl = W.workload_tiny(4)
     st = GpuStage(B, wl.layers)

@@ -367,6 +367,24 @@ def workload_full_stage(seed: int, budget: int, mix: str, n_vit: int = 24, n_dec
     return make_workload("full_stage", full_stage_layers(n_vit, n_dec), batch, seed, with_data)
 
 
+def workload_dec_qkvbias_7b(seed: int, budget: int = 32768, with_data=True) -> Workload:
+    batch = batch_from_samples(draw_samples_mix8b(seed, budget), with_images=False)
+    return make_workload("dec_qkvbias_7b", [dec_qkvbias_7b_layer()], batch, seed, with_data)
+
+
+def workload_variant_stage(seed: int, budget: int = 4096, with_data=True) -> Workload:
+    """One tanh-GELU ViT-L layer, a two-layer MLP connector 1024 -> 3584 -> 3584 and one
+    QKV-bias decoder layer of the 7B shape, on a `budget`-token microbatch of the narrow mix."""
+    samples = draw_samples_mix7b(seed, budget)
+    if sum(k for k, _ in samples) == 0:
+        k0, t0 = samples[0]
+        if t0 > IMG_TOKENS:
+            samples[0] = (1, t0 - IMG_TOKENS)
+    layers = [vit_layer(1024, 16, 64, 4096, eps=1e-6, act=ACT_GELU_TANH),
+              projector_layer(1024, 3584, d_hidden=3584), dec_qkvbias_7b_layer()]
+    return make_workload("variant_stage", layers, batch_from_samples(samples), seed, with_data)
+
+
 def full_stage_sweep() -> List[Tuple[int, int, str]]:
     """The 16 (seed, budget, mix) microbatches: 4 budgets x 2 mixes x 2 seeds."""
     out = []
