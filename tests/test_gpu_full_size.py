@@ -83,6 +83,36 @@ def test_dec8b_layer_sampled_samples(B):
         assert nmax_err(dx_seq[a:b], dx_ref) <= 3e-2, ("dx", s, b - a)
 
 
+def test_full_width_stack_32k_one_sample_through_all_layers(B):
+    """The benchmark's microbatch (seed 414, 32768 packed tokens, 43 images) through a stack of the
+    benchmark's layers at full width and reduced depth (4 ViT-L + connector + 2 8B-GQA layers; the
+    oracle needs minutes for all 32).  The GPU runs the whole microbatch; the oracle runs the
+    shortest image-bearing sample alone through every layer.  Its rows of y, dx_seq and dx_img must
+    match: a sample's rows do not depend on what it is packed with (Model Profiler, "Throughput
+    Profiling")."""
+    wl = W.workload_full_stage(414, 32768, "8b", n_vit=4, n_dec=2)
+    st = GpuStage(B, wl.layers)
+    try:
+        y, dx_img, dx_seq, _ = st.run(wl)
+        y, dx_img, dx_seq = host_f64(y), host_f64(dx_img), host_f64(dx_seq)
+    finally:
+        st.close()
+    samples = wl.batch.samples
+    _, i = min((W.IMG_TOKENS * k + t, i) for i, (k, t) in enumerate(samples) if k >= 1)
+    k, t = samples[i]
+    cu = wl.batch.seq.cu_seqlens
+    a, b = int(cu[i]), int(cu[i + 1])
+    i0 = W.IMG_TOKENS * sum(kk for kk, _ in samples[:i])
+    i1 = i0 + W.IMG_TOKENS * k
+    one = W.batch_from_samples([(k, t)])
+    y_ref, caches = O.stage_fwd(wl.layers, wl.params, one, wl.x_img[i0:i1], wl.x_seq[a:b])
+    dxi_ref, dxs_ref, _ = O.stage_bwd(wl.layers, wl.params, one, caches, wl.dy[a:b].astype(np.float64))
+    assert nmax_err(y[a:b], y_ref) <= 2e-2
+    assert nmax_err(dx_seq[a:b], dxs_ref) <= 3e-2
+    assert nmax_err(dx_img[i0:i1], dxi_ref) <= 3e-2
+    assert np.all(dx_seq[a:a + W.IMG_TOKENS * k] == 0.0)      # rows the connector overwrote
+
+
 @pytest.mark.parametrize("what", ["fwd_up", "dx_down", "dw_up", "dw_qkv"])
 def test_gemm_full_shapes_sampled(B, what):
     T, d, f, nq = 32768, 4096, 14336, 6144

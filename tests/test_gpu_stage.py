@@ -134,6 +134,15 @@ def test_multi_layer_stage(B):
     _layer_case(B, layers, batch, 23)
 
 
+def test_deep_narrow_stage(B):
+    """Error growth with depth: 12 encoder layers + connector + 8 decoder layers at small widths,
+    every output and every gradient still within the stated tolerances."""
+    layers = ([W.vit_layer(256, 4, 64, 512) for _ in range(12)] + [W.projector_layer(256, 384)]
+              + [W.decoder_layer(384, 6, 2, 64, 640, 500000.0) for _ in range(8)])
+    batch = W.batch_from_samples([(2, 61), (0, 200), (1, 7), (3, 130)], img_tokens=80)
+    _layer_case(B, layers, batch, 29)
+
+
 def test_stage_without_dx_and_vit_only(B):
     wl = W.make_workload("v", [W.vit_layer(192, 3, 64, 768)], W.Batch(W.make_pack([64, 30], 0), None, None, []), 24)
     st = GpuStage(B, wl.layers)
