@@ -17,6 +17,7 @@
 // -> LDS.  Tiles are visited in an order that keeps the workgroups resident on one XCD (they
 // share that XCD's L2) on neighbouring tiles of a GROUP_M-tall panel.
 #include <algorithm>
+#include <utility>
 
 #include "gemm_common.h"
 
@@ -90,6 +91,19 @@ __device__ __forceinline__ bf16x8 fetch_frag(const bf16_t* tile, int r0, int kk,
     f.h[1] = lds_read_tr4(tile, STRIDE, kk * 16 + 8 * h + 4, n0, lane & 15);
   }
   return f.v;
+}
+
+// Scheduling pattern of one k-step: MFMA slot M is preceded by up to PER LDS reads while any
+// of the N_READS remain.
+template <int PER, int N_READS, int M>
+__device__ __forceinline__ void interleave_slot() {
+  if constexpr (M * PER < N_READS)
+    __builtin_amdgcn_sched_group_barrier(0x100, (M + 1) * PER <= N_READS ? PER : N_READS - M * PER, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+}
+template <int PER, int N_READS, int... Ms>
+__device__ __forceinline__ void interleave_reads(std::integer_sequence<int, Ms...>) {
+  (interleave_slot<PER, N_READS, Ms>(), ...);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool OUT_F32, int BKT>
@@ -193,6 +207,14 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
 #pragma unroll
         for (int j = 0; j < TN; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      // Issue order inside the step: the LDS reads of the next fragments go out one per MFMA from
+      // the step's start (left alone, the scheduler puts them after the MFMAs and the wavefront
+      // then waits on LDS with nothing queued behind it).
+      if constexpr (kk + 1 < STEPS) {
+        constexpr int N_READS = TM * (A_T ? 2 : 1) + TN * (B_T ? 2 : 1), N_MFMA = TM * TN;
+        constexpr int PER = (N_READS + N_MFMA - 1) / N_MFMA;     // reads per MFMA slot
+        interleave_reads<PER, N_READS>(std::make_integer_sequence<int, N_MFMA>{});
+      }
       __builtin_amdgcn_sched_barrier(0);
     };
     step(std::integral_constant<int, 0>{});
@@ -204,6 +226,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
     if constexpr (!EARLY) {
       __syncthreads();
       fetch(0, an, bn, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
