@@ -165,11 +165,11 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
   constexpr int STEPS = BKT / 16;
   using LA = TileLoader<A_ROWS, A_COLS, A_PAD, NT, A_T, BKT>;
   using LB = TileLoader<B_ROWS, B_COLS, B_PAD, NT, B_T, BKT>;
-  // EARLY (weight-gradient layout, where it measured faster): the tile is moved in the first half
-  // of the k-steps and the barrier sits before the last step's MFMAs, so the next tile's first
-  // fragments are fetched under them.  Otherwise the move is spread over all k-steps and the
-  // barrier closes the iteration.
-  constexpr bool EARLY = A_T && STEPS == 4;
+  // EARLY (four k-steps per tile): the tile is moved in the first half of the k-steps and the
+  // barrier sits before the last step's MFMAs, so the next tile's first fragments are fetched
+  // under them.  Otherwise the move is spread over all k-steps and the barrier closes the
+  // iteration.
+  constexpr bool EARLY = STEPS == 4;
   constexpr int MOVE_STEPS = EARLY ? STEPS / 2 : STEPS;
   constexpr int A_PER = LA::PER_THREAD / MOVE_STEPS, B_PER = LB::PER_THREAD / MOVE_STEPS;
   static_assert(A_PER * MOVE_STEPS == LA::PER_THREAD && B_PER * MOVE_STEPS == LB::PER_THREAD && A_PER >= 1 && B_PER >= 1,
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
       // Issue order inside the step: the LDS reads of the next fragments go out one per MFMA from
       // the step's start (left alone, the scheduler puts them after the MFMAs and the wavefront
       // then waits on LDS with nothing queued behind it).
-      if constexpr (kk + 1 < STEPS) {
+      if constexpr (kk + 1 < STEPS || EARLY) {
         constexpr int N_READS = TM * (A_T ? 2 : 1) + TN * (B_T ? 2 : 1), N_MFMA = TM * TN;
         constexpr int PER = (N_READS + N_MFMA - 1) / N_MFMA;     // reads per MFMA slot
         interleave_reads<PER, N_READS>(std::make_integer_sequence<int, N_MFMA>{});
