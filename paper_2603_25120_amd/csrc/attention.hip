@@ -360,16 +360,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 // dK/dV pass: one workgroup per (key tile of 128, kv head); each wavefront owns 32 key rows and
 // loops over the query heads of the group and the query tiles that can see its keys.
+//
+// The query-side tiles (Q, dO) are double-buffered in LDS and filled by buffer loads that write
+// LDS directly (no staging registers, no LDS store instructions): the loads of tile i+1 are
+// enqueued right after the barrier that opens tile i and have all of tile i's MFMAs to land.
+// One such instruction moves 64 chunks of 16 bytes into 1 KiB of LDS, lane l to chunk position
+// l % CPR of row l / CPR; the lane therefore asks for the global chunk that the XOR swizzle keeps
+// at that position.  Rows past the segment are out of the descriptor's range and arrive as zeros.
 // ---------------------------------------------------------------------------------------------
+#define MLLM_LDS_VOID(ptr) ((MLLM_LDS void*)(ptr))
+// s_waitcnt vmcnt(0) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int WAIT_VMCNT_0 = (0x7 << 4) | (0xF << 8);
+
 template <int HD>
 __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(AttnParams p) {
-  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * STRIDE];
-  __shared__ float lse_s[BQ], delta_s[BQ];
+  constexpr int NC = HD / 16, ND = HD / 32, TILE = BQ * HD;
+  __shared__ __attribute__((aligned(1024))) bf16_t Qs0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Qs1[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t dOs0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t dOs1[TILE];
+  __shared__ float lse_s0[BQ], lse_s1[BQ], delta_s0[BQ], delta_s1[BQ];
   const AttnTile t = p.tiles[blockIdx.y];
   const int kvh = blockIdx.x, grp = p.Hq / p.Hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int krow = t.tile0 + 32 * wave + (lane & 31);
   const bool kok = krow < t.seg_len;
   const int64_t gkrow = t.seg_start + (kok ? krow : 0);
@@ -389,62 +403,112 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
 
   const int q_begin = t.causal ? (t.tile0 / BQ) * BQ : 0;
   const int wave_first_k = t.tile0 + 32 * wave;
-  RowTile<BQ, HD> lq, ldo;
-  for (int j = 0; j < grp; j++) {
-    const int head = kvh * grp + j;
-    const bf16_t* qbase = p.q + (int64_t)t.seg_start * p.q_stride + head * HD;
-    const bf16_t* dobase = p.d_o + (int64_t)t.seg_start * p.o_stride + head * HD;
-    const float* lse_h = p.lse + (int64_t)head * p.T + t.seg_start;
-    const float* delta_h = p.delta + (int64_t)head * p.T + t.seg_start;
-    for (int q0 = q_begin; q0 < t.seg_len; q0 += BQ) {
-      lq.load(qbase, p.q_stride, q0, t.seg_len, tid);
-      ldo.load(dobase, p.o_stride, q0, t.seg_len, tid);
-      float my_lse = INFINITY, my_delta = 0.f;   // +inf: probabilities of rows past the segment are 0
-      if (tid < BQ && q0 + tid < t.seg_len) {
-        my_lse = lse_h[q0 + tid] * LOG2E;
-        my_delta = delta_h[q0 + tid];
+  const int n_it = grp * ((t.seg_len - q_begin + BQ - 1) / BQ);
+
+  constexpr int CPR = HD / 8, RPI = 64 / CPR, PER_WAVE = BQ / RPI / 4;
+  uint32_t q_off[PER_WAVE], do_off[PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; i++) {
+    const int r = (wave * PER_WAVE + i) * RPI + lane / CPR, c = (lane % CPR) ^ swz<HD>(r);
+    q_off[i] = (uint32_t)((r * p.q_stride + 8 * c) * 2);
+    do_off[i] = (uint32_t)((r * p.o_stride + 8 * c) * 2);
+  }
+  const uint32_t q_bytes = (uint32_t)(((int64_t)(t.seg_len - 1) * p.q_stride + HD) * 2);
+  const uint32_t do_bytes = (uint32_t)(((int64_t)(t.seg_len - 1) * p.o_stride + HD) * 2);
+
+  // The tile to be loaded next: query head nj of the group, query rows from nq0.  Past the last
+  // tile the descriptors are empty and the loads write zeros.
+  int nj = 0, nq0 = q_begin;
+  float r_lse = 0.f, r_delta = 0.f;   // statistics of the tile in flight, one row per thread (tid < BQ)
+  bool r_ok = false;
+  auto issue = [&](bf16_t* qs, bf16_t* dos) {
+    const bool valid = nj < grp;
+    const int head = kvh * grp + (valid ? nj : 0);
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.q + (int64_t)t.seg_start * p.q_stride + head * HD), 0, valid ? (int)q_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rdo = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.d_o + (int64_t)t.seg_start * p.o_stride + head * HD), 0, valid ? (int)do_bytes : 0, 0x00020000);
+    const uint32_t qrow = (uint32_t)nq0 * (uint32_t)(p.q_stride * 2), dorow = (uint32_t)nq0 * (uint32_t)(p.o_stride * 2);
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; i++) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, MLLM_LDS_VOID(qs + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(q_off[i] + qrow), 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdo, MLLM_LDS_VOID(dos + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(do_off[i] + dorow), 0, 0, 0);
+    }
+    const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.lse + (int64_t)head * p.T + t.seg_start), 0, valid ? t.seg_len * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.delta + (int64_t)head * p.T + t.seg_start), 0, valid ? t.seg_len * 4 : 0, 0x00020000);
+    const uint32_t so = tid < BQ ? (uint32_t)(nq0 + tid) * 4u : 0xFFFFFFFFu;
+    r_lse = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, (int)so, 0, 0));
+    r_delta = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rd, (int)so, 0, 0));
+    r_ok = valid && tid < BQ && nq0 + tid < t.seg_len;
+    nq0 += BQ;
+    if (nq0 >= t.seg_len) { nq0 = q_begin; nj++; }
+  };
+
+  // One tile: publish the statistics of the tile whose loads were enqueued a tile ago, wait for
+  // those loads, barrier (every wavefront is now done with the other stage), enqueue the next
+  // tile into the other stage, multiply.
+  auto tile = [&](const bf16_t* Qs, const bf16_t* dOs, float* lse_s, float* delta_s, bf16_t* Qn, bf16_t* dOn,
+                  int q0, bool live) {
+    if (tid < BQ) {
+      lse_s[tid] = r_ok ? r_lse * LOG2E : INFINITY;   // +inf: probabilities of rows past the segment are 0
+      delta_s[tid] = r_ok ? r_delta : 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
+    __syncthreads();
+    issue(Qn, dOn);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!live || (t.causal && q0 + BQ - 1 < wave_first_k)) return;  // no query here sees this wave's keys
+#pragma unroll
+    for (int b = 0; b < BQ / 32; b++) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < NC; c++) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
       }
-      __syncthreads();  // previous step's readers are done
-      lq.store(Qs, tid);
-      ldo.store(dOs, tid);
-      if (tid < BQ) { lse_s[tid] = my_lse; delta_s[tid] = my_delta; }
-      __syncthreads();
-      if (t.causal && q0 + BQ - 1 < wave_first_k) continue;  // no query here sees this wave's keys
+      f32x16 pr;
+      if (t.causal && q0 + 32 * b <= wave_first_k + 31) {   // block touches the diagonal
 #pragma unroll
-      for (int b = 0; b < BQ / 32; b++) {
-        f32x16 s, dp;
+        for (int v = 0; v < 16; v++) s[v] = (krow <= q0 + 32 * b + acc_row(v, h)) ? s[v] : -INFINITY;
+      }
 #pragma unroll
-        for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+      for (int v = 0; v < 16; v++) {
+        const int qi = 32 * b + acc_row(v, h);
+        pr[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse_s[qi]));
+        s[v] = pr[v] * (dp[v] - delta_s[qi]);   // dS
+      }
 #pragma unroll
-        for (int c = 0; c < NC; c++) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
-        }
-        f32x16 pr;
-        if (t.causal && q0 + 32 * b <= wave_first_k + 31) {   // block touches the diagonal
+      for (int cc = 0; cc < 2; cc++) {
+        const bf16x8 pf = acc_to_frag(pr, cc), dsf = acc_to_frag(s, cc);
 #pragma unroll
-          for (int v = 0; v < 16; v++) s[v] = (krow <= q0 + 32 * b + acc_row(v, h)) ? s[v] : -INFINITY;
-        }
-#pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const int qi = 32 * b + acc_row(v, h);
-          pr[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse_s[qi]));
-          s[v] = pr[v] * (dp[v] - delta_s[qi]);   // dS
-        }
-#pragma unroll
-        for (int cc = 0; cc < 2; cc++) {
-          const bf16x8 pf = acc_to_frag(pr, cc), dsf = acc_to_frag(s, cc);
-#pragma unroll
-          for (int d = 0; d < ND; d++) {
-            dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols_permuted<HD>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
-            dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols_permuted<HD>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
-          }
+        for (int d = 0; d < ND; d++) {
+          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_permuted<HD>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
+          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_permuted<HD>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
         }
       }
     }
+  };
+
+  issue(Qs0, dOs0);
+  int q0 = q_begin;
+  auto advance = [&]() { q0 += BQ; if (q0 >= t.seg_len) q0 = q_begin; };
+  for (int it = 0; it < n_it; it += 2) {
+    tile(Qs0, dOs0, lse_s0, delta_s0, Qs1, dOs1, q0, true);
+    advance();
+    tile(Qs1, dOs1, lse_s1, delta_s1, Qs0, dOs0, q0, it + 1 < n_it);
+    advance();
   }
+  // the last enqueued loads (an empty tile: zeros) must have landed before this workgroup's LDS
+  // can be handed to another one
+  __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
   if (!kok) return;
   bf16_t* dkp = p.dk + gkrow * p.kv_stride + kvh * HD;
   bf16_t* dvp = p.dv + gkrow * p.kv_stride + kvh * HD;
