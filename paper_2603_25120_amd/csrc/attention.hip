@@ -17,6 +17,8 @@
 //   dQ pass:  S^T, dP^T = V.dO^T, dS^T = P^T*(dP^T - delta), dQ^T += K^T.dS^T
 //   dK/dV:    S = Q.K^T, dP = dO.V^T, dV^T += dO^T.P, dK^T += Q^T.dS, looping the query tiles
 //             and the query heads of the GQA group, so dK/dV need no atomics.
+#include <utility>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -368,6 +370,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // l % CPR of row l / CPR; the lane therefore asks for the global chunk that the XOR swizzle keeps
 // at that position.  Rows past the segment are out of the descriptor's range and arrive as zeros.
 // ---------------------------------------------------------------------------------------------
+// Scheduling patterns (one call per slot): an MFMA followed by N LDS reads; four LDS reads
+// followed by a pair of MFMAs.
+template <int N, int... Is>
+__device__ __forceinline__ void reads_behind_mfmas(std::integer_sequence<int, Is...>) {
+  ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0), __builtin_amdgcn_sched_group_barrier(0x100, N, 0), (void)Is), ...);
+}
+template <int... Is>
+__device__ __forceinline__ void reads_before_mfma_pairs(std::integer_sequence<int, Is...>) {
+  ((__builtin_amdgcn_sched_group_barrier(0x100, 4, 0), __builtin_amdgcn_sched_group_barrier(0x008, 2, 0), (void)Is), ...);
+}
 #define MLLM_LDS_VOID(ptr) ((MLLM_LDS void*)(ptr))
 // s_waitcnt vmcnt(0) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int WAIT_VMCNT_0 = (0x7 << 4) | (0xF << 8);
@@ -467,12 +479,33 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
       f32x16 s, dp;
 #pragma unroll
       for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+      // Scores: 2 NC MFMAs, their LDS reads issued four ahead (left alone, the scheduler reads
+      // each fragment into the same registers right before its MFMA and waits for it every time).
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int c = 0; c < NC; c++) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Qs, 32 * b, c, lane), kf[c], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(dOs, 32 * b, c, lane), vf[c], dp, 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      reads_behind_mfmas<1>(std::make_integer_sequence<int, 2 * NC - 4>{});
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      // First fragments of the dV / dK products: their LDS latency runs under the vector work.
+      constexpr int NPV = 2 * ND;            // (cc, d) pairs, two MFMAs each
+      bf16x8 fdo = frag_cols_permuted<HD>(dOs, 32 * b, 0, lane), fq = frag_cols_permuted<HD>(Qs, 32 * b, 0, lane);
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 pr;
+      // The scores are consumed by the vector ALU: keep them out of the accumulation registers
+      // (with the whole register file available the allocator otherwise parks them there and
+      // copies every value back and forth).
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        float a = s[v], c = dp[v];
+        asm volatile("" : "+v"(a), "+v"(c));
+        s[v] = a;
+        dp[v] = c;
+      }
       if (t.causal && q0 + 32 * b <= wave_first_k + 31) {   // block touches the diagonal
 #pragma unroll
         for (int v = 0; v < 16; v++) s[v] = (krow <= q0 + 32 * b + acc_row(v, h)) ? s[v] : -INFINITY;
@@ -483,17 +516,28 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
         pr[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse_s[qi]));
         s[v] = pr[v] * (dp[v] - delta_s[qi]);   // dS
       }
+      bf16x8 pf[2], dsf[2];
 #pragma unroll
-      for (int cc = 0; cc < 2; cc++) {
-        const bf16x8 pf = acc_to_frag(pr, cc), dsf = acc_to_frag(s, cc);
+      for (int cc = 0; cc < 2; cc++) { pf[cc] = acc_to_frag(pr, cc); dsf[cc] = acc_to_frag(s, cc); }
+      __builtin_amdgcn_sched_barrier(0);
+      // dV, dK: every pair of MFMAs is preceded by the four LDS reads of the next pair's fragments.
 #pragma unroll
-        for (int d = 0; d < ND; d++) {
-          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<HD>(dOs, 32 * b + 16 * cc, 32 * d, lane), pf, dvacc[d], 0, 0, 0);
-          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<HD>(Qs, 32 * b + 16 * cc, 32 * d, lane), dsf, dkacc[d], 0, 0, 0);
+      for (int i = 0; i < NPV; i++) {
+        const int cc = i / ND, d = i % ND;
+        bf16x8 ndo = fdo, nq = fq;
+        if (i + 1 < NPV) {
+          const int cc1 = (i + 1) / ND, d1 = (i + 1) % ND;
+          ndo = frag_cols_permuted<HD>(dOs, 32 * b + 16 * cc1, 32 * d1, lane);
+          nq = frag_cols_permuted<HD>(Qs, 32 * b + 16 * cc1, 32 * d1, lane);
         }
+        dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo, pf[cc], dvacc[d], 0, 0, 0);
+        dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, dsf[cc], dkacc[d], 0, 0, 0);
+        fdo = ndo;
+        fq = nq;
       }
+      reads_before_mfma_pairs(std::make_integer_sequence<int, NPV - 1>{});
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
