@@ -17,6 +17,7 @@
 //   dQ pass:  S^T, dP^T = V.dO^T, dS^T = P^T*(dP^T - delta), dQ^T += K^T.dS^T
 //   dK/dV:    S = Q.K^T, dP = dO.V^T, dV^T += dO^T.P, dK^T += Q^T.dS, looping the query tiles
 //             and the query heads of the GQA group, so dK/dV need no atomics.
+#include <algorithm>
 #include <utility>
 
 #include "common.h"
@@ -40,6 +41,12 @@ template <int HD>
 __device__ __forceinline__ int swz(int r) {
   if constexpr (HD == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
   else { const int t = (r >> 1) & 7; return ((t & 1) << 2) | (t >> 1); }
+}
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// Descriptor over rows [0, rows) of a row-major bf16 matrix slice of `width` columns.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_rsrc(const bf16_t* base, int64_t stride, int rows, int width) {
+  const uint32_t bytes = rows > 0 ? (uint32_t)(((int64_t)(rows - 1) * stride + width) * 2) : 0u;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)bytes, 0x00020000);
 }
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -69,6 +76,16 @@ struct RowTile {
       r[i] = (row0 + rr < seg_len)
                  ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + rr) * stride + cc)
                  : make_uint4(0, 0, 0, 0);
+    }
+  }
+  // The same through a buffer descriptor whose range ends with the last wanted row: rows beyond
+  // it come back as zeros without a branch (and without traffic).
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int64_t stride, int row0, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; i++) {
+      const int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
+      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(uint32_t)(((row0 + rr) * stride + cc) * 2), 0, 0);
+      r[i] = make_uint4(v.x, v.y, v.z, v.w);
     }
   }
   __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
@@ -119,6 +136,22 @@ __device__ __forceinline__ bf16x8 global_frag(const bf16_t* p, bool ok) {
 // Row index inside a 32x32 accumulator block held at position v by a lane of half h.
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
+// Scheduling patterns (one call per slot): an MFMA followed by N LDS reads; four LDS reads
+// followed by a pair of MFMAs.
+template <int N, int... Is>
+__device__ __forceinline__ void reads_behind_mfmas(std::integer_sequence<int, Is...>) {
+  ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0), __builtin_amdgcn_sched_group_barrier(0x100, N, 0), (void)Is), ...);
+}
+// N LDS reads followed by one MFMA.
+template <int N, int... Is>
+__device__ __forceinline__ void reads_before_mfmas(std::integer_sequence<int, Is...>) {
+  ((__builtin_amdgcn_sched_group_barrier(0x100, N, 0), __builtin_amdgcn_sched_group_barrier(0x008, 1, 0), (void)Is), ...);
+}
+template <int... Is>
+__device__ __forceinline__ void reads_before_mfma_pairs(std::integer_sequence<int, Is...>) {
+  ((__builtin_amdgcn_sched_group_barrier(0x100, 4, 0), __builtin_amdgcn_sched_group_barrier(0x008, 2, 0), (void)Is), ...);
+}
+
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
@@ -151,29 +184,37 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
   float m = -INFINITY, l = 0.f;
   const float c2 = p.scale_log2e;
 
+  const __amdgpu_buffer_rsrc_t rk = rows_rsrc(kbase, p.kv_stride, kv_end, HD), rv = rows_rsrc(vbase, p.kv_stride, kv_end, HD);
   RowTile<BKV, HD> lk, lv;
-  lk.load(kbase, p.kv_stride, 0, t.seg_len, tid);
-  lv.load(vbase, p.kv_stride, 0, t.seg_len, tid);
+  lk.load(rk, p.kv_stride, 0, tid);
+  lv.load(rv, p.kv_stride, 0, tid);
   for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
     __syncthreads();  // previous step's readers are done
     lk.store(Ks, tid);
     lv.store(Vs, tid);
     __syncthreads();
-    if (kv0 + BKV < kv_end) {
-      lk.load(kbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
-      lv.load(vbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
-    }
+    lk.load(rk, p.kv_stride, kv0 + BKV, tid);   // rows past kv_end: zeros, no traffic
+    lv.load(rv, p.kv_stride, kv0 + BKV, tid);
     if (t.causal && kv0 > wave_last_q) continue;  // wavefront-uniform
     f32x16 s[NB];
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
       for (int v = 0; v < 16; v++) s[b][v] = 0.f;
+    // Scores: the LDS reads of the K fragments run four ahead of their MFMAs.
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int c = 0; c < NC; c++)
 #pragma unroll
       for (int b = 0; b < NB; b++)
         s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Ks, 32 * b, c, lane), qf[c], s[b], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    reads_behind_mfmas<1>(std::make_integer_sequence<int, NC * NB - 4>{});
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // First V fragment: its LDS latency runs under the softmax.
+    bf16x8 fv = frag_cols_permuted<HD>(Vs, 0, 0, lane);
+    __builtin_amdgcn_sched_barrier(0);
     // Only tiles that cross the segment end or the diagonal need the mask (wavefront-uniform).
     const bool need_mask = (kv0 + BKV > t.seg_len) || (t.causal && kv0 + BKV - 1 > wave_first_q);
     if (need_mask) {
@@ -211,16 +252,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
         for (int v = 0; v < 16; v++) oacc[d][v] *= alpha;
     }
     m = m_new;
+    bf16x8 pf[NB][2];
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
-      for (int cc = 0; cc < 2; cc++) {
-        const bf16x8 pf = acc_to_frag(s[b], cc);
+      for (int cc = 0; cc < 2; cc++) pf[b][cc] = acc_to_frag(s[b], cc);
+    __builtin_amdgcn_sched_barrier(0);
+    // O^T += V^T.P^T: each MFMA is preceded by the two LDS reads of the next V fragment.
+    constexpr int NPV = NB * 2 * ND;
 #pragma unroll
-        for (int d = 0; d < ND; d++)
-          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<HD>(Vs, 32 * b + 16 * cc, 32 * d, lane), pf, oacc[d], 0, 0, 0);
-      }
+    for (int i = 0; i < NPV; i++) {
+      const int bc = i / ND, d = i % ND;          // bc = 2 b + cc
+      bf16x8 nv = fv;
+      if (i + 1 < NPV) nv = frag_cols_permuted<HD>(Vs, 16 * ((i + 1) / ND), 32 * ((i + 1) % ND), lane);
+      oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, pf[bc / 2][bc % 2], oacc[d], 0, 0, 0);
+      fv = nv;
+    }
+    reads_before_mfmas<2>(std::make_integer_sequence<int, NPV - 1>{});
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
   l += __shfl_xor(l, 32, 64);
   if (!qok) return;
@@ -302,29 +352,37 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 #pragma unroll
     for (int v = 0; v < 16; v++) dqacc[d][v] = 0.f;
 
+  const __amdgpu_buffer_rsrc_t rk = rows_rsrc(kbase, p.kv_stride, kv_end, HD), rv = rows_rsrc(vbase, p.kv_stride, kv_end, HD);
   RowTile<BKV, HD> lk, lv;
-  lk.load(kbase, p.kv_stride, 0, t.seg_len, tid);
-  lv.load(vbase, p.kv_stride, 0, t.seg_len, tid);
+  lk.load(rk, p.kv_stride, 0, tid);
+  lv.load(rv, p.kv_stride, 0, tid);
   for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
     __syncthreads();
     lk.store(Ks, tid);
     lv.store(Vs, tid);
     __syncthreads();
-    if (kv0 + BKV < kv_end) {
-      lk.load(kbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
-      lv.load(vbase, p.kv_stride, kv0 + BKV, t.seg_len, tid);
-    }
+    lk.load(rk, p.kv_stride, kv0 + BKV, tid);   // rows past kv_end: zeros, no traffic
+    lv.load(rv, p.kv_stride, kv0 + BKV, tid);
     if (t.causal && kv0 > wave_last_q) continue;
 #pragma unroll
     for (int b = 0; b < BKV / 32; b++) {
       f32x16 s, dp;
 #pragma unroll
       for (int v = 0; v < 16; v++) { s[v] = 0.f; dp[v] = 0.f; }
+      // Scores and dP: the LDS reads run four ahead of their MFMAs.
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int c = 0; c < NC; c++) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Ks, 32 * b, c, lane), qf[c], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HD>(Vs, 32 * b, c, lane), dof[c], dp, 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      reads_behind_mfmas<1>(std::make_integer_sequence<int, 2 * NC - 4>{});
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      // First K^T fragment of the dQ product: its LDS latency runs under the vector work.
+      bf16x8 fk = frag_cols_permuted<HD>(Ks, 32 * b, 0, lane);
+      __builtin_amdgcn_sched_barrier(0);
       const bool need_mask = (kv0 + 32 * b + 32 > t.seg_len) || (t.causal && kv0 + 32 * b + 31 > wave_first_q);
       if (need_mask) {
 #pragma unroll
@@ -336,14 +394,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
       }
 #pragma unroll
       for (int v = 0; v < 16; v++) s[v] = fast_exp2(fmaf(s[v], p.scale_log2e, -lse2)) * (dp[v] - delta);   // dS^T
+      bf16x8 dsf[2];
 #pragma unroll
-      for (int cc = 0; cc < 2; cc++) {
-        const bf16x8 dsf = acc_to_frag(s, cc);
+      for (int cc = 0; cc < 2; cc++) dsf[cc] = acc_to_frag(s, cc);
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int NDQ = 2 * ND;
 #pragma unroll
-        for (int d = 0; d < ND; d++)
-          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_permuted<HD>(Ks, 32 * b + 16 * cc, 32 * d, lane), dsf, dqacc[d], 0, 0, 0);
+      for (int i = 0; i < NDQ; i++) {
+        bf16x8 nk = fk;
+        if (i + 1 < NDQ) nk = frag_cols_permuted<HD>(Ks, 32 * b + 16 * ((i + 1) / ND), 32 * ((i + 1) % ND), lane);
+        dqacc[i % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, dsf[i / ND], dqacc[i % ND], 0, 0, 0);
+        fk = nk;
       }
+      reads_before_mfmas<2>(std::make_integer_sequence<int, NDQ - 1>{});
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   if (!qok) return;
@@ -370,16 +435,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // l % CPR of row l / CPR; the lane therefore asks for the global chunk that the XOR swizzle keeps
 // at that position.  Rows past the segment are out of the descriptor's range and arrive as zeros.
 // ---------------------------------------------------------------------------------------------
-// Scheduling patterns (one call per slot): an MFMA followed by N LDS reads; four LDS reads
-// followed by a pair of MFMAs.
-template <int N, int... Is>
-__device__ __forceinline__ void reads_behind_mfmas(std::integer_sequence<int, Is...>) {
-  ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0), __builtin_amdgcn_sched_group_barrier(0x100, N, 0), (void)Is), ...);
-}
-template <int... Is>
-__device__ __forceinline__ void reads_before_mfma_pairs(std::integer_sequence<int, Is...>) {
-  ((__builtin_amdgcn_sched_group_barrier(0x100, 4, 0), __builtin_amdgcn_sched_group_barrier(0x008, 2, 0), (void)Is), ...);
-}
 #define MLLM_LDS_VOID(ptr) ((MLLM_LDS void*)(ptr))
 // s_waitcnt vmcnt(0) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int WAIT_VMCNT_0 = (0x7 << 4) | (0xF << 8);
@@ -585,8 +640,17 @@ AttnParams make_params(const AttnArgs& a) {
 
 }  // namespace
 
+// The kernels address K, V, Q and dO rows through 32-bit byte offsets from the segment start
+// (buffer descriptors whose range ends at the last wanted row); a tile may run up to 255 rows
+// past the end before the range check rejects it, so those offsets must not wrap either.
+static bool offsets_fit(const AttnArgs& a) {
+  const int64_t widest = std::max(a.q_stride, std::max(a.kv_stride, a.o_stride));
+  return ((int64_t)a.total_tokens + 256) * widest * 2 < (int64_t)0xFFFFFFFFll;
+}
+
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (a.n_q_tiles == 0) return hipSuccess;
+  if (!offsets_fit(a)) return hipErrorInvalidValue;
   ProfScope prof(PROF_ATTN_FWD, a.fwd_flops, s);
   AttnParams p = make_params(a);
   p.tiles = a.q_tiles;
@@ -599,6 +663,7 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   if (a.n_q_tiles == 0) return hipSuccess;
+  if (!offsets_fit(a)) return hipErrorInvalidValue;
   ProfScope prof(PROF_ATTN_BWD, 2.0 * a.fwd_flops, s);
   AttnParams p = make_params(a);
   const int64_t n = (int64_t)a.total_tokens * a.n_q_heads * (a.head_dim / 8);

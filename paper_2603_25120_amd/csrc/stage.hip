@@ -275,6 +275,8 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     const size_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
     const size_t widest = std::max<size_t>(std::max(d, 2 * f), nq);
     P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)(T * widest * 2));
+    // the attention kernels' 32-bit row offsets may run 256 rows past the last token
+    P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)((T + 256) * std::max(nq, d) * 2));
     part = std::max(part, (size_t)norm_bwd_partial_rows(T) * d * 4 * 2);
     part = std::max(part, (size_t)colsum_partial_rows(T) * widest * 4);
     a = std::max(a, T * f * 2);
