@@ -388,6 +388,83 @@ hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const voi
   return hipGetLastError();
 }
 
+// Narrow rows (d <= 1024): a wavefront owns a row, so there is no barrier per row and all 256
+// threads have data; the four wavefronts' column sums are added through LDS once at the end.
+template <int KIND, int NV>
+__global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
+    const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+    const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
+    float* __restrict__ partial, int64_t T, int d) {
+  __shared__ float red[2][4][1024];  // [d gamma | d beta][wavefront][column]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int B = gridDim.x, b = blockIdx.x;
+  const int nvec = d >> 3;
+  float g[NV][8], dg[NV][8], db[NV][8];
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    const int c = lane + 64 * j;
+    if (c < nvec) unpack8(*reinterpret_cast<const uint4*>(gamma + 8 * c), g[j]);
+#pragma unroll
+    for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; if (c >= nvec) g[j][e] = 0.f; }
+  }
+  for (int64_t row = (int64_t)b * 4 + wave; row < T; row += (int64_t)4 * B) {
+    const float rstd = stats[row];
+    const float mean = KIND == 0 ? stats[T + row] : 0.f;
+    float xh[NV][8], dxh[NV][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      const int c = lane + 64 * j;
+#pragma unroll
+      for (int e = 0; e < 8; e++) { xh[j][e] = 0.f; dxh[j][e] = 0.f; }
+      if (c < nvec) {
+        float xv[8], dv[8];
+        unpack8(*reinterpret_cast<const uint4*>(x + row * d + 8 * c), xv);
+        unpack8(*reinterpret_cast<const uint4*>(dy + row * d + 8 * c), dv);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          xh[j][e] = (xv[e] - mean) * rstd;
+          dxh[j][e] = dv[e] * g[j][e];
+          s1 += dxh[j][e];
+          s2 += dxh[j][e] * xh[j][e];
+          dg[j][e] += dv[e] * xh[j][e];
+          db[j][e] += dv[e];
+        }
+      }
+    }
+    const float m2 = wave_sum(s2) / (float)d;
+    const float m1 = KIND == 0 ? wave_sum(s1) / (float)d : 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float o[8], r[8];
+        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * d + 8 * c), r);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd;
+          if (dres) o[e] += r[e];
+        }
+        *reinterpret_cast<uint4*>(dx + row * d + 8 * c) = pack8(o);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) { red[0][wave][8 * c + e] = dg[j][e]; red[1][wave][8 * c + e] = db[j][e]; }
+    }
+  }
+  __syncthreads();
+  for (int col = tid; col < d; col += 256) {
+    partial[(int64_t)b * d + col] = (red[0][0][col] + red[0][1][col]) + (red[0][2][col] + red[0][3][col]);
+    if (KIND == 0)
+      partial[(int64_t)(B + b) * d + col] = (red[1][0][col] + red[1][1][col]) + (red[1][2][col] + red[1][3][col]);
+  }
+}
+
 int64_t norm_bwd_partial_rows(int64_t t) {
   return t < 1 ? 1 : (t > 1024 ? 1024 : t);
 }
@@ -406,7 +483,14 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
   else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
   const int64_t nvec = d / 8;
-  if (nvec <= 256) { CALL(1) } else if (nvec <= 512) { CALL(2) } else { CALL(4) }
+#define CALL_WAVE(NV)                                                                                   \
+  if (kind == 0) hipLaunchKernelGGL((norm_bwd_wave_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d); \
+  else hipLaunchKernelGGL((norm_bwd_wave_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
+  if (nvec <= 64) { CALL_WAVE(1) } else if (nvec <= 128) { CALL_WAVE(2) }
+  else if (nvec <= 256) { CALL(1) } else if (nvec <= 512) { CALL(2) } else { CALL(4) }
+#undef CALL_WAVE
 #undef CALL
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
