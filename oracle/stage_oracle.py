@@ -357,9 +357,41 @@ def decoder_layer_bwd(L, P, C, dy, cu, mask_kind):
     return dx, [d_g1, d_wqkv, d_wo, d_g2, d_wgu, d_wd]
 
 
-def projector_fwd(L, P, x):
+def pool_windows(cu, pool):
+    """(first row, row count) of every pooling window: consecutive windows of `pool` rows inside
+    each segment, the last one of a segment shorter when the length is no multiple."""
+    out = []
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        for r in range(a, b, pool):
+            out.append((r, min(pool, b - r)))
+    return out
+
+
+def pool_fwd(x, cu, pool):
+    """Average pooling at the end of the encoder (Evaluation, audio modality): row j of the result
+    is the mean of the encoder rows of window j."""
+    return np.stack([x[r:r + n].sum(axis=0) / n for r, n in pool_windows(cu, pool)]) if len(cu) > 1 and cu[-1] > 0 \
+        else np.zeros((0, x.shape[1]))
+
+
+def pool_bwd(dp, cu, pool, rows):
+    dx = np.zeros((rows, dp.shape[1]))
+    for j, (r, n) in enumerate(pool_windows(cu, pool)):
+        dx[r:r + n] = dp[j] / n
+    return dx
+
+
+def projector_fwd(L, P, x, cu=None):
     """Connector (MLLM Architecture: a linear projector or a multi-layer perceptron):
-    p = x.Wp + bp, or p = act(x.W1 + b1).W2 + b2 when the layer has a hidden width."""
+    p = x.Wp + bp, or p = act(x.W1 + b1).W2 + b2 when the layer has a hidden width; with
+    pool > 1 the encoder rows are average-pooled first."""
+    if getattr(L, "pool", 0) > 1:
+        pooled = pool_fwd(x, cu, L.pool)
+        plain = type(L)(**{**L.__dict__, "pool": 0})
+        y, c = projector_fwd(plain, P, pooled)
+        c["rows"] = x.shape[0]
+        return y, c
     if L.d_ff:
         w1, b1, w2, b2 = P
         h = x @ w1 + b1
@@ -368,7 +400,11 @@ def projector_fwd(L, P, x):
     return x @ P[0] + P[1], dict(x=x)
 
 
-def projector_bwd(L, P, C, dp):
+def projector_bwd(L, P, C, dp, cu=None):
+    if getattr(L, "pool", 0) > 1:
+        plain = type(L)(**{**L.__dict__, "pool": 0})
+        dpooled, g = projector_bwd(plain, P, C, dp)
+        return pool_bwd(dpooled, cu, L.pool, C["rows"]), g
     if L.d_ff:
         w1, _b1, w2, _b2 = P
         da = dp @ w2.T
@@ -402,7 +438,7 @@ def stage_fwd(layers, params, batch, x_img=None, x_seq=None):
         if L.kind == LAYER_VIT:
             cur_img, c = vit_layer_fwd(L, P, cur_img, batch.img.cu_seqlens, batch.img.mask_kind)
         elif L.kind == LAYER_PROJECTOR:
-            proj, c = projector_fwd(L, P, cur_img)
+            proj, c = projector_fwd(L, P, cur_img, batch.img.cu_seqlens)
             cur_seq[np.asarray(batch.img_to_seq_row, dtype=np.int64), :] = proj
             in_seq_space = True
         else:
@@ -435,7 +471,7 @@ def stage_bwd(layers, params, batch, caches, dy):
             dproj = d[rows, :]
             dx_seq = d.copy()
             dx_seq[rows, :] = 0.0
-            d, g = projector_bwd(L, P, C, dproj)
+            d, g = projector_bwd(L, P, C, dproj, batch.img.cu_seqlens)
         else:
             d, g = vit_layer_bwd(L, P, C, d, batch.img.cu_seqlens, batch.img.mask_kind)
         for j, gj in enumerate(g):

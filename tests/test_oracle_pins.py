@@ -266,9 +266,9 @@ def _fwd(wl, params=None, x_img=None, x_seq=None):
                        wl.x_seq if x_seq is None else x_seq)
 
 
-@pytest.mark.parametrize("seed,variant", [(0, False), (3, False), (1, True)])
+@pytest.mark.parametrize("seed,variant", [(0, 0), (3, 0), (1, 1), (2, 2)])
 def test_stage_gradients_by_central_differences(seed, variant):
-    wl = W.workload_tiny_variant(seed) if variant else _tiny(seed)
+    wl = (_tiny, W.workload_tiny_variant, W.workload_tiny_pooled)[variant](seed)
     y, caches = _fwd(wl)
     dy = wl.dy.astype(np.float64)
     dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, dy)
@@ -508,3 +508,34 @@ def test_variant_reductions():
     eye = np.eye(320, 256)
     p, _ = O.projector_fwd(proj, [w1, b1, eye, np.zeros((1, 256))], xi)
     assert np.allclose(p, O.gelu_erf(xi @ w1 + b1)[:, :256], rtol=0, atol=1e-15)
+
+
+def test_pooling_is_the_averaging_matrix():
+    """Average pooling against an explicit [windows x rows] averaging matrix built here; backward is
+    its transpose; pool = 1 is the identity; a ragged last window averages what it has."""
+    cu = np.array([0, 7, 7, 12, 13])
+    x = _rand(13, 5)
+    A = np.zeros((0, 13))
+    for s in range(4):
+        a, b = cu[s], cu[s + 1]
+        for r in range(a, b, 3):
+            row = np.zeros(13)
+            row[r:min(r + 3, b)] = 1.0 / (min(r + 3, b) - r)
+            A = np.vstack([A, row])
+    assert A.shape[0] == 3 + 0 + 2 + 1
+    assert np.allclose(O.pool_fwd(x, cu, 3), A @ x, rtol=0, atol=1e-15)
+    dp = _rand(A.shape[0], 5)
+    assert np.allclose(O.pool_bwd(dp, cu, 3, 13), A.T @ dp, rtol=0, atol=1e-15)
+    assert np.array_equal(O.pool_fwd(x, cu, 1), x)
+    assert np.allclose(O.pool_fwd(x, cu, 3)[2], (x[6] + 0) / 1)            # rows 6..6: the 7-row segment's tail
+
+
+def test_pooled_connector_equals_connector_on_pooled_rows():
+    wl = W.workload_tiny_pooled(3)
+    proj = wl.layers[1]
+    P = [p.astype(np.float64) for p in wl.params[12:14]]
+    x = wl.x_img.astype(np.float64)
+    y, _ = O.projector_fwd(proj, P, x, wl.batch.img.cu_seqlens)
+    assert y.shape[0] == 2 * 17 == len(wl.batch.img_to_seq_row)
+    ref = np.stack([x[50 * c + 3 * j:min(50 * c + 3 * j + 3, 50 * (c + 1))].mean(axis=0) for c in range(2) for j in range(17)])
+    assert np.allclose(y, ref @ P[0] + P[1], rtol=0, atol=1e-13)

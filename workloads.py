@@ -67,6 +67,7 @@ class LayerDesc:
     has_bias: int = 0
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
+    pool: int = 0           # projector: average-pool this many consecutive encoder tokens first (0/1: none)
 
 
 def vit_layer(d, heads, head_dim, d_ff, eps=1e-5, act=ACT_GELU_ERF) -> LayerDesc:
@@ -78,10 +79,11 @@ def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5, qkv_bias=0) -
     return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, qkv_bias, eps, rope_base)
 
 
-def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF) -> LayerDesc:
+def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF, pool=0) -> LayerDesc:
     """d_hidden = 0: one biased linear map; otherwise a two-layer MLP d_in -> d_hidden -> d_out
-    with a GELU in between (d_ff carries d_hidden)."""
-    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, d_hidden, d_out, act if d_hidden else 0, 1, 0.0, 0.0)
+    with a GELU in between (d_ff carries d_hidden).  pool > 1: every `pool` consecutive encoder
+    tokens of a segment are averaged first, so fewer tokens reach the LLM."""
+    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, d_hidden, d_out, act if d_hidden else 0, 1, 0.0, 0.0, pool)
 
 
 def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
@@ -168,16 +170,19 @@ class Batch:
 
 
 def batch_from_samples(samples: Sequence[Tuple[int, int]], img_tokens: int = IMG_TOKENS,
-                       with_images: bool = True) -> Batch:
-    """Pack samples of (n_images, n_text_tokens): image tokens first (image-major), then text."""
-    seq_lens = [k * img_tokens + t for k, t in samples]
+                       with_images: bool = True, pool: int = 1) -> Batch:
+    """Pack samples of (n_images, n_text_tokens): image tokens first (image-major), then text.
+    With a pooling connector every image (or audio clip) of `img_tokens` encoder tokens takes
+    ceil(img_tokens / pool) rows of the LLM sequence."""
+    llm_tokens = -(-img_tokens // max(pool, 1))
+    seq_lens = [k * llm_tokens + t for k, t in samples]
     seq = make_pack(seq_lens, MASK_CAUSAL)
     n_img = sum(k for k, _ in samples)
     img = make_pack([img_tokens] * n_img, MASK_BIDIR)
     rows = []
     for s, (k, _t) in enumerate(samples):
         base = int(seq.cu_seqlens[s])
-        rows.append(np.arange(base, base + k * img_tokens, dtype=np.int32))
+        rows.append(np.arange(base, base + k * llm_tokens, dtype=np.int32))
     i2s = np.concatenate(rows) if rows else np.zeros(0, dtype=np.int32)
     i2s = i2s.astype(np.int32)
     if not with_images:
@@ -306,6 +311,21 @@ def workload_tiny_variant(seed: int) -> Workload:
     samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
     batch = batch_from_samples(samples, img_tokens=64)
     return make_workload("tiny_variant", tiny_variant_layers(), batch, seed)
+
+
+def tiny_pooled_layers() -> List[LayerDesc]:
+    """Encoder layer, a connector that averages 3 consecutive encoder tokens before its linear map
+    (the audio-language setting of the paper's evaluation), decoder layer."""
+    return [vit_layer(192, 3, 64, 768), projector_layer(192, 256, pool=3),
+            decoder_layer(256, 4, 4, 64, 1024, 10000.0)]
+
+
+def workload_tiny_pooled(seed: int) -> Workload:
+    """2 samples x (one clip of 50 encoder tokens -> 17 LLM rows, the last window holds 2) + text."""
+    rng = np.random.default_rng(seed)
+    samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
+    batch = batch_from_samples(samples, img_tokens=50, pool=3)
+    return make_workload("tiny_pooled", tiny_pooled_layers(), batch, seed)
 
 
 def workload_tiny(seed: int) -> Workload:
