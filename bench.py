@@ -56,6 +56,9 @@ def build_workload(name: str):
     elif name == "variant_stage_16k":
         wl = W.workload_variant_stage(410, 16384, with_data=False)
         desc = "tanh-GELU ViT-L layer + MLP connector 1024->3584->3584 + QKV-bias 7B-shaped decoder layer, 16384-token microbatch, seed 410"
+    elif name == "audio_stage":
+        wl = W.workload_audio_stage(600, with_data=False)
+        desc = "audio-language stand-in: 4 encoder layers (d 1280, 20 heads, MLP 5120) on 16 clips of 1500 tokens + pooling connector (pairs, 1280->3584) + 2 QKV-bias 7B-shaped decoder layers"
     elif name == "vit_l":
         wl = W.workload_vit_l(100, with_data=False)
         desc = "one ViT-L/14-336 layer, 16 samples x 1..4 images of 576 tokens, seed 100"

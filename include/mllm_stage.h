@@ -68,7 +68,12 @@ enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
  *   PROJECTOR: p = x.W_p + b_p, or with a hidden width d_ff > 0 the two-layer perceptron
  *              p = GELU(x.W_p1 + b_p1).W_p2 + b_p2; row i of p is written to row img_to_seq_row[i]
  *              of the packed sequence (the learnable connector of Section 2.1, which names linear
- *              projectors and multi-layer perceptrons).
+ *              projectors and multi-layer perceptrons).  With pool = r > 1 the encoder rows are
+ *              average-pooled first (Evaluation, audio modality: pooling at the end of the encoder
+ *              reduces the tokens fed to the LLM): inside every img segment, consecutive windows of
+ *              r rows are replaced by their mean, a shorter last window by the mean of what it
+ *              holds; the connector then has sum over segments of ceil(length / r) rows, and
+ *              img_to_seq_row has that many entries.
  * Parameter tensors per layer, in order (all bf16, matrices [in, out], vectors [n]):
  *   VIT:       ln1_g, ln1_b, w_qkv [d, 3d], b_qkv, w_o [d, d], b_o, ln2_g, ln2_b,
  *              w_1 [d, f], b_1, w_2 [f, d], b_2
@@ -93,6 +98,8 @@ typedef struct {
   int32_t has_bias;   /* 1 for VIT / PROJECTOR; DECODER: 0, or 1 = QKV bias */
   float norm_eps;
   float rope_base;    /* DECODER only                                   */
+  int32_t pool;       /* PROJECTOR only: average this many consecutive encoder tokens of a segment
+                         before the connector's map (0 or 1: none)  */
 } mllm_layer_desc_t;
 
 /* Layers in execution order: zero or more VIT, then at most one PROJECTOR, then zero or more

@@ -334,6 +334,41 @@ __global__ void scatter_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __re
   if (gather) reinterpret_cast<uint4*>(dst)[r * vec_per_row + c] = reinterpret_cast<const uint4*>(src)[other * vec_per_row + c];
   else reinterpret_cast<uint4*>(dst)[other * vec_per_row + c] = reinterpret_cast<const uint4*>(src)[r * vec_per_row + c];
 }
+// Average pooling at the end of the encoder (Evaluation, audio modality) and its gradient.
+__global__ void pool_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                 const int32_t* __restrict__ first, const int32_t* __restrict__ count,
+                                 int64_t n_out, int64_t vec_per_row) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_out * vec_per_row) return;
+  const int64_t j = i / vec_per_row, c = i % vec_per_row;
+  const int64_t r0 = first[j];
+  const int n = count[j];
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < n; r++) {
+    float v[8];
+    unpack8(reinterpret_cast<const uint4*>(src)[(r0 + r) * vec_per_row + c], v);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] += v[e];
+  }
+  const float inv = 1.f / (float)n;
+#pragma unroll
+  for (int e = 0; e < 8; e++) acc[e] *= inv;
+  reinterpret_cast<uint4*>(dst)[j * vec_per_row + c] = pack8(acc);
+}
+__global__ void unpool_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                   const int32_t* __restrict__ window, const int32_t* __restrict__ count,
+                                   int64_t n_rows, int64_t vec_per_row) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_rows * vec_per_row) return;
+  const int64_t r = i / vec_per_row, c = i % vec_per_row;
+  const int64_t j = window[r];
+  float v[8];
+  unpack8(reinterpret_cast<const uint4*>(src)[j * vec_per_row + c], v);
+  const float inv = 1.f / (float)count[j];
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] *= inv;
+  reinterpret_cast<uint4*>(dst)[r * vec_per_row + c] = pack8(v);
+}
 __global__ void zero_rows_kernel(bf16_t* __restrict__ dst, const int32_t* __restrict__ rows,
                                  int64_t n_rows, int64_t vec_per_row) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -568,6 +603,28 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, 
   ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n_rows * (double)d, s);
   hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s,
                      (const bf16_t*)src, (bf16_t*)dst, rows, n_rows, d / 8, gather);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_rows(const void* src, void* dst, const int32_t* first, const int32_t* count,
+                            int64_t n_out, int64_t d, hipStream_t s) {
+  if (n_out == 0) return hipSuccess;
+  if (d % 8 != 0) return hipErrorInvalidValue;
+  const int64_t n = n_out * (d / 8);
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n_out * (double)d, s);
+  hipLaunchKernelGGL(pool_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const bf16_t*)src,
+                     (bf16_t*)dst, first, count, n_out, d / 8);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpool_rows(const void* src, void* dst, const int32_t* window, const int32_t* count,
+                              int64_t n_rows, int64_t d, hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  if (d % 8 != 0) return hipErrorInvalidValue;
+  const int64_t n = n_rows * (d / 8);
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n_rows * (double)d, s);
+  hipLaunchKernelGGL(unpool_rows_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (const bf16_t*)src,
+                     (bf16_t*)dst, window, count, n_rows, d / 8);
   return hipGetLastError();
 }
 

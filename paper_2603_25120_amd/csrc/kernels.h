@@ -72,6 +72,12 @@ hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate,
 // dst[rows[i], :] = src[i, :] (scatter) or dst[i, :] = src[rows[i], :] (gather); bf16 rows of d.
 hipError_t launch_scatter_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows,
                                int64_t d, int gather, hipStream_t s);
+// dst[j, :] = mean of src[first[j] .. first[j] + count[j]) (bf16 rows of d, fp32 sum).
+hipError_t launch_pool_rows(const void* src, void* dst, const int32_t* first, const int32_t* count,
+                            int64_t n_out, int64_t d, hipStream_t s);
+// dst[i, :] = src[window[i], :] / count[window[i]]: the gradient of launch_pool_rows.
+hipError_t launch_unpool_rows(const void* src, void* dst, const int32_t* window, const int32_t* count,
+                              int64_t n_rows, int64_t d, hipStream_t s);
 // Zero the rows named by rows[] of a bf16 [*, d] matrix.
 hipError_t launch_zero_rows(void* dst, const int32_t* rows, int64_t n_rows, int64_t d,
                             hipStream_t s);

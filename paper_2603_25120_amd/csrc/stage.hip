@@ -79,6 +79,7 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
   if (L.kind == MLLM_LAYER_PROJECTOR) {
     if (!m64(L.d_model) || !m64(L.d_out)) return fail(MLLM_ERR_DESC, "layer %d: projector widths must be positive multiples of 64", i);
     if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: projector needs has_bias = 1", i);
+    if (L.pool < 0 || L.pool > 64) return fail(MLLM_ERR_DESC, "layer %d: the connector's pooling width must be in 0..64", i);
     if (L.d_ff != 0) {
       if (!m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: the connector's hidden width must be 0 or a positive multiple of 64", i);
       if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: an MLP connector's activation must be GELU", i);
@@ -123,6 +124,16 @@ mllm_status_t check_pack(const mllm_pack_t& p, const char* what) {
   return MLLM_OK;
 }
 
+// Rows the connector produces: the encoder rows, or with pooling the windows of every segment.
+int64_t connector_rows(const mllm_stage* st, const mllm_batch_t* b) {
+  const int pool = st->proj >= 0 ? st->layers[st->proj].pool : 0;
+  if (pool <= 1) return b->img.total_tokens;
+  int64_t n = 0;
+  for (int s = 0; s < b->img.n_segments; s++)
+    n += (b->img.cu_seqlens_host[s + 1] - b->img.cu_seqlens_host[s] + pool - 1) / pool;
+  return n;
+}
+
 mllm_status_t check_batch(const mllm_stage* st, const mllm_batch_t* b) {
   if (!st || !b) return fail(MLLM_ERR_NULL, "stage or batch is NULL");
   mllm_status_t r;
@@ -131,12 +142,13 @@ mllm_status_t check_batch(const mllm_stage* st, const mllm_batch_t* b) {
   if (need_img && (r = check_pack(b->img, "img")) != MLLM_OK) return r;
   if (need_seq && (r = check_pack(b->seq, "seq")) != MLLM_OK) return r;
   if (st->proj >= 0) {
-    if (b->img.total_tokens > 0 && !b->img_to_seq_row_host) return fail(MLLM_ERR_NULL, "img_to_seq_row_host is NULL");
+    const int64_t n_con = connector_rows(st, b);
+    if (n_con > 0 && !b->img_to_seq_row_host) return fail(MLLM_ERR_NULL, "img_to_seq_row_host is NULL");
     int64_t prev = -1;
-    for (int i = 0; i < b->img.total_tokens; i++) {
+    for (int64_t i = 0; i < n_con; i++) {
       int32_t r0 = b->img_to_seq_row_host[i];
-      if (r0 < 0 || r0 >= b->seq.total_tokens) return fail(MLLM_ERR_INDEX, "img_to_seq_row[%d] = %d out of range", i, r0);
-      if (r0 <= prev) return fail(MLLM_ERR_INDEX, "img_to_seq_row not strictly increasing at %d", i);
+      if (r0 < 0 || r0 >= b->seq.total_tokens) return fail(MLLM_ERR_INDEX, "img_to_seq_row[%lld] = %d out of range", (long long)i, r0);
+      if (r0 <= prev) return fail(MLLM_ERR_INDEX, "img_to_seq_row not strictly increasing at %lld", (long long)i);
       prev = r0;
     }
   }
@@ -162,6 +174,7 @@ struct LayerSaved {  // byte offsets into `saved`
 
 struct Meta {  // byte offsets into the metadata blob at the head of the workspace
   size_t img_q_tiles = 0, img_kv_tiles = 0, seq_q_tiles = 0, seq_kv_tiles = 0, pos = 0, i2s = 0;
+  size_t pool_first = 0, pool_count = 0, row_window = 0;   // pooling connector: window tables
   int n_img_q = 0, n_img_kv = 0, n_seq_q = 0, n_seq_kv = 0;
   size_t bytes = 0;
 };
@@ -185,6 +198,8 @@ struct Plan {
   size_t split_bytes = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
+  int64_t T_con = 0;              // rows of the connector (T_img, or the pooling windows)
+  int pool = 1;
   int64_t largest_operand_bytes = 0;   // largest [tokens, width] bf16 matrix any GEMM of the stage reads
   double img_pairs = 0, seq_pairs = 0;  // sum over segments of visible (query, key) pairs
 };
@@ -204,6 +219,10 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   const bool need_seq = st->n_dec > 0 || st->proj >= 0;
   P.T_img = need_img ? b->img.total_tokens : 0;
   P.T_seq = need_seq ? b->seq.total_tokens : 0;
+  if (st->proj >= 0) {
+    P.pool = std::max(1, (int)st->layers[st->proj].pool);
+    P.T_con = connector_rows(st, b);
+  }
   if (st->n_vit > 0) P.img_pairs = visible_pairs(b->img);
   if (st->n_dec > 0) P.seq_pairs = visible_pairs(b->seq);
   Bump sv;
@@ -213,10 +232,11 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     LayerSaved& S = P.saved[i];
     memset(&S, 0, sizeof S);
     if (L.kind == MLLM_LAYER_PROJECTOR) {
-      S.x = sv.take((size_t)P.T_img * L.d_model * 2);   // connector input
+      S.x = sv.take((size_t)P.T_img * L.d_model * 2);   // encoder output
+      if (P.pool > 1) S.n1 = sv.take((size_t)P.T_con * L.d_model * 2);   // its pooled rows: the connector's input
       if (L.d_ff) {                                      // MLP connector: hidden pre-activation and activation
-        S.pre = sv.take((size_t)P.T_img * L.d_ff * 2);
-        S.act = sv.take((size_t)P.T_img * L.d_ff * 2);
+        S.pre = sv.take((size_t)P.T_con * L.d_ff * 2);
+        S.act = sv.take((size_t)P.T_con * L.d_ff * 2);
       }
       continue;
     }
@@ -251,22 +271,28 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     M.seq_kv_tiles = ws.take(sizeof(AttnTile) * M.n_seq_kv);
     M.pos = ws.take(sizeof(int32_t) * P.T_seq);
   }
-  if (st->proj >= 0) M.i2s = ws.take(sizeof(int32_t) * P.T_img);
+  if (st->proj >= 0) M.i2s = ws.take(sizeof(int32_t) * P.T_con);
+  if (st->proj >= 0 && P.pool > 1) {
+    M.pool_first = ws.take(sizeof(int32_t) * P.T_con);
+    M.pool_count = ws.take(sizeof(int32_t) * P.T_con);
+    M.row_window = ws.take(sizeof(int32_t) * P.T_img);
+  }
   M.bytes = ws.off;
 
   size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0, split = 0;
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
-      proj = (size_t)P.T_img * L.d_out * 2;
+      proj = (size_t)P.T_con * L.d_out * 2;
       P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)P.T_img * std::max(std::max(L.d_model, L.d_out), L.d_ff) * 2);
       if (L.d_ff) {
-        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_ff, P.T_img));
-        split = std::max(split, gemm_splitk_ws_bytes(L.d_ff, L.d_out, P.T_img));
-        a = std::max(a, (size_t)P.T_img * L.d_ff * 2);
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_ff, P.T_con));
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_ff, L.d_out, P.T_con));
+        a = std::max(a, (size_t)P.T_con * L.d_ff * 2);
       } else {
-        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_img));
+        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_con));
       }
-      part = std::max(part, (size_t)colsum_partial_rows(P.T_img) * std::max(L.d_out, L.d_ff) * 4);
+      if (P.pool > 1) c = std::max(c, (size_t)P.T_con * L.d_model * 2);   // gradient of the pooled rows
+      part = std::max(part, (size_t)colsum_partial_rows(P.T_con) * std::max(L.d_out, L.d_ff) * 4);
       g = std::max(g, (size_t)P.T_img * L.d_model * 2);
       g = std::max(g, (size_t)P.T_seq * L.d_out * 2);
       continue;
@@ -357,7 +383,21 @@ mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, 
       for (int t = b->seq.cu_seqlens_host[sgm]; t < b->seq.cu_seqlens_host[sgm + 1]; t++)
         pos[t] = t - b->seq.cu_seqlens_host[sgm];
   }
-  if (st->proj >= 0 && P.T_img > 0) memcpy(h + M.i2s, b->img_to_seq_row_host, sizeof(int32_t) * P.T_img);
+  if (st->proj >= 0 && P.T_con > 0) memcpy(h + M.i2s, b->img_to_seq_row_host, sizeof(int32_t) * P.T_con);
+  if (st->proj >= 0 && P.pool > 1) {
+    int32_t* first = (int32_t*)(h + M.pool_first);
+    int32_t* count = (int32_t*)(h + M.pool_count);
+    int32_t* window = (int32_t*)(h + M.row_window);
+    int64_t j = 0;
+    for (int sgm = 0; sgm < b->img.n_segments; sgm++) {
+      const int end = b->img.cu_seqlens_host[sgm + 1];
+      for (int r = b->img.cu_seqlens_host[sgm]; r < end; r += P.pool, j++) {
+        first[j] = r;
+        count[j] = std::min(P.pool, end - r);
+        for (int q = 0; q < count[j]; q++) window[r + q] = (int32_t)j;
+      }
+    }
+  }
   HIP_TRY(hipMemcpyAsync(workspace, h, M.bytes, hipMemcpyHostToDevice, s));
   HIP_TRY(hipEventRecord(st->upload_done, s));
   st->upload_pending = true;
@@ -665,16 +705,22 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       if (i == 0) K_TRY(launch_copy(x_img, saved + P.saved[i].x, (size_t)P.T_img * L.d_model * 2, s));
       void* dst = last ? y : (void*)(saved + P.saved[i + 1].x);
       K_TRY(launch_copy(x_seq, dst, (size_t)P.T_seq * L.d_out * 2, s));
+      const char* xin = saved + P.saved[i].x;
+      if (P.pool > 1) {   // average pooling at the end of the encoder
+        K_TRY(launch_pool_rows(xin, saved + P.saved[i].n1, (const int32_t*)(ws + P.meta.pool_first),
+                               (const int32_t*)(ws + P.meta.pool_count), P.T_con, L.d_model, s));
+        xin = saved + P.saved[i].n1;
+      }
       if (L.d_ff) {   // p = act(x.W1 + b1).W2 + b2
         char* pre = saved + P.saved[i].pre;
         char* act = saved + P.saved[i].act;
-        K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], pre, P.T_img, L.d_model, L.d_ff, prm[1], nullptr, s));
-        K_TRY(launch_act_fwd(L.act, pre, act, P.T_img, L.d_ff, s));
-        K_TRY(linear_fwd(act, prm[2], ws + P.w_proj, P.T_img, L.d_ff, L.d_out, prm[3], nullptr, s));
+        K_TRY(linear_fwd(xin, prm[0], pre, P.T_con, L.d_model, L.d_ff, prm[1], nullptr, s));
+        K_TRY(launch_act_fwd(L.act, pre, act, P.T_con, L.d_ff, s));
+        K_TRY(linear_fwd(act, prm[2], ws + P.w_proj, P.T_con, L.d_ff, L.d_out, prm[3], nullptr, s));
       } else {
-        K_TRY(linear_fwd(saved + P.saved[i].x, prm[0], ws + P.w_proj, P.T_img, L.d_model, L.d_out, prm[1], nullptr, s));
+        K_TRY(linear_fwd(xin, prm[0], ws + P.w_proj, P.T_con, L.d_model, L.d_out, prm[1], nullptr, s));
       }
-      K_TRY(launch_scatter_rows(ws + P.w_proj, dst, (const int32_t*)(ws + P.meta.i2s), P.T_img, L.d_out, 0, s));
+      K_TRY(launch_scatter_rows(ws + P.w_proj, dst, (const int32_t*)(ws + P.meta.i2s), P.T_con, L.d_out, 0, s));
       continue;
     }
     const bool vit = L.kind == MLLM_LAYER_VIT;
@@ -715,30 +761,35 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       const int32_t* i2s = (const int32_t*)(ws + P.meta.i2s);
       char* dproj = ws + P.w_proj;
-      K_TRY(launch_scatter_rows(cur, dproj, i2s, P.T_img, L.d_out, 1, s));
+      K_TRY(launch_scatter_rows(cur, dproj, i2s, P.T_con, L.d_out, 1, s));
       if (dx_seq) {
         K_TRY(launch_copy(cur, dx_seq, (size_t)P.T_seq * L.d_out * 2, s));
-        K_TRY(launch_zero_rows(dx_seq, i2s, P.T_img, L.d_out, s));
+        K_TRY(launch_zero_rows(dx_seq, i2s, P.T_con, L.d_out, s));
       }
       const SplitWs split{ws + P.w_split, P.split_bytes};
       float* partial = (float*)(ws + P.w_partial);
       void* out = (i == 0 && dx_img) ? dx_img : (void*)pp[flip];
+      const char* xin = P.pool > 1 ? saved + P.saved[i].n1 : saved + P.saved[i].x;
+      void* dxin = P.pool > 1 ? (void*)(ws + P.w_c) : out;   // gradient of the connector's input rows
       if (L.d_ff) {
         const char* pre = saved + P.saved[i].pre;
         const char* act = saved + P.saved[i].act;
-        char* dh = ws + P.w_a;     // d act, then d pre in place   [T_img, d_ff]
-        K_TRY(linear_dw(act, dproj, dprm[2], P.T_img, L.d_ff, L.d_out, accumulate, s, split));
-        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[3], accumulate, partial, P.T_img, L.d_out, s));
-        K_TRY(linear_dx(dproj, prm[2], dh, P.T_img, L.d_ff, L.d_out, s));
-        K_TRY(launch_act_bwd(L.act, dh, pre, dh, P.T_img, L.d_ff, s));
-        K_TRY(linear_dw(saved + P.saved[i].x, dh, dprm[0], P.T_img, L.d_model, L.d_ff, accumulate, s, split));
-        K_TRY(launch_colsum(dh, L.d_ff, (float*)dprm[1], accumulate, partial, P.T_img, L.d_ff, s));
-        K_TRY(linear_dx(dh, prm[0], out, P.T_img, L.d_model, L.d_ff, s));
+        char* dh = ws + P.w_a;     // d act, then d pre in place   [T_con, d_ff]
+        K_TRY(linear_dw(act, dproj, dprm[2], P.T_con, L.d_ff, L.d_out, accumulate, s, split));
+        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[3], accumulate, partial, P.T_con, L.d_out, s));
+        K_TRY(linear_dx(dproj, prm[2], dh, P.T_con, L.d_ff, L.d_out, s));
+        K_TRY(launch_act_bwd(L.act, dh, pre, dh, P.T_con, L.d_ff, s));
+        K_TRY(linear_dw(xin, dh, dprm[0], P.T_con, L.d_model, L.d_ff, accumulate, s, split));
+        K_TRY(launch_colsum(dh, L.d_ff, (float*)dprm[1], accumulate, partial, P.T_con, L.d_ff, s));
+        K_TRY(linear_dx(dh, prm[0], dxin, P.T_con, L.d_model, L.d_ff, s));
       } else {
-        K_TRY(linear_dw(saved + P.saved[i].x, dproj, dprm[0], P.T_img, L.d_model, L.d_out, accumulate, s, split));
-        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, partial, P.T_img, L.d_out, s));
-        K_TRY(linear_dx(dproj, prm[0], out, P.T_img, L.d_model, L.d_out, s));
+        K_TRY(linear_dw(xin, dproj, dprm[0], P.T_con, L.d_model, L.d_out, accumulate, s, split));
+        K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, partial, P.T_con, L.d_out, s));
+        K_TRY(linear_dx(dproj, prm[0], dxin, P.T_con, L.d_model, L.d_out, s));
       }
+      if (P.pool > 1)
+        K_TRY(launch_unpool_rows(dxin, out, (const int32_t*)(ws + P.meta.row_window),
+                                 (const int32_t*)(ws + P.meta.pool_count), P.T_img, L.d_model, s));
       cur = out;
       flip ^= 1;
       continue;

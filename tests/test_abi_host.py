@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_param_table_matches_the_generator(B):
     for layers in (W.tiny_stage_layers(), W.full_stage_layers(2, 2), [W.dec7b_layer()], [W.vit_l_layer()],
-                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()]):
+                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()], W.tiny_pooled_layers()):
         h = B.mllm_stage_create(layers)
         got = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
         want = [(n, li, r, c) for li, L in enumerate(layers) for n, r, c in W.param_specs(L)]
@@ -65,6 +65,7 @@ def test_descriptor_validation(B):
         [_bad(dec, has_bias=2)],                                   # decoder: 0, or 1 for a QKV bias
         [vit, _bad(proj, d_ff=100), dec],                          # connector hidden width not a multiple of 64
         [vit, _bad(proj, d_ff=128, act=W.ACT_SWIGLU), dec],        # MLP connector needs a GELU
+        [vit, _bad(proj, pool=-1), dec],                           # pooling width out of range
         [],
     ]
     for layers in cases:
@@ -209,3 +210,23 @@ def test_microbatch_beyond_the_addressing_limit_is_refused(B):
         B.mllm_stage_sizes(h, too_big)
     assert e.value.status == 3 and "too large" in str(e.value)
     B.mllm_stage_destroy(h)
+
+
+def test_pooling_connector_row_count(B):
+    """With pool = 3 the connector has ceil(length / 3) rows per encoder segment, and that is how
+    many entries img_to_seq_row must have (one more or one fewer entry in range is an error only
+    when it breaks the ordering or the range; a NULL table is refused)."""
+    wl = W.workload_tiny_pooled(0)
+    h = B.mllm_stage_create(wl.layers)
+    try:
+        assert len(wl.batch.img_to_seq_row) == 2 * 17
+        sb, wb = B.mllm_stage_sizes(h, wl.batch)
+        plain = B.mllm_stage_create(W.tiny_stage_layers())
+        assert sb > 0 and wb > 0
+        B.mllm_stage_destroy(plain)
+        bad = W.Batch(wl.batch.img, wl.batch.seq, None, wl.batch.samples)
+        with pytest.raises(B.MllmError) as e:
+            B.mllm_stage_sizes(h, bad)
+        assert e.value.status == 1
+    finally:
+        B.mllm_stage_destroy(h)

@@ -44,6 +44,33 @@ def test_tiny_variant_stage_matches_oracle(B, seed):
         st.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_pooled_stage_matches_oracle(B, seed):
+    """Connector that averages 3 consecutive encoder tokens (ragged last window) before its map."""
+    wl = W.workload_tiny_pooled(seed)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+def test_pooled_mlp_connector_ragged_segments(B):
+    """Pooling by 4 over encoder segments of 1, 4, 9 and 130 tokens, MLP connector, image-only and
+    text-only samples."""
+    layers = [W.vit_layer(128, 2, 64, 256), W.projector_layer(128, 192, d_hidden=128, pool=4),
+              W.decoder_layer(192, 3, 1, 64, 320, 10000.0, qkv_bias=1)]
+    img_lens = [1, 4, 9, 130]
+    con = [-(-n // 4) for n in img_lens]                      # connector rows per encoder segment
+    seq_lens = [con[0] + 5, 40, con[1] + con[2], con[3] + 3]  # sample 1 is text only, sample 2 image only
+    seq = W.make_pack(seq_lens, W.MASK_CAUSAL)
+    cu = seq.cu_seqlens
+    rows = np.concatenate([np.arange(cu[0], cu[0] + con[0]), np.arange(cu[2], cu[2] + con[1] + con[2]),
+                           np.arange(cu[3], cu[3] + con[3])]).astype(np.int32)
+    batch = W.Batch(W.make_pack(img_lens, W.MASK_BIDIR), seq, rows, [])
+    _layer_case(B, layers, batch, 31)
+
+
 def test_tiny_stage_deterministic_and_accumulates(B):
     wl = W.workload_tiny(4)
     st = GpuStage(B, wl.layers)

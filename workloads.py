@@ -405,6 +405,18 @@ def workload_variant_stage(seed: int, budget: int = 4096, with_data=True) -> Wor
     return make_workload("variant_stage", layers, batch_from_samples(samples), seed, with_data)
 
 
+def workload_audio_stage(seed: int, n_clips: int = 16, with_data=True) -> Workload:
+    """Audio-language stand-in (Evaluation, audio modality): 4 encoder layers of width 1280 (20 heads
+    of 64, GELU MLP 5120) over clips of 1500 encoder tokens, a connector that average-pools pairs of
+    tokens and maps 1280 -> 3584, and 2 QKV-bias decoder layers of the 7B shape.  One clip plus
+    lognormal(median 200, sigma 0.8) text tokens per sample."""
+    rng = np.random.default_rng(seed)
+    samples = [(1, int(min(max(int(round(rng.lognormal(np.log(200.0), 0.8))), 1), 2048))) for _ in range(n_clips)]
+    layers = ([vit_layer(1280, 20, 64, 5120) for _ in range(4)] + [projector_layer(1280, 3584, pool=2)]
+              + [dec_qkvbias_7b_layer() for _ in range(2)])
+    return make_workload("audio_stage", layers, batch_from_samples(samples, img_tokens=1500, pool=2), seed, with_data)
+
+
 def full_stage_sweep() -> List[Tuple[int, int, str]]:
     """The 16 (seed, budget, mix) microbatches: 4 budgets x 2 mixes x 2 seeds."""
     out = []
