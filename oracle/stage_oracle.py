@@ -382,10 +382,30 @@ def pool_bwd(dp, cu, pool, rows):
     return dx
 
 
+def merge_fwd(x, cu, merge):
+    """Token merging: row j of the result is the concatenation of the encoder rows of window j
+    (consecutive windows of `merge` rows; every segment's length is a multiple of `merge`)."""
+    out = []
+    for r, n in pool_windows(cu, merge):
+        assert n == merge, "segment length is no multiple of the merge width"
+        out.append(np.concatenate([x[r + q] for q in range(merge)]))
+    return np.stack(out) if out else np.zeros((0, x.shape[1] * merge))
+
+
+def merge_bwd(dm, merge):
+    d = dm.shape[1] // merge
+    return np.stack([dm[j, q * d:(q + 1) * d] for j in range(dm.shape[0]) for q in range(merge)]) if dm.shape[0] \
+        else np.zeros((0, d))
+
+
 def projector_fwd(L, P, x, cu=None):
     """Connector (MLLM Architecture: a linear projector or a multi-layer perceptron):
     p = x.Wp + bp, or p = act(x.W1 + b1).W2 + b2 when the layer has a hidden width; with
     pool > 1 the encoder rows are average-pooled first."""
+    if getattr(L, "merge", 0) > 1:
+        merged = merge_fwd(x, cu, L.merge)
+        plain = type(L)(**{**L.__dict__, "merge": 0, "d_model": L.d_model * L.merge})
+        return projector_fwd(plain, P, merged)
     if getattr(L, "pool", 0) > 1:
         pooled = pool_fwd(x, cu, L.pool)
         plain = type(L)(**{**L.__dict__, "pool": 0})
@@ -401,6 +421,10 @@ def projector_fwd(L, P, x, cu=None):
 
 
 def projector_bwd(L, P, C, dp, cu=None):
+    if getattr(L, "merge", 0) > 1:
+        plain = type(L)(**{**L.__dict__, "merge": 0, "d_model": L.d_model * L.merge})
+        dmerged, g = projector_bwd(plain, P, C, dp)
+        return merge_bwd(dmerged, L.merge), g
     if getattr(L, "pool", 0) > 1:
         plain = type(L)(**{**L.__dict__, "pool": 0})
         dpooled, g = projector_bwd(plain, P, C, dp)

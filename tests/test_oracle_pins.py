@@ -266,9 +266,9 @@ def _fwd(wl, params=None, x_img=None, x_seq=None):
                        wl.x_seq if x_seq is None else x_seq)
 
 
-@pytest.mark.parametrize("seed,variant", [(0, 0), (3, 0), (1, 1), (2, 2)])
+@pytest.mark.parametrize("seed,variant", [(0, 0), (3, 0), (1, 1), (2, 2), (4, 3)])
 def test_stage_gradients_by_central_differences(seed, variant):
-    wl = (_tiny, W.workload_tiny_variant, W.workload_tiny_pooled)[variant](seed)
+    wl = (_tiny, W.workload_tiny_variant, W.workload_tiny_pooled, W.workload_tiny_merged)[variant](seed)
     y, caches = _fwd(wl)
     dy = wl.dy.astype(np.float64)
     dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, dy)
@@ -539,3 +539,16 @@ def test_pooled_connector_equals_connector_on_pooled_rows():
     assert y.shape[0] == 2 * 17 == len(wl.batch.img_to_seq_row)
     ref = np.stack([x[50 * c + 3 * j:min(50 * c + 3 * j + 3, 50 * (c + 1))].mean(axis=0) for c in range(2) for j in range(17)])
     assert np.allclose(y, ref @ P[0] + P[1], rtol=0, atol=1e-13)
+
+
+def test_token_merging_is_a_reshape():
+    """Concatenating r consecutive rows is the row-major reshape [T, d] -> [T / r, r d] when every
+    segment is a multiple of r; the backward is the inverse reshape."""
+    cu = np.array([0, 8, 8, 20])
+    x = _rand(20, 6)
+    m = O.merge_fwd(x, cu, 4)
+    assert np.array_equal(m, x.reshape(5, 24))
+    dm = _rand(5, 24)
+    assert np.array_equal(O.merge_bwd(dm, 4), dm.reshape(20, 6))
+    with pytest.raises(AssertionError):
+        O.merge_fwd(x, np.array([0, 7, 20]), 4)

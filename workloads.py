@@ -68,6 +68,7 @@ class LayerDesc:
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
     pool: int = 0           # projector: average-pool this many consecutive encoder tokens first (0/1: none)
+    merge: int = 0          # projector: concatenate this many consecutive encoder tokens into one row (0/1: none)
 
 
 def vit_layer(d, heads, head_dim, d_ff, eps=1e-5, act=ACT_GELU_ERF) -> LayerDesc:
@@ -79,11 +80,14 @@ def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5, qkv_bias=0) -
     return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, qkv_bias, eps, rope_base)
 
 
-def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF, pool=0) -> LayerDesc:
+def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF, pool=0, merge=0) -> LayerDesc:
     """d_hidden = 0: one biased linear map; otherwise a two-layer MLP d_in -> d_hidden -> d_out
     with a GELU in between (d_ff carries d_hidden).  pool > 1: every `pool` consecutive encoder
-    tokens of a segment are averaged first, so fewer tokens reach the LLM."""
-    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, d_hidden, d_out, act if d_hidden else 0, 1, 0.0, 0.0, pool)
+    tokens of a segment are averaged first, so fewer tokens reach the LLM; merge > 1: every `merge`
+    consecutive encoder tokens are concatenated into one row of width merge * d_in instead (token
+    merging of the pixel-shuffle kind: the caller orders the patches so that those to be merged
+    are adjacent)."""
+    return LayerDesc(LAYER_PROJECTOR, d_in, 0, 0, 0, d_hidden, d_out, act if d_hidden else 0, 1, 0.0, 0.0, pool, merge)
 
 
 def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
@@ -107,10 +111,11 @@ def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
         qkv = [("w_qkv", d, nqkv), ("b_qkv", 1, nqkv)] if layer.has_bias else [("w_qkv", d, nqkv)]
         return [("rms1_g", 1, d)] + qkv + [("w_o", no, d), ("rms2_g", 1, d), ("w_gu", d, 2 * f), ("w_d", f, d)]
     if layer.kind == LAYER_PROJECTOR:
+        d_in = d * max(1, layer.merge)
         if layer.d_ff:
-            return [("w_p1", d, layer.d_ff), ("b_p1", 1, layer.d_ff), ("w_p2", layer.d_ff, layer.d_out),
+            return [("w_p1", d_in, layer.d_ff), ("b_p1", 1, layer.d_ff), ("w_p2", layer.d_ff, layer.d_out),
                     ("b_p2", 1, layer.d_out)]
-        return [("w_p", d, layer.d_out), ("b_p", 1, layer.d_out)]
+        return [("w_p", d_in, layer.d_out), ("b_p", 1, layer.d_out)]
     raise ValueError("unknown layer kind")
 
 
@@ -326,6 +331,21 @@ def workload_tiny_pooled(seed: int) -> Workload:
     samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
     batch = batch_from_samples(samples, img_tokens=50, pool=3)
     return make_workload("tiny_pooled", tiny_pooled_layers(), batch, seed)
+
+
+def tiny_merged_layers() -> List[LayerDesc]:
+    """Encoder layer, an MLP connector over rows that concatenate 4 consecutive encoder tokens
+    (192 -> 768 wide), decoder layer."""
+    return [vit_layer(192, 3, 64, 768), projector_layer(192, 256, d_hidden=256, merge=4),
+            decoder_layer(256, 4, 4, 64, 1024, 10000.0)]
+
+
+def workload_tiny_merged(seed: int) -> Workload:
+    """2 samples x (one image of 64 encoder tokens -> 16 LLM rows) + text."""
+    rng = np.random.default_rng(seed)
+    samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
+    batch = batch_from_samples(samples, img_tokens=64, pool=4)
+    return make_workload("tiny_merged", tiny_merged_layers(), batch, seed)
 
 
 def workload_tiny(seed: int) -> Workload:
