@@ -73,7 +73,12 @@ enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
  *              reduces the tokens fed to the LLM): inside every img segment, consecutive windows of
  *              r rows are replaced by their mean, a shorter last window by the mean of what it
  *              holds; the connector then has sum over segments of ceil(length / r) rows, and
- *              img_to_seq_row has that many entries.
+ *              img_to_seq_row has that many entries.  With merge = r > 1 the connector instead
+ *              reads rows that concatenate r consecutive encoder rows (token merging of the
+ *              pixel-shuffle kind, Data Profiler: connectors that shorten the modality sequence; the
+ *              caller orders patches so that those to be merged are adjacent): every img segment
+ *              length must be a multiple of r, the connector has total / r rows of width r * d_model
+ *              and its first matrix is [r * d_model, .].
  * Parameter tensors per layer, in order (all bf16, matrices [in, out], vectors [n]):
  *   VIT:       ln1_g, ln1_b, w_qkv [d, 3d], b_qkv, w_o [d, d], b_o, ln2_g, ln2_b,
  *              w_1 [d, f], b_1, w_2 [f, d], b_2
@@ -100,6 +105,8 @@ typedef struct {
   float rope_base;    /* DECODER only                                   */
   int32_t pool;       /* PROJECTOR only: average this many consecutive encoder tokens of a segment
                          before the connector's map (0 or 1: none)  */
+  int32_t merge;      /* PROJECTOR only: concatenate this many consecutive encoder tokens of a segment
+                         into one connector row of width merge * d_model (0 or 1: none; not with pool) */
 } mllm_layer_desc_t;
 
 /* Layers in execution order: zero or more VIT, then at most one PROJECTOR, then zero or more

@@ -41,7 +41,8 @@ class LayerDescC(C.Structure):
     _fields_ = [("kind", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("has_bias", C.c_int32),
-                ("norm_eps", C.c_float), ("rope_base", C.c_float), ("pool", C.c_int32)]
+                ("norm_eps", C.c_float), ("rope_base", C.c_float), ("pool", C.c_int32),
+                ("merge", C.c_int32)]
 
 
 class StageDescC(C.Structure):

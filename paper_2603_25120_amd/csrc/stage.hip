@@ -80,6 +80,8 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
     if (!m64(L.d_model) || !m64(L.d_out)) return fail(MLLM_ERR_DESC, "layer %d: projector widths must be positive multiples of 64", i);
     if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: projector needs has_bias = 1", i);
     if (L.pool < 0 || L.pool > 64) return fail(MLLM_ERR_DESC, "layer %d: the connector's pooling width must be in 0..64", i);
+    if (L.merge < 0 || L.merge > 64) return fail(MLLM_ERR_DESC, "layer %d: the connector's merge width must be in 0..64", i);
+    if (L.merge > 1 && L.pool > 1) return fail(MLLM_ERR_DESC, "layer %d: a connector either pools or merges", i);
     if (L.d_ff != 0) {
       if (!m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: the connector's hidden width must be 0 or a positive multiple of 64", i);
       if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: an MLP connector's activation must be GELU", i);
@@ -127,6 +129,8 @@ mllm_status_t check_pack(const mllm_pack_t& p, const char* what) {
 // Rows the connector produces: the encoder rows, or with pooling the windows of every segment.
 int64_t connector_rows(const mllm_stage* st, const mllm_batch_t* b) {
   const int pool = st->proj >= 0 ? st->layers[st->proj].pool : 0;
+  const int merge = st->proj >= 0 ? st->layers[st->proj].merge : 0;
+  if (merge > 1) return b->img.total_tokens / merge;   // every segment is a multiple (check_batch)
   if (pool <= 1) return b->img.total_tokens;
   int64_t n = 0;
   for (int s = 0; s < b->img.n_segments; s++)
@@ -142,6 +146,11 @@ mllm_status_t check_batch(const mllm_stage* st, const mllm_batch_t* b) {
   if (need_img && (r = check_pack(b->img, "img")) != MLLM_OK) return r;
   if (need_seq && (r = check_pack(b->seq, "seq")) != MLLM_OK) return r;
   if (st->proj >= 0) {
+    const int merge = st->layers[st->proj].merge;
+    if (merge > 1)
+      for (int sgm = 0; sgm < b->img.n_segments; sgm++)
+        if ((b->img.cu_seqlens_host[sgm + 1] - b->img.cu_seqlens_host[sgm]) % merge)
+          return fail(MLLM_ERR_SHAPE, "img segment %d: length is no multiple of the connector's merge width %d", sgm, merge);
     const int64_t n_con = connector_rows(st, b);
     if (n_con > 0 && !b->img_to_seq_row_host) return fail(MLLM_ERR_NULL, "img_to_seq_row_host is NULL");
     int64_t prev = -1;
@@ -282,14 +291,15 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0, split = 0;
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
+      const int64_t d_in = (int64_t)L.d_model * std::max(1, (int)L.merge);
       proj = (size_t)P.T_con * L.d_out * 2;
       P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)P.T_img * std::max(std::max(L.d_model, L.d_out), L.d_ff) * 2);
       if (L.d_ff) {
-        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_ff, P.T_con));
+        split = std::max(split, gemm_splitk_ws_bytes(d_in, L.d_ff, P.T_con));
         split = std::max(split, gemm_splitk_ws_bytes(L.d_ff, L.d_out, P.T_con));
         a = std::max(a, (size_t)P.T_con * L.d_ff * 2);
       } else {
-        split = std::max(split, gemm_splitk_ws_bytes(L.d_model, L.d_out, P.T_con));
+        split = std::max(split, gemm_splitk_ws_bytes(d_in, L.d_out, P.T_con));
       }
       if (P.pool > 1) c = std::max(c, (size_t)P.T_con * L.d_model * 2);   // gradient of the pooled rows
       part = std::max(part, (size_t)colsum_partial_rows(P.T_con) * std::max(L.d_out, L.d_ff) * 4);
@@ -632,10 +642,12 @@ mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** ou
       const ParamInfo ps[] = {{"w_o", i, d, d}, {"rms2_g", i, 1, d}, {"w_gu", i, d, 2 * f}, {"w_d", i, f, d}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
     } else if (L.d_ff) {
-      const ParamInfo ps[] = {{"w_p1", i, d, f}, {"b_p1", i, 1, f}, {"w_p2", i, f, L.d_out}, {"b_p2", i, 1, L.d_out}};
+      const int64_t d_in = d * std::max(1, (int)L.merge);
+      const ParamInfo ps[] = {{"w_p1", i, d_in, f}, {"b_p1", i, 1, f}, {"w_p2", i, f, L.d_out}, {"b_p2", i, 1, L.d_out}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
     } else {
-      const ParamInfo ps[] = {{"w_p", i, d, L.d_out}, {"b_p", i, 1, L.d_out}};
+      const int64_t d_in = d * std::max(1, (int)L.merge);
+      const ParamInfo ps[] = {{"w_p", i, d_in, L.d_out}, {"b_p", i, 1, L.d_out}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
     }
   }
@@ -706,6 +718,8 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       void* dst = last ? y : (void*)(saved + P.saved[i + 1].x);
       K_TRY(launch_copy(x_seq, dst, (size_t)P.T_seq * L.d_out * 2, s));
       const char* xin = saved + P.saved[i].x;
+      // token merging: the [T_img, d] rows read as [T_img / r, r d] rows (no data movement)
+      const int64_t d_in = (int64_t)L.d_model * std::max(1, (int)L.merge);
       if (P.pool > 1) {   // average pooling at the end of the encoder
         K_TRY(launch_pool_rows(xin, saved + P.saved[i].n1, (const int32_t*)(ws + P.meta.pool_first),
                                (const int32_t*)(ws + P.meta.pool_count), P.T_con, L.d_model, s));
@@ -714,11 +728,11 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       if (L.d_ff) {   // p = act(x.W1 + b1).W2 + b2
         char* pre = saved + P.saved[i].pre;
         char* act = saved + P.saved[i].act;
-        K_TRY(linear_fwd(xin, prm[0], pre, P.T_con, L.d_model, L.d_ff, prm[1], nullptr, s));
+        K_TRY(linear_fwd(xin, prm[0], pre, P.T_con, d_in, L.d_ff, prm[1], nullptr, s));
         K_TRY(launch_act_fwd(L.act, pre, act, P.T_con, L.d_ff, s));
         K_TRY(linear_fwd(act, prm[2], ws + P.w_proj, P.T_con, L.d_ff, L.d_out, prm[3], nullptr, s));
       } else {
-        K_TRY(linear_fwd(xin, prm[0], ws + P.w_proj, P.T_con, L.d_model, L.d_out, prm[1], nullptr, s));
+        K_TRY(linear_fwd(xin, prm[0], ws + P.w_proj, P.T_con, d_in, L.d_out, prm[1], nullptr, s));
       }
       K_TRY(launch_scatter_rows(ws + P.w_proj, dst, (const int32_t*)(ws + P.meta.i2s), P.T_con, L.d_out, 0, s));
       continue;
@@ -770,6 +784,7 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       float* partial = (float*)(ws + P.w_partial);
       void* out = (i == 0 && dx_img) ? dx_img : (void*)pp[flip];
       const char* xin = P.pool > 1 ? saved + P.saved[i].n1 : saved + P.saved[i].x;
+      const int64_t d_in = (int64_t)L.d_model * std::max(1, (int)L.merge);
       void* dxin = P.pool > 1 ? (void*)(ws + P.w_c) : out;   // gradient of the connector's input rows
       if (L.d_ff) {
         const char* pre = saved + P.saved[i].pre;
@@ -779,13 +794,13 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
         K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[3], accumulate, partial, P.T_con, L.d_out, s));
         K_TRY(linear_dx(dproj, prm[2], dh, P.T_con, L.d_ff, L.d_out, s));
         K_TRY(launch_act_bwd(L.act, dh, pre, dh, P.T_con, L.d_ff, s));
-        K_TRY(linear_dw(xin, dh, dprm[0], P.T_con, L.d_model, L.d_ff, accumulate, s, split));
+        K_TRY(linear_dw(xin, dh, dprm[0], P.T_con, d_in, L.d_ff, accumulate, s, split));
         K_TRY(launch_colsum(dh, L.d_ff, (float*)dprm[1], accumulate, partial, P.T_con, L.d_ff, s));
-        K_TRY(linear_dx(dh, prm[0], dxin, P.T_con, L.d_model, L.d_ff, s));
+        K_TRY(linear_dx(dh, prm[0], dxin, P.T_con, d_in, L.d_ff, s));
       } else {
-        K_TRY(linear_dw(xin, dproj, dprm[0], P.T_con, L.d_model, L.d_out, accumulate, s, split));
+        K_TRY(linear_dw(xin, dproj, dprm[0], P.T_con, d_in, L.d_out, accumulate, s, split));
         K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[1], accumulate, partial, P.T_con, L.d_out, s));
-        K_TRY(linear_dx(dproj, prm[0], dxin, P.T_con, L.d_model, L.d_out, s));
+        K_TRY(linear_dx(dproj, prm[0], dxin, P.T_con, d_in, L.d_out, s));
       }
       if (P.pool > 1)
         K_TRY(launch_unpool_rows(dxin, out, (const int32_t*)(ws + P.meta.row_window),

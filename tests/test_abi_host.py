@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_param_table_matches_the_generator(B):
     for layers in (W.tiny_stage_layers(), W.full_stage_layers(2, 2), [W.dec7b_layer()], [W.vit_l_layer()],
-                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()], W.tiny_pooled_layers()):
+                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()], W.tiny_pooled_layers(), W.tiny_merged_layers()):
         h = B.mllm_stage_create(layers)
         got = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
         want = [(n, li, r, c) for li, L in enumerate(layers) for n, r, c in W.param_specs(L)]
@@ -66,6 +66,7 @@ def test_descriptor_validation(B):
         [vit, _bad(proj, d_ff=100), dec],                          # connector hidden width not a multiple of 64
         [vit, _bad(proj, d_ff=128, act=W.ACT_SWIGLU), dec],        # MLP connector needs a GELU
         [vit, _bad(proj, pool=-1), dec],                           # pooling width out of range
+        [vit, _bad(proj, pool=2, merge=2), dec],                   # a connector either pools or merges
         [],
     ]
     for layers in cases:
@@ -228,5 +229,19 @@ def test_pooling_connector_row_count(B):
         with pytest.raises(B.MllmError) as e:
             B.mllm_stage_sizes(h, bad)
         assert e.value.status == 1
+    finally:
+        B.mllm_stage_destroy(h)
+
+
+def test_merging_connector_needs_segment_multiples(B):
+    wl = W.workload_tiny_merged(0)
+    h = B.mllm_stage_create(wl.layers)
+    try:
+        assert len(wl.batch.img_to_seq_row) == 2 * 16
+        assert B.mllm_stage_sizes(h, wl.batch)[0] > 0
+        odd = W.Batch(W.make_pack([64, 62, 2], W.MASK_BIDIR), wl.batch.seq, wl.batch.img_to_seq_row, [])
+        with pytest.raises(B.MllmError) as e:
+            B.mllm_stage_sizes(h, odd)
+        assert e.value.status == 3
     finally:
         B.mllm_stage_destroy(h)

@@ -55,6 +55,17 @@ def test_tiny_pooled_stage_matches_oracle(B, seed):
         st.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_tiny_merged_stage_matches_oracle(B, seed):
+    """MLP connector over rows that concatenate 4 consecutive encoder tokens."""
+    wl = W.workload_tiny_merged(seed)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_pooled_mlp_connector_ragged_segments(B):
     """Pooling by 4 over encoder segments of 1, 4, 9 and 130 tokens, MLP connector, image-only and
     text-only samples."""
