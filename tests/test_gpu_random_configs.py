@@ -61,13 +61,14 @@ def random_case(seed):
         v = vit()
         d_llm = hd * int(rng.integers(1, 5))
         hidden = int(rng.choice([0, 64 * int(rng.integers(1, 6))]))
-        layers = [v, W.projector_layer(v.d_model, d_llm, d_hidden=hidden), dec(d_llm)]
+        reduce = [(0, 0), (2, 0), (3, 0), (0, 2)][(seed // 3) % 4]      # (pool, merge): none, average 2 / 3, concatenate 2
+        layers = [v, W.projector_layer(v.d_model, d_llm, d_hidden=hidden, pool=reduce[0], merge=reduce[1]), dec(d_llm)]
         img_tokens = int(rng.choice([16, 40, 96, 130]))
         samples = [(int(rng.integers(0, 3)), int(rng.integers(0, 150))) for _ in range(int(rng.integers(1, 5)))]
         samples = [(k, t) for k, t in samples if k * img_tokens + t > 0] or [(1, 5)]
         if sum(k for k, _ in samples) == 0:
             samples.append((1, 0))                # an image-only sample
-        batch = W.batch_from_samples(samples, img_tokens=img_tokens)
+        batch = W.batch_from_samples(samples, img_tokens=img_tokens, pool=max(1, reduce[0], reduce[1]))
     return layers, batch
 
 
