@@ -67,6 +67,42 @@ def build_workload(name: str):
     return wl, desc
 
 
+def sample_clocks(step, torch, min_seconds=1.5):
+    """Median shader clock (MHz) and socket power (W) reported by rocm-smi while `step` repeats for
+    at least `min_seconds`; None values when the tool is missing or prints something else."""
+    import re
+    import subprocess
+    import threading
+    sclk, power, stop = [], [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks", "--showpower"], capture_output=True, text=True,
+                                     timeout=10).stdout
+            except Exception:
+                return
+            for line in out.splitlines():
+                m = re.search(r"sclk clock level.*\((\d+)Mhz\)", line)
+                if m:
+                    sclk.append(float(m.group(1)))
+                m = re.search(r"Power \(W\):\s*([\d.]+)", line)
+                if m:
+                    power.append(float(m.group(1)))
+            stop.wait(0.1)
+
+    th = threading.Thread(target=poll, daemon=True)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < min_seconds:
+        step()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=15)
+    med = lambda v: float(np.median(v)) if v else None
+    return {"sclk_mhz_under_load": med(sclk), "socket_power_w": med(power), "samples": len(sclk)}
+
+
 def run_gpu(args, wl):
     import torch
     from paper_2603_25120_amd import binding as B
@@ -124,6 +160,9 @@ def run_gpu(args, wl):
     gpu_ms = e0.elapsed_time(e1)
     prof, dropped = B.mllm_profile_end()
 
+    # shader clock and power under this load, sampled in a separate untimed pass
+    clocks = sample_clocks(lambda: step(1), torch, min_seconds=1.5)
+
     # forward-only timing (for the forward : backward ratio)
     f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     f0.record()
@@ -137,7 +176,7 @@ def run_gpu(args, wl):
     props = torch.cuda.get_device_properties(0)
     return dict(gpu_ms=gpu_ms, wall_ms=wall_ms, prof=prof, dropped=dropped, fwd_ms=fwd_ms, finite=finite,
                 saved_gib=sb / 2 ** 30, workspace_gib=wb / 2 ** 30, device=props.name,
-                cus=props.multi_processor_count, clock_mhz=getattr(props, 'clock_rate', 0) / 1e3)
+                cus=props.multi_processor_count, clock_mhz=getattr(props, 'clock_rate', 0) / 1e3, clocks=clocks)
 
 
 def cpu_baseline(sample_tokens: int = 6912):
@@ -470,6 +509,9 @@ def main():
         "model_tflop_per_step": step_flops / 1e12,
         "model_tflops": step_flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_peak_frac": step_flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
+        # the same against the peak scaled to the shader clock measured under this load (2.4 GHz nominal)
+        "mfma_peak_frac_at_measured_clock": (step_flops / (ms_per_step * 1e-3) / (MFMA_BF16_PEAK * r["clocks"]["sclk_mhz_under_load"] / 2400.0)
+                                             if r["clocks"].get("sclk_mhz_under_load") else None),
         "attention_flop_share": attn_f / (lin_f + attn_f),
         "fwd_ms": r["fwd_ms"], "bwd_over_fwd": (ms_per_step - r["fwd_ms"]) / r["fwd_ms"],
         "host_wall_ms_per_step": r["wall_ms"] / args.steps,
@@ -486,7 +528,7 @@ def main():
                if prof["elementwise"][1] > 0 else {})},
         "profile_records_dropped": r["dropped"], "outputs_finite": r["finite"],
         "saved_GiB": r["saved_gib"], "workspace_GiB": r["workspace_gib"],
-        "device": r["device"], "compute_units": r["cus"], "clock_mhz": r["clock_mhz"],
+        "device": r["device"], "compute_units": r["cus"], "clock_mhz": r["clock_mhz"], "clocks": r["clocks"],
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
