@@ -68,28 +68,30 @@ def build_workload(name: str):
 
 
 def sample_clocks(step, torch, min_seconds=1.5):
-    """Median shader clock (MHz) and socket power (W) reported by rocm-smi while `step` repeats for
-    at least `min_seconds`; None values when the tool is missing or prints something else."""
+    """Median shader clock (MHz) while `step` repeats for at least `min_seconds`, read from the
+    driver's sysfs table (pp_dpm_sclk, the current level carries a '*'); None when the file is not
+    there or not readable.  No other program is started for this."""
+    import glob
     import re
-    import subprocess
     import threading
-    sclk, power, stop = [], [], threading.Event()
+    paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+    sclk, stop = [], threading.Event()
 
     def poll():
         while not stop.is_set():
-            try:
-                out = subprocess.run(["rocm-smi", "--showclocks", "--showpower"], capture_output=True, text=True,
-                                     timeout=10).stdout
-            except Exception:
-                return
-            for line in out.splitlines():
-                m = re.search(r"sclk clock level.*\((\d+)Mhz\)", line)
-                if m:
-                    sclk.append(float(m.group(1)))
-                m = re.search(r"Power \(W\):\s*([\d.]+)", line)
-                if m:
-                    power.append(float(m.group(1)))
-            stop.wait(0.1)
+            best = None
+            for path in paths:
+                try:
+                    with open(path) as f:
+                        for line in f:
+                            m = re.search(r"(\d+)\s*Mhz\s*\*", line)
+                            if m:
+                                best = max(best or 0.0, float(m.group(1)))   # the busy GPU is the fastest one
+                except OSError:
+                    pass
+            if best is not None:
+                sclk.append(best)
+            stop.wait(0.05)
 
     th = threading.Thread(target=poll, daemon=True)
     th.start()
@@ -98,9 +100,9 @@ def sample_clocks(step, torch, min_seconds=1.5):
         step()
         torch.cuda.synchronize()
     stop.set()
-    th.join(timeout=15)
-    med = lambda v: float(np.median(v)) if v else None
-    return {"sclk_mhz_under_load": med(sclk), "socket_power_w": med(power), "samples": len(sclk)}
+    th.join(timeout=5)
+    return {"sclk_mhz_under_load": float(np.median(sclk)) if sclk else None, "samples": len(sclk),
+            "source": "pp_dpm_sclk"}
 
 
 def run_gpu(args, wl):
