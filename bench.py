@@ -491,9 +491,9 @@ def main():
     gemm_all = ("gemm_fwd", "gemm_dx", "gemm_dw", "gemm_small")
     all_gemm_ms = sum(prof[c][1] for c in gemm_all)
     all_gemm_work = sum(prof[c][2] for c in gemm_all)
-    kernel_names = {"gemm_fwd": "gemm_kernel<256, 256, 128, 64, false, true, false> (Y = X.W)",
-                    "gemm_dx": "gemm_kernel<256, 256, 128, 64, false, false, false> (dX = dY.W^T)",
-                    "gemm_dw": "gemm_kernel<256, 256, 128, 64, true, true, true> (dW = X^T.dY, fp32)"}
+    kernel_names = {"gemm_fwd": "gemm4_kernel<false, true, false> (Y = X.W, 256x256x64 tiles)",
+                    "gemm_dx": "gemm4_kernel<false, false, false> (dX = dY.W^T, 256x256x64 tiles)",
+                    "gemm_dw": "gemm4_kernel<true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
     # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
     # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
     traffic_table = {"gemm_fwd": (778199 * 2.0 + 247320) * 1024, "gemm_dx": (761588 * 2.0 + 164530) * 1024,

@@ -16,6 +16,11 @@
 // global -> registers (prefetch of the next tile, issued before the MFMAs of the current one)
 // -> LDS.  Tiles are visited in an order that keeps the workgroups resident on one XCD (they
 // share that XCD's L2) on neighbouring tiles of a GROUP_M-tall panel.
+//
+// Two kernels.  gemm4_kernel: 256x256 tiles on four wavefronts of 128x128 with a hand-placed
+// k-loop, for every problem that fills the chip with such tiles and whose K is a multiple of 64.
+// gemm_kernel: the general template (128x128 tiles on four wavefronts of 64x64 for small
+// problems, 256x256 tiles on eight wavefronts of 128x64 when K has a ragged tail).
 #include <algorithm>
 #include <utility>
 
@@ -237,6 +242,188 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
+// ---------------------------------------------------------------------------------------------
+// 256x256x64 tiles on four wavefronts (one per SIMD), each owning 128x128 = 4x4 MFMA blocks with
+// the accumulators in AGPRs: a third fewer LDS fragment reads per MFMA than 128x64 sub-tiles.
+// With a single wavefront per SIMD nothing else hides a stall, so the k-loop is written slot by
+// slot: every MFMA slot names the LDS read, LDS store and global load that issue in front of it and
+// a scheduling barrier after every slot keeps that order.  Two sets of staging registers: a
+// global load has two whole iterations to land.  Needs K to be a multiple of 64: the k-advance of
+// the global loads is a scalar offset (no per-load address arithmetic), clamped to the last tile
+// so that no address leaves the operand.
+template <class F, int... Is>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  for_each_index(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+template <int ROWS, int COLS, int PADC, int NT, bool K_ROWS>
+struct ScalarStepLoader {
+  static constexpr int VEC_PER_ROW = COLS / 8;
+  static constexpr int NVEC = ROWS * COLS / 8;
+  static constexpr int PER_THREAD = NVEC / NT;
+  static constexpr int STRIDE = COLS + PADC;
+  static_assert(NVEC % NT == 0 && NT % VEC_PER_ROW == 0, "tile must divide among threads");
+  u32x4 r[2][PER_THREAD];
+  uint32_t off[PER_THREAD];   // byte offset of this thread's vectors in k-tile 0, OOB if never valid
+  uint32_t kstep;             // bytes per k-tile
+
+  __device__ __forceinline__ void init(int64_t ld, int64_t fixed0, int64_t nfixed, int tid) {
+    kstep = (uint32_t)(K_ROWS ? BK * ld * 2 : BK * 2);
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; i++) {
+      const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
+      const int64_t fx = fixed0 + (K_ROWS ? cc : rr);
+      const int64_t lin = K_ROWS ? (int64_t)rr * ld + fx : fx * ld + cc;
+      off[i] = fx < nfixed ? (uint32_t)(lin * 2) : OOB;
+    }
+  }
+  template <int S, int I>
+  __device__ __forceinline__ void load1(__amdgpu_buffer_rsrc_t rsrc, uint32_t soff) {
+    r[S][I] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off[I], (int)soff, 0);
+  }
+  template <int S, int I>
+  __device__ __forceinline__ void store1(bf16_t* lds, int tid) const {
+    const int v = tid + I * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
+    *reinterpret_cast<u32x4*>(lds + rr * STRIDE + cc) = r[S][I];
+  }
+};
+
+template <bool A_T, bool B_T, bool OUT_F32>
+__global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
+  constexpr int BM = 256, BN = 256, WM = 128, WN = 128, NT = 256, TM = 4, TN = 4;
+  constexpr int A_ROWS = A_T ? BK : BM, A_COLS = A_T ? BM : BK, A_PAD = A_T ? PAD_T : PAD_K;
+  constexpr int B_ROWS = B_T ? BK : BN, B_COLS = B_T ? BN : BK, B_PAD = B_T ? PAD_T : PAD_K;
+  constexpr int A_STRIDE = A_COLS + A_PAD, B_STRIDE = B_COLS + B_PAD;
+  constexpr int A_SIZE = A_ROWS * A_STRIDE, B_SIZE = B_ROWS * B_STRIDE;
+  __shared__ __attribute__((aligned(16))) bf16_t As[2 * A_SIZE];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * B_SIZE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tm, tn;
+  tile_of_block(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  using LA = ScalarStepLoader<A_ROWS, A_COLS, A_PAD, NT, A_T>;
+  using LB = ScalarStepLoader<B_ROWS, B_COLS, B_PAD, NT, B_T>;
+  static_assert(LA::PER_THREAD == 8 && LB::PER_THREAD == 8, "eight vectors per thread and operand");
+  LA la;
+  LB lb;
+  la.init(p.lda, m0, p.M, tid);
+  lb.init(p.ldb, n0, p.N, tid);
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes), rb = make_rsrc(p.b, p.b_bytes);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  const int kt0 = blockIdx.y * p.kt_per_split;
+  const int last_tile = (int)(p.K / BK) - 1;
+  const int nk = min(p.kt_per_split, last_tile + 1 - kt0);
+  auto load_all = [&](auto s_c, int kt) {
+    constexpr int S = decltype(s_c)::value;
+    const uint32_t t = (uint32_t)min(kt, last_tile);
+    static_for<8>([&](auto i) { la.template load1<S, decltype(i)::value>(ra, t * la.kstep); });
+    static_for<8>([&](auto i) { lb.template load1<S, decltype(i)::value>(rb, t * lb.kstep); });
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  load_all(C0{}, kt0);
+  static_for<8>([&](auto i) { la.template store1<0, decltype(i)::value>(As, tid); });
+  static_for<8>([&](auto i) { lb.template store1<0, decltype(i)::value>(Bs, tid); });
+  load_all(C0{}, kt0 + 1);
+  load_all(C1{}, kt0 + 2);
+  {
+    const uint32_t t = (uint32_t)min(kt0 + 3, last_tile);
+    static_for<4>([&](auto i) { la.template store1<0, decltype(i)::value>(As + A_SIZE, tid); });
+    static_for<4>([&](auto i) { la.template load1<0, decltype(i)::value>(ra, t * la.kstep); });
+  }
+  __syncthreads();
+
+  // Fragments, double-buffered: unit u of a k-step, in the order of first use: A0, B0..B3, A1..A3.
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto fetch_unit = [&](auto u_c, auto buf_c, const bf16_t* at, const bf16_t* bt, auto kk_c) {
+    constexpr int u = decltype(u_c)::value, buf = decltype(buf_c)::value, kk = decltype(kk_c)::value;
+    if constexpr (u == 0) af[buf][0] = fetch_frag<A_T, A_STRIDE>(at, wm * WM, kk, lane);
+    else if constexpr (u <= 4) bfr[buf][u - 1] = fetch_frag<B_T, B_STRIDE>(bt, wn * WN + 32 * (u - 1), kk, lane);
+    else af[buf][u - 4] = fetch_frag<A_T, A_STRIDE>(at, wm * WM + 32 * (u - 4), kk, lane);
+  };
+  static_for<8>([&](auto u) { fetch_unit(u, C0{}, As, Bs, C0{}); });
+
+  // One k-tile.  P = parity of the tile = its LDS stage = the staging set that holds tile kt+1
+  // (the other set holds tile kt+2).
+  auto iteration = [&](auto p_c, int kt) __attribute__((always_inline)) {
+    constexpr int P = decltype(p_c)::value;
+    bf16_t* an = As + (P ^ 1) * A_SIZE;
+    bf16_t* bn = Bs + (P ^ 1) * B_SIZE;
+    const bf16_t* at = As + P * A_SIZE;
+    const bf16_t* bt = Bs + P * B_SIZE;
+    const uint32_t t3 = (uint32_t)min(kt0 + kt + 3, last_tile), t4 = (uint32_t)min(kt0 + kt + 4, last_tile);
+    const uint32_t sa3 = t3 * la.kstep, sb3 = t3 * lb.kstep, sa4 = t4 * la.kstep, sb4 = t4 * lb.kstep;
+    // slot m of k-step kk: MFMA block (m / 4, m % 4), preceded by
+    //   m even : the read of fragment unit m/2 of the next k-step (in the last k-step, after the
+    //            barrier, of the next tile's first k-step);
+    //   m odd  : a quarter-step of the tile move, alternately one vector from its staging register
+    //            to LDS and the refill of that register.  k-steps 0..2 move vectors 4..15 of tile
+    //            kt+1 (set P -> the other stage, refilled with tile kt+3); k-step 3, once the
+    //            barrier has freed this tile's own stage, vectors 0..3 of tile kt+2 (other set ->
+    //            this stage, refilled with tile kt+4).
+    auto slot = [&](auto kk_c, auto m_c) __attribute__((always_inline)) {
+      constexpr int kk = decltype(kk_c)::value, m = decltype(m_c)::value;
+      if constexpr (kk == 3 && m == 0) __syncthreads();
+      if constexpr (m % 2 == 0) {
+        using U = std::integral_constant<int, m / 2>;
+        if constexpr (kk < 3)
+          fetch_unit(U{}, std::integral_constant<int, (kk + 1) & 1>{}, at, bt, std::integral_constant<int, kk + 1>{});
+        else
+          fetch_unit(U{}, C0{}, an, bn, C0{});
+      } else {
+        constexpr int o = (m - 1) / 2;                       // 0..7 within the k-step
+        constexpr int q = (kk == 3 ? 0 : 4 + 4 * kk) + o / 2; // vector 0..15: A vectors then B vectors
+        constexpr int S = kk == 3 ? (P ^ 1) : P;
+        bf16_t* a_dst = kk == 3 ? const_cast<bf16_t*>(at) : an;
+        bf16_t* b_dst = kk == 3 ? const_cast<bf16_t*>(bt) : bn;
+        if constexpr (o % 2 == 0) {
+          if constexpr (q < 8) la.template store1<S, q>(a_dst, tid);
+          else lb.template store1<S, q - 8>(b_dst, tid);
+        } else {
+          if constexpr (q < 8) la.template load1<S, q>(ra, kk == 3 ? sa4 : sa3);
+          else lb.template load1<S, q - 8>(rb, kk == 3 ? sb4 : sb3);
+        }
+      }
+      constexpr int i = m / 4, j = m % 4;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto step = [&](auto kk_c) __attribute__((always_inline)) {
+      static_for<16>([&](auto m) __attribute__((always_inline)) { slot(kk_c, m); });
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+  };
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    iteration(C0{}, kt);
+    iteration(C1{}, kt + 1);
+  }
+  if (nk & 1) iteration(C0{}, nk - 1);
+
+  constexpr int ST_STRIDE = WN + 4;  // floats
+  static_assert(4 * 32 * ST_STRIDE * 4 <= 2 * A_SIZE * 2, "staging must fit in the A stages");
+  if constexpr (OUT_F32) p.c = reinterpret_cast<float*>(p.c) + blockIdx.y * p.c_split_stride;
+  store_tile<TM, TN, OUT_F32>(p, acc, reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE,
+                              m0 + wm * WM, n0 + wn * WN, lane);
+}
+
 template <int BM, int BN, int WM, int WN, int BKT = 64>
 hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   GemmParams p = make_gemm_params(g, BM, BN);
@@ -247,6 +434,24 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   }
   dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits), block(64 * (BM / WM) * (BN / WN));
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
+  // 256x256 tiles with K a positive multiple of 64: the four-wavefront kernel
+  if (BM == 256 && BN == 256 && g.k >= BK && g.k % BK == 0) {
+    const dim3 block4(256);
+#define MLLM_GEMM4_CASE(AT, BT, F32)                                                     \
+  if (at == AT && bt == BT && (g.out_fp32 != 0) == F32) {                                \
+    hipLaunchKernelGGL((gemm4_kernel<AT, BT, F32>), grid, block4, 0, s, p);              \
+    return hipGetLastError();                                                            \
+  }
+    MLLM_GEMM4_CASE(false, true, false)
+    MLLM_GEMM4_CASE(false, false, false)
+    MLLM_GEMM4_CASE(true, true, true)
+    MLLM_GEMM4_CASE(false, true, true)
+    MLLM_GEMM4_CASE(false, false, true)
+    MLLM_GEMM4_CASE(true, true, false)
+    MLLM_GEMM4_CASE(true, false, false)
+    MLLM_GEMM4_CASE(true, false, true)
+#undef MLLM_GEMM4_CASE
+  }
 #define MLLM_GEMM_CASE(AT, BT, F32)                                                      \
   if (at == AT && bt == BT && (g.out_fp32 != 0) == F32) {                                \
     hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AT, BT, F32, BKT>), grid, block, 0, s, p); \
