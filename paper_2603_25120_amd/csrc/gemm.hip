@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   constexpr int ST_STRIDE = WN + 4;  // floats
   static_assert(4 * 32 * ST_STRIDE * 4 <= 2 * A_SIZE * 2, "staging must fit in the A stages");
   if constexpr (OUT_F32) p.c = reinterpret_cast<float*>(p.c) + blockIdx.y * p.c_split_stride;
-  store_tile<TM, TN, OUT_F32>(p, acc, reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE,
+  store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE,
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 

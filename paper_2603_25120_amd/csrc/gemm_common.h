@@ -69,8 +69,9 @@ __device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, in
 // runs of four consecutive columns.  One 32-row band at a time goes through a per-wavefront fp32
 // staging area in LDS (32 x (WN+4) floats at `stage`) and leaves as 16-byte chunks (256 or 512
 // contiguous bytes per row), with bias / residual / accumulate applied in fp32 and a single
-// rounding on the way out.  Every wavefront of the workgroup must call it (it synchronises).
-template <int TM, int TN, bool OUT_F32>
+// rounding on the way out.  Every wavefront of the workgroup must call it (it synchronises: once
+// with WAVE_LOCAL, which is valid when each wavefront passes a staging area of its own).
+template <int TM, int TN, bool OUT_F32, bool WAVE_LOCAL = false>
 __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM][TN], float* stage,
                                            int64_t row0, int64_t col0, int lane) {
   constexpr int WN = 32 * TN, ST_STRIDE = WN + 4;
@@ -79,14 +80,18 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW;
 #pragma unroll
   for (int i = 0; i < TM; i++) {
-    __syncthreads();  // the band staged before (or the last tile's fragments) has been read
+    // the band staged before (or the last tile's fragments) has been read; a wavefront's own
+    // LDS accesses execute in order, so after the first band only its own order matters
+    if (!WAVE_LOCAL || i == 0) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < TN; j++)
 #pragma unroll
       for (int g4 = 0; g4 < 4; g4++)
         *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
             make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
-    __syncthreads();
+    if (!WAVE_LOCAL) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int t = 0; t < CHUNKS / 64; t++) {
       const int c = lane + 64 * t, rr = c / CHUNKS_PER_ROW, cc = (c % CHUNKS_PER_ROW) * EPC;
