@@ -77,7 +77,41 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   constexpr int WN = 32 * TN, ST_STRIDE = WN + 4;
   const int h = lane >> 5, cl = lane & 31;
   constexpr int EPC = OUT_F32 ? 4 : 8;  // output elements per 16-byte chunk
-  constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW;
+  constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW, PER_BAND = CHUNKS / 64;
+  static_assert(64 % CHUNKS_PER_ROW == 0, "a lane keeps its columns from chunk to chunk");
+  // chunk t of a band: row rr0 + t * ROWS_PER_PASS of the band, columns [cc, cc + EPC) for every t
+  constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
+  const int rr0 = lane / CHUNKS_PER_ROW, cc = (lane % CHUNKS_PER_ROW) * EPC;
+  const int64_t col = col0 + cc;
+  const bool col_ok = col < p.N;
+  // the bias of this lane's columns, once for the whole tile
+  float bias_f[EPC];
+#pragma unroll
+  for (int q = 0; q < EPC; q++) bias_f[q] = 0.f;
+  if (p.bias && col_ok) {
+#pragma unroll
+    for (int q = 0; q < EPC / 2; q++) {
+      const uint32_t bb = *reinterpret_cast<const uint32_t*>(p.bias + col + 2 * q);
+      bias_f[2 * q] = bf16lo(bb);
+      bias_f[2 * q + 1] = bf16hi(bb);
+    }
+  }
+  // WAVE_LOCAL callers have registers to spare: the residual of the whole tile is requested up
+  // front, so one memory latency is exposed instead of one per band
+  constexpr bool RES_AHEAD = WAVE_LOCAL && !OUT_F32;
+  uint4 res_ahead[RES_AHEAD ? TM * PER_BAND : 1];
+  if constexpr (RES_AHEAD) {
+    if (p.res) {
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int t = 0; t < PER_BAND; t++) {
+          const int64_t row = row0 + 32 * i + rr0 + t * ROWS_PER_PASS;
+          res_ahead[i * PER_BAND + t] = (row < p.M && col_ok)
+              ? *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col) : make_uint4(0, 0, 0, 0);
+        }
+    }
+  }
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     // the band staged before (or the last tile's fragments) has been read; a wavefront's own
@@ -93,24 +127,18 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
     if (!WAVE_LOCAL) __syncthreads();
     else __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int t = 0; t < CHUNKS / 64; t++) {
-      const int c = lane + 64 * t, rr = c / CHUNKS_PER_ROW, cc = (c % CHUNKS_PER_ROW) * EPC;
-      const int64_t row = row0 + 32 * i + rr, col = col0 + cc;
-      if (row >= p.M || col >= p.N) continue;
+    for (int t = 0; t < PER_BAND; t++) {
+      const int rr = rr0 + t * ROWS_PER_PASS;
+      const int64_t row = row0 + 32 * i + rr;
+      if (row >= p.M || !col_ok) continue;
       float f[EPC];
 #pragma unroll
       for (int q = 0; q < EPC / 4; q++) {
         const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
         f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
       }
-      if (p.bias) {
 #pragma unroll
-        for (int q = 0; q < EPC / 2; q++) {
-          const uint32_t bb = *reinterpret_cast<const uint32_t*>(p.bias + col + 2 * q);
-          f[2 * q] += bf16lo(bb);
-          f[2 * q + 1] += bf16hi(bb);
-        }
-      }
+      for (int q = 0; q < EPC; q++) f[q] += bias_f[q];
       if constexpr (OUT_F32) {
         float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.c) + row * p.ldc + col);
         if (p.accumulate) {
@@ -120,7 +148,9 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
         *dst = make_float4(f[0], f[1], f[2], f[3]);
       } else {
         if (p.res) {
-          const uint4 r = *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col);
+          uint4 r;
+          if constexpr (RES_AHEAD) r = res_ahead[i * PER_BAND + t];
+          else r = *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col);
           f[0] += bf16lo(r.x); f[1] += bf16hi(r.x); f[2] += bf16lo(r.y); f[3] += bf16hi(r.y);
           f[4] += bf16lo(r.z); f[5] += bf16hi(r.z); f[6] += bf16lo(r.w); f[7] += bf16hi(r.w);
         }

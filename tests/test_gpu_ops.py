@@ -69,6 +69,33 @@ def test_gemm_large_ragged(B, a_layout, b_layout, f32):
     assert nmax_err(host_f64(c), ref2) < (2e-3 if f32 else 1e-2)
 
 
+@pytest.mark.parametrize("k", [64, 128, 192, 320, 1024])
+@pytest.mark.parametrize("a_layout,b_layout,f32", [(0, 0, 0), (0, 1, 0), (1, 0, 0), (1, 1, 0),
+                                                   (0, 0, 1), (0, 1, 1), (1, 0, 1), (1, 1, 1)])
+def test_gemm_large_tiles_k_multiple_of_64(B, k, a_layout, b_layout, f32):
+    """The four-wavefront 256x256 kernel (enough tiles, K a multiple of 64): one, two, an odd and
+    an even number of k-tiles, ragged M and N, every layout, with the fused epilogue terms."""
+    m, n = 3512, 4104
+    a = W.draw_tensor(71, m, k)
+    b = W.bf16_round(W.draw_tensor(72, k, n) * np.float32(0.125))
+    a_st = np.ascontiguousarray(a.T) if a_layout else a
+    b_st = np.ascontiguousarray(b.T) if b_layout else b
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    bias = W.draw_tensor(73, 1, n)
+    if f32:
+        init = np.random.default_rng(74).standard_normal((m, n)).astype(np.float32)
+        c = torch.from_numpy(init.copy()).cuda()
+        B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout, out_fp32=1, accumulate=1,
+                       bias=dev_bf16(bias))
+        assert nmax_err(host_f64(c), ref + bias + init) < 2e-3
+    else:
+        res = W.draw_tensor(75, m, n)
+        c = empty_bf16(m, n)
+        B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout, bias=dev_bf16(bias),
+                       residual=dev_bf16(res))
+        assert nmax_err(host_f64(c), ref + bias + res) < 1e-2
+
+
 def test_gemm_epilogues(B):
     m, n, k = 333, 192, 256
     a, b = W.draw_tensor(3, m, k), W.bf16_round(W.draw_tensor(4, k, n) * np.float32(0.1))
