@@ -213,6 +213,33 @@ def cpu_baseline(sample_tokens: int = 6912):
                       % (batch.seq.total_tokens, batch.img.total_tokens, t_vit, t_dec)}
 
 
+def gemm_microbench(args):
+    """One GEMM of the library on its own (the kernel the stage spends four fifths of its time in):
+    `--gemm M N K A_LAYOUT B_LAYOUT OUT_FP32`, normally distributed bf16 operands, timed with HIP
+    events over `--steps` back-to-back launches after `--warmup`.  Prints one JSON line."""
+    import torch
+    from paper_2603_25120_amd import binding as B
+    B.lib()
+    m, n, k, al, bl, f32 = args.gemm
+    dev = torch.device("cuda:0")
+    a = torch.randn((k, m) if al else (m, k), device=dev).to(torch.bfloat16)
+    b = torch.randn((n, k) if bl else (k, n), device=dev).to(torch.bfloat16)
+    c = torch.empty(m, n, device=dev, dtype=torch.float32 if f32 else torch.bfloat16)
+    for _ in range(max(1, args.warmup)):
+        B.mllm_op_gemm(a, b, c, m, n, k, al, bl, f32, 0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        B.mllm_op_gemm(a, b, c, m, n, k, al, bl, f32, 0)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    tf = 2.0 * m * n * k / (ms * 1e-3) / 1e12
+    print(json.dumps({"gemm": {"m": m, "n": n, "k": k, "a_layout": al, "b_layout": bl, "out_fp32": f32},
+                      "launches": args.steps, "ms_per_launch": ms, "TFLOP/s": tf, "mfma_peak_frac": tf / 2500.0}))
+
+
 def sweep(args):
     """Stage time versus microbatch shape: the 16 seeded full-stage microbatches (4 token budgets x
     2 length mixes x 2 seeds) and, for one 8B-GQA decoder layer at 32768 tokens, equal-length
@@ -463,6 +490,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print stage time versus microbatch shape instead")
     ap.add_argument("--schedule", action="store_true", help="run the microbatch-scheduling experiment instead")
     ap.add_argument("--plan", action="store_true", help="run the model profiler, its held-out check and Algorithm 1 instead")
+    ap.add_argument("--gemm", type=int, nargs=6, metavar=("M", "N", "K", "A_LAYOUT", "B_LAYOUT", "OUT_FP32"),
+                    help="time one GEMM of the library on its own instead")
     ap.add_argument("--sched-items", type=int, default=64)
     ap.add_argument("--sched-buckets", type=int, default=8)
     ap.add_argument("--sched-nodes", type=int, default=2_000_000)
@@ -470,6 +499,8 @@ def main():
     if args.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU's stage; run with --gpus 1 "
                          "(no collectives or sharding are part of it)")
+    if args.gemm:
+        return gemm_microbench(args)
     if args.sweep:
         return sweep(args)
     if args.schedule:
