@@ -338,15 +338,19 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   };
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
+  // Prologue.  Tiles 0 and 1 are requested together (one exposed latency for both); tile 0 goes
+  // to stage 0 and its registers take tile 2.  From here on, at k-tile kt of parity P, set P^1
+  // holds tile kt+1 and set P tile kt+2.  The first quarter of tile 1's A vectors is moved here:
+  // the k-loop moves that quarter in the last k-step of the tile before.
   load_all(C0{}, kt0);
+  load_all(C1{}, kt0 + 1);
   static_for<8>([&](auto i) { la.template store1<0, decltype(i)::value>(As, tid); });
   static_for<8>([&](auto i) { lb.template store1<0, decltype(i)::value>(Bs, tid); });
-  load_all(C0{}, kt0 + 1);
-  load_all(C1{}, kt0 + 2);
+  load_all(C0{}, kt0 + 2);
   {
     const uint32_t t = (uint32_t)min(kt0 + 3, last_tile);
-    static_for<4>([&](auto i) { la.template store1<0, decltype(i)::value>(As + A_SIZE, tid); });
-    static_for<4>([&](auto i) { la.template load1<0, decltype(i)::value>(ra, t * la.kstep); });
+    static_for<4>([&](auto i) { la.template store1<1, decltype(i)::value>(As + A_SIZE, tid); });
+    static_for<4>([&](auto i) { la.template load1<1, decltype(i)::value>(ra, t * la.kstep); });
   }
   __syncthreads();
 
@@ -360,8 +364,8 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   };
   static_for<8>([&](auto u) { fetch_unit(u, C0{}, As, Bs, C0{}); });
 
-  // One k-tile.  P = parity of the tile = its LDS stage = the staging set that holds tile kt+1
-  // (the other set holds tile kt+2).
+  // One k-tile.  P = parity of the tile = its LDS stage = the staging set that holds tile kt+2
+  // (the other set holds tile kt+1).
   auto iteration = [&](auto p_c, int kt) __attribute__((always_inline)) {
     constexpr int P = decltype(p_c)::value;
     bf16_t* an = As + (P ^ 1) * A_SIZE;
@@ -375,8 +379,8 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
     //            barrier, of the next tile's first k-step);
     //   m odd  : a quarter-step of the tile move, alternately one vector from its staging register
     //            to LDS and the refill of that register.  k-steps 0..2 move vectors 4..15 of tile
-    //            kt+1 (set P -> the other stage, refilled with tile kt+3); k-step 3, once the
-    //            barrier has freed this tile's own stage, vectors 0..3 of tile kt+2 (other set ->
+    //            kt+1 (set P^1 -> the other stage, refilled with tile kt+3); k-step 3, once the
+    //            barrier has freed this tile's own stage, vectors 0..3 of tile kt+2 (set P ->
     //            this stage, refilled with tile kt+4).
     auto slot = [&](auto kk_c, auto m_c) __attribute__((always_inline)) {
       constexpr int kk = decltype(kk_c)::value, m = decltype(m_c)::value;
@@ -390,7 +394,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
       } else {
         constexpr int o = (m - 1) / 2;                       // 0..7 within the k-step
         constexpr int q = (kk == 3 ? 0 : 4 + 4 * kk) + o / 2; // vector 0..15: A vectors then B vectors
-        constexpr int S = kk == 3 ? (P ^ 1) : P;
+        constexpr int S = kk == 3 ? P : (P ^ 1);
         bf16_t* a_dst = kk == 3 ? const_cast<bf16_t*>(at) : an;
         bf16_t* b_dst = kk == 3 ? const_cast<bf16_t*>(bt) : bn;
         if constexpr (o % 2 == 0) {
