@@ -137,8 +137,10 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
         const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
         f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
       }
+      if (p.bias) {
 #pragma unroll
-      for (int q = 0; q < EPC; q++) f[q] += bias_f[q];
+        for (int q = 0; q < EPC; q++) f[q] += bias_f[q];
+      }
       if constexpr (OUT_F32) {
         float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.c) + row * p.ldc + col);
         if (p.accumulate) {
