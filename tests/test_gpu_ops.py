@@ -96,6 +96,24 @@ def test_gemm_large_tiles_k_multiple_of_64(B, k, a_layout, b_layout, f32):
         assert nmax_err(host_f64(c), ref + bias + res) < 1e-2
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_gemm_large_tiles_random_shapes(B, seed):
+    """Seeded random problems that take the four-wavefront kernel: ragged M and N in every
+    residue class of the 256-wide tiles, 1 to 12 k-tiles, random layouts and output types."""
+    rng = np.random.default_rng(9000 + seed)
+    m, n = 8 * int(rng.integers(365, 520)), 8 * int(rng.integers(375, 540))
+    k = 64 * int(rng.integers(1, 13))
+    a_layout, b_layout, f32 = (int(v) for v in rng.integers(0, 2, 3))
+    a = W.draw_tensor(81 + seed, m, k)
+    b = W.bf16_round(W.draw_tensor(91 + seed, k, n) * np.float32(0.125))
+    a_st = np.ascontiguousarray(a.T) if a_layout else a
+    b_st = np.ascontiguousarray(b.T) if b_layout else b
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    c = torch.empty(m, n, dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout, out_fp32=f32)
+    assert nmax_err(host_f64(c), ref) < (2e-3 if f32 else 1e-2)
+
+
 def test_gemm_epilogues(B):
     m, n, k = 333, 192, 256
     a, b = W.draw_tensor(3, m, k), W.bf16_round(W.draw_tensor(4, k, n) * np.float32(0.1))
