@@ -329,7 +329,8 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
 
   const int kt0 = blockIdx.y * p.kt_per_split;
   const int last_tile = (int)(p.K / BK) - 1;
-  const int nk = min(p.kt_per_split, last_tile + 1 - kt0);
+  // a split past the end of K (the last ones, when K does not divide evenly) has no k-tiles: zeros
+  const int nk = max(0, min(p.kt_per_split, last_tile + 1 - kt0));
   auto load_all = [&](auto s_c, int kt) {
     constexpr int S = decltype(s_c)::value;
     const uint32_t t = (uint32_t)min(kt, last_tile);

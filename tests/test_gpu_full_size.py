@@ -41,6 +41,21 @@ def test_vit_l_layer_full(B):
         st.close()
 
 
+def test_weight_gradient_split_with_empty_last_parts(B):
+    """Weight gradient of a 1280 -> 1280 connector over 6720 image tokens (105 k-tiles of 64): the
+    1280 x 1280 product is cut along the tokens into 13 parts of 9 k-tiles, so the last part starts
+    past the end of the contraction and must contribute zeros."""
+    layers = [W.projector_layer(1280, 1280)]
+    batch = W.batch_from_samples([(1, 3)] * 12, img_tokens=560)
+    assert batch.img.total_tokens == 105 * 64
+    wl = W.make_workload("split_tail", layers, batch, 907)
+    st = GpuStage(B, layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec7b_layer_full(B):
     wl = W.workload_dec7b(200)                       # 8192 packed tokens, d = 4096, MHA, SwiGLU 11008
     st = GpuStage(B, wl.layers)
