@@ -27,6 +27,8 @@ namespace mllm {
 
 namespace {
 
+#define MLLM_LDS_VOID(ptr) ((MLLM_LDS void*)(ptr))
+constexpr int WAIT_VMCNT_0 = (0x7 << 4) | (0xF << 8);
 constexpr int BKV = 64;   // key rows staged per step (forward, dQ)
 constexpr int BQ = 64;    // query rows staged per step (dK/dV)
 
@@ -157,12 +159,17 @@ __device__ __forceinline__ void reads_before_mfma_pairs(std::integer_sequence<in
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
-  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32, NB = BKV / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
+  constexpr int NC = HD / 16, ND = HD / 32, NB = BKV / 32, TILE = BKV * HD;
+  // K and V tiles go from global memory straight into LDS (`buffer_load ... lds`), two stages
+  // each in arrays of their own so that every access names its stage statically.
+  __shared__ __attribute__((aligned(1024))) bf16_t Ks0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Ks1[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vs0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vs1[TILE];
   const AttnTile t = p.tiles[blockIdx.y];
   const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qrow = t.tile0 + 32 * wave + (lane & 31);
   const bool qok = qrow < t.seg_len;
   const bf16_t* qp = p.q + (int64_t)(t.seg_start + qrow) * p.q_stride + head * HD + 8 * h;
@@ -184,18 +191,37 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
   float m = -INFINITY, l = 0.f;
   const float c2 = p.scale_log2e;
 
+  // One direct-to-LDS instruction moves 64 lanes x 16 bytes = RPI rows of the tile; lane l's
+  // chunk lands at position l of that 1 KiB, so the lane fetches the global chunk that the
+  // permutation puts there.  Rows past kv_end are outside the descriptor: zeros, no traffic.
   const __amdgpu_buffer_rsrc_t rk = rows_rsrc(kbase, p.kv_stride, kv_end, HD), rv = rows_rsrc(vbase, p.kv_stride, kv_end, HD);
-  RowTile<BKV, HD> lk, lv;
-  lk.load(rk, p.kv_stride, 0, tid);
-  lv.load(rv, p.kv_stride, 0, tid);
-  for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
-    __syncthreads();  // previous step's readers are done
-    lk.store(Ks, tid);
-    lv.store(Vs, tid);
+  constexpr int CPR = HD / 8, RPI = 64 / CPR, PER_WAVE = BKV / RPI / 4;
+  uint32_t kv_off[PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; i++) {
+    const int r = (wave * PER_WAVE + i) * RPI + lane / CPR, c = (lane % CPR) ^ swz<HD>(r);
+    kv_off[i] = (uint32_t)((r * p.kv_stride + 8 * c) * 2);
+  }
+  const uint32_t tile_bytes = (uint32_t)(BKV * p.kv_stride * 2);
+  auto issue = [&](int kv0, bf16_t* kn, bf16_t* vn) {
+    const uint32_t row = (uint32_t)(kv0 / BKV) * tile_bytes;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; i++) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, MLLM_LDS_VOID(kn + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(kv_off[i] + row), 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, MLLM_LDS_VOID(vn + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(kv_off[i] + row), 0, 0, 0);
+    }
+  };
+
+  // One key tile: wait for its loads (enqueued a tile ago), barrier (every wavefront is now done
+  // with the other stage), enqueue the next tile into the other stage, multiply.
+  auto tile = [&](const bf16_t* Ks, const bf16_t* Vs, bf16_t* Kn, bf16_t* Vn, int kv0, bool live) {
+    __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
     __syncthreads();
-    lk.load(rk, p.kv_stride, kv0 + BKV, tid);   // rows past kv_end: zeros, no traffic
-    lv.load(rv, p.kv_stride, kv0 + BKV, tid);
-    if (t.causal && kv0 > wave_last_q) continue;  // wavefront-uniform
+    issue(kv0 + BKV, Kn, Vn);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!live || (t.causal && kv0 > wave_last_q)) return;  // wavefront-uniform
     f32x16 s[NB];
 #pragma unroll
     for (int b = 0; b < NB; b++)
@@ -271,7 +297,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
     reads_before_mfmas<2>(std::make_integer_sequence<int, NPV - 1>{});
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_barrier(0);
+  };
+
+  issue(0, Ks0, Vs0);
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 2 * BKV) {
+    tile(Ks0, Vs0, Ks1, Vs1, kv0, true);
+    tile(Ks1, Vs1, Ks0, Vs0, kv0 + BKV, kv0 + BKV < kv_end);
   }
+  // the last enqueued loads (rows past the end: zeros) must have landed before this workgroup's
+  // LDS can be handed to another one
+  __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
   l += __shfl_xor(l, 32, 64);
   if (!qok) return;
   const float inv = 1.f / l;
@@ -435,9 +470,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
 // l % CPR of row l / CPR; the lane therefore asks for the global chunk that the XOR swizzle keeps
 // at that position.  Rows past the segment are out of the descriptor's range and arrive as zeros.
 // ---------------------------------------------------------------------------------------------
-#define MLLM_LDS_VOID(ptr) ((MLLM_LDS void*)(ptr))
 // s_waitcnt vmcnt(0) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
-constexpr int WAIT_VMCNT_0 = (0x7 << 4) | (0xF << 8);
 
 template <int HD>
 __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(AttnParams p) {
