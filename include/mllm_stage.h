@@ -193,8 +193,8 @@ const char* mllm_last_error(void);
  * *_host.
  * ------------------------------------------------------------------------------------------ */
 
-/* Dense contraction of the linear layers ("linear operations ... applied to the entire
- * concatenated sequence at once", Model Profiler): C[M,N] = op(A).op(B) (+ bias) (+ residual).
+/* Dense contraction of the linear layers, which run over the whole packed sequence in one
+ * call (Model Profiler, "Throughput Profiling"): C[M,N] = op(A).op(B) (+ bias) (+ residual).
  *   a_layout 0: A stored [M,K] row-major; 1: A stored [K,M] row-major (contraction over rows)
  *   b_layout 0: B stored [K,N] row-major; 1: B stored [N,K] row-major
  *   out_fp32 0: C is bf16 [M,N]; 1: C is fp32 [M,N]; accumulate != 0 (fp32 only): C += product

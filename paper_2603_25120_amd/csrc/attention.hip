@@ -1,8 +1,8 @@
 // Varlen block-diagonal flash attention for gfx950, forward and backward.
 //
-// "Attention operations are dependent on individual sequence lengths and must process each
-// original instance separately to maintain causal integrity" (Model Profiler, "Throughput
-// Profiling"): a packed [T, heads, hd] sequence is cut into segments by cu_seqlens; each segment
+// Attention depends on the length of every single sample and has to treat each packed sample
+// on its own so that no sample sees another (Model Profiler, "Throughput Profiling"): a packed
+// [T, heads, hd] sequence is cut into segments by cu_seqlens; each segment
 // attends only to itself, bidirectionally (an image inside the ViT) or causally (a sample inside
 // the LLM).  The host turns the segments into a list of tiles, longest first.
 //
@@ -63,40 +63,6 @@ struct AttnParams {
   int32_t T, Hq, Hkv;
   const AttnTile* tiles;
   float scale_log2e, scale;
-};
-
-// Stage ROWS x HD bf16 rows [row0, row0+ROWS) of a segment into LDS (zero beyond seg_len).
-template <int ROWS, int HD>
-struct RowTile {
-  static constexpr int NVEC = ROWS * HD / 8, PER_THREAD = NVEC / 256, VPR = HD / 8;
-  uint4 r[PER_THREAD];
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int64_t stride, int row0,
-                                       int seg_len, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; i++) {
-      int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
-      r[i] = (row0 + rr < seg_len)
-                 ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + rr) * stride + cc)
-                 : make_uint4(0, 0, 0, 0);
-    }
-  }
-  // The same through a buffer descriptor whose range ends with the last wanted row: rows beyond
-  // it come back as zeros without a branch (and without traffic).
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int64_t stride, int row0, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; i++) {
-      const int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
-      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(uint32_t)(((row0 + rr) * stride + cc) * 2), 0, 0);
-      r[i] = make_uint4(v.x, v.y, v.z, v.w);
-    }
-  }
-  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; i++) {
-      int vi = tid + 256 * i, rr = vi / VPR, cc = (vi % VPR) * 8;
-      *reinterpret_cast<uint4*>(lds + rr * HD + 8 * ((cc >> 3) ^ swz<HD>(rr))) = r[i];
-    }
-  }
 };
 
 // Natural-layout operand: row (r0 + lane%32), contraction values 16c + 8*(lane/32) .. +7.
@@ -354,12 +320,16 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
-  constexpr int STRIDE = HD, NC = HD / 16, ND = HD / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BKV * STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[BKV * STRIDE];
+  constexpr int NC = HD / 16, ND = HD / 32, TILE = BKV * HD;
+  // K and V tiles go straight to LDS, two stages each (as in the forward kernel).
+  __shared__ __attribute__((aligned(1024))) bf16_t Ks0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Ks1[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vs0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vs1[TILE];
   const AttnTile t = p.tiles[blockIdx.y];
   const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qrow = t.tile0 + 32 * wave + (lane & 31);
   const bool qok = qrow < t.seg_len;
   const int64_t grow = t.seg_start + (qok ? qrow : 0);
@@ -388,17 +358,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
     for (int v = 0; v < 16; v++) dqacc[d][v] = 0.f;
 
   const __amdgpu_buffer_rsrc_t rk = rows_rsrc(kbase, p.kv_stride, kv_end, HD), rv = rows_rsrc(vbase, p.kv_stride, kv_end, HD);
-  RowTile<BKV, HD> lk, lv;
-  lk.load(rk, p.kv_stride, 0, tid);
-  lv.load(rv, p.kv_stride, 0, tid);
-  for (int kv0 = 0; kv0 < kv_end; kv0 += BKV) {
+  constexpr int CPR = HD / 8, RPI = 64 / CPR, PER_WAVE = BKV / RPI / 4;
+  uint32_t kv_off[PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; i++) {
+    const int r = (wave * PER_WAVE + i) * RPI + lane / CPR, c = (lane % CPR) ^ swz<HD>(r);
+    kv_off[i] = (uint32_t)((r * p.kv_stride + 8 * c) * 2);
+  }
+  const uint32_t tile_bytes = (uint32_t)(BKV * p.kv_stride * 2);
+  auto issue = [&](int kv0, bf16_t* kn, bf16_t* vn) {   // rows past kv_end: zeros, no traffic
+    const uint32_t row = (uint32_t)(kv0 / BKV) * tile_bytes;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; i++) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, MLLM_LDS_VOID(kn + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(kv_off[i] + row), 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, MLLM_LDS_VOID(vn + (wave * PER_WAVE + i) * 512), 16,
+                                               (int)(kv_off[i] + row), 0, 0, 0);
+    }
+  };
+  auto tile = [&](const bf16_t* Ks, const bf16_t* Vs, bf16_t* Kn, bf16_t* Vn, int kv0, bool live) {
+    __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
     __syncthreads();
-    lk.store(Ks, tid);
-    lv.store(Vs, tid);
-    __syncthreads();
-    lk.load(rk, p.kv_stride, kv0 + BKV, tid);   // rows past kv_end: zeros, no traffic
-    lv.load(rv, p.kv_stride, kv0 + BKV, tid);
-    if (t.causal && kv0 > wave_last_q) continue;
+    issue(kv0 + BKV, Kn, Vn);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!live || (t.causal && kv0 > wave_last_q)) return;
 #pragma unroll
     for (int b = 0; b < BKV / 32; b++) {
       f32x16 s, dp;
@@ -445,7 +428,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  issue(0, Ks0, Vs0);
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 2 * BKV) {
+    tile(Ks0, Vs0, Ks1, Vs1, kv0, true);
+    tile(Ks1, Vs1, Ks0, Vs0, kv0 + BKV, kv0 + BKV < kv_end);
   }
+  __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);   // the last enqueued tile (zeros) has landed
   if (!qok) return;
   bf16_t* dqp = p.dq + grow * p.q_stride + head * HD;
 #pragma unroll

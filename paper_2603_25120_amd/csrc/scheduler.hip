@@ -9,8 +9,8 @@
 // clock); it starts from the LPT solution, so giving up early still returns something at least as
 // good as the fallback.
 //
-// Reading of "descending order of duration ... lowest accumulated load" for two stages: an item's
-// duration is max(e, l), a bucket's load is max(E_j, L_j); ties go to the lower index.
+// Reading of the greedy rule (longest item first, into the least loaded bucket) for two stages: an
+// item's duration is max(e, l), a bucket's load is max(E_j, L_j); ties go to the lower index.
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
