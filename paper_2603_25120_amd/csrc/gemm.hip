@@ -500,10 +500,21 @@ SplitPlan plan_split(int64_t m, int64_t n, int64_t k) {
     return {best, true};
   }
   const bool big = t256 >= 24;
-  int64_t want = big ? (320 + t256 - 1) / t256 : (512 + t128 - 1) / t128;
-  want = std::min<int64_t>(want, 16);
-  want = std::min<int64_t>(want, nk / 8);   // at least 8 k-tiles per split
-  return {(int)std::max<int64_t>(want, 1), big};
+  const int64_t cap = std::max<int64_t>(1, std::min<int64_t>(16, nk / 8));   // at least 8 k-tiles per split
+  if (big) {
+    // One 256x256 workgroup per CU: S splits make t256 * S workgroups that run in
+    // ceil(t256 * S / 256) rounds of 1/S of the K loop each; a split also costs its partial
+    // product's trip through memory, about a hundredth of a full K loop.
+    int best = 1;
+    double best_cost = 1e30;
+    for (int sp = 1; sp <= cap; sp++) {
+      const double cost = (double)((t256 * sp + 255) / 256) / sp + 0.01 * sp;
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = sp; }
+    }
+    return {best, true};
+  }
+  const int64_t want = std::min<int64_t>((512 + t128 - 1) / t128, cap);
+  return {(int)std::max<int64_t>(want, 1), false};
 }
 }  // namespace
 
