@@ -527,8 +527,8 @@ def main():
                     "gemm_dw": "gemm4_kernel<true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
     # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
     # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
-    traffic_table = {"gemm_fwd": (767634 * 2.0 + 247320) * 1024, "gemm_dx": (752780 * 2.0 + 164530) * 1024,
-                     "gemm_dw": (1080120 * 2.0 + 147768) * 1024}
+    traffic_table = {"gemm_fwd": (767631 * 2.0 + 247320) * 1024, "gemm_dx": (752778 * 2.0 + 164530) * 1024,
+                     "gemm_dw": (1073460 * 2.0 + 134505) * 1024}
     traffic = traffic_table[gemm_cls] if args.workload == "full_stage_32k" else None
     out = {
         "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",
