@@ -294,9 +294,16 @@ struct ScalarStepLoader {
   }
 };
 
-template <bool A_T, bool B_T, bool OUT_F32>
+template <int TM, bool A_T, bool B_T, bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
-  constexpr int BM = 256, BN = 256, WM = 128, WN = 128, NT = 256, TM = 4, TN = 4;
+  // TM = 4: 256x256 tiles, wavefronts of 128x128.  TM = 3: 192x256 tiles, wavefronts of 96x128,
+  // for problems whose 256-row tiles would leave the last round of workgroups mostly empty.
+  static_assert(TM == 4 || (TM == 3 && !A_T), "192-row tiles only for an A operand stored [M, K]");
+  constexpr int BM = 64 * TM, BN = 256, WM = 32 * TM, WN = 128, NT = 256, TN = 4;
+  constexpr int NA = 2 * TM;          // A vectors per thread and k-tile (B: 8)
+  constexpr int NU = TM + 4;          // fragment units per k-step
+  constexpr int NS = 4 * TM;          // MFMA slots per k-step
+  constexpr int Q3 = TM == 4 ? 4 : 3; // vectors moved in the last k-step (into the tile's own stage)
   constexpr int A_ROWS = A_T ? BK : BM, A_COLS = A_T ? BM : BK, A_PAD = A_T ? PAD_T : PAD_K;
   constexpr int B_ROWS = B_T ? BK : BN, B_COLS = B_T ? BN : BK, B_PAD = B_T ? PAD_T : PAD_K;
   constexpr int A_STRIDE = A_COLS + A_PAD, B_STRIDE = B_COLS + B_PAD;
@@ -312,7 +319,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
 
   using LA = ScalarStepLoader<A_ROWS, A_COLS, A_PAD, NT, A_T>;
   using LB = ScalarStepLoader<B_ROWS, B_COLS, B_PAD, NT, B_T>;
-  static_assert(LA::PER_THREAD == 8 && LB::PER_THREAD == 8, "eight vectors per thread and operand");
+  static_assert(LA::PER_THREAD == NA && LB::PER_THREAD == 8, "vectors per thread and operand");
   LA la;
   LB lb;
   la.init(p.lda, m0, p.M, tid);
@@ -334,28 +341,28 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   auto load_all = [&](auto s_c, int kt) {
     constexpr int S = decltype(s_c)::value;
     const uint32_t t = (uint32_t)min(kt, last_tile);
-    static_for<8>([&](auto i) { la.template load1<S, decltype(i)::value>(ra, t * la.kstep); });
+    static_for<NA>([&](auto i) { la.template load1<S, decltype(i)::value>(ra, t * la.kstep); });
     static_for<8>([&](auto i) { lb.template load1<S, decltype(i)::value>(rb, t * lb.kstep); });
   };
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
   // Prologue.  Tiles 0 and 1 are requested together (one exposed latency for both); tile 0 goes
   // to stage 0 and its registers take tile 2.  From here on, at k-tile kt of parity P, set P^1
-  // holds tile kt+1 and set P tile kt+2.  The first quarter of tile 1's A vectors is moved here:
-  // the k-loop moves that quarter in the last k-step of the tile before.
+  // holds tile kt+1 and set P tile kt+2.  The first Q3 of tile 1's A vectors are moved here: the
+  // k-loop moves those in the last k-step of the tile before.
   load_all(C0{}, kt0);
   load_all(C1{}, kt0 + 1);
-  static_for<8>([&](auto i) { la.template store1<0, decltype(i)::value>(As, tid); });
+  static_for<NA>([&](auto i) { la.template store1<0, decltype(i)::value>(As, tid); });
   static_for<8>([&](auto i) { lb.template store1<0, decltype(i)::value>(Bs, tid); });
   load_all(C0{}, kt0 + 2);
   {
     const uint32_t t = (uint32_t)min(kt0 + 3, last_tile);
-    static_for<4>([&](auto i) { la.template store1<1, decltype(i)::value>(As + A_SIZE, tid); });
-    static_for<4>([&](auto i) { la.template load1<1, decltype(i)::value>(ra, t * la.kstep); });
+    static_for<Q3>([&](auto i) { la.template store1<1, decltype(i)::value>(As + A_SIZE, tid); });
+    static_for<Q3>([&](auto i) { la.template load1<1, decltype(i)::value>(ra, t * la.kstep); });
   }
   __syncthreads();
 
-  // Fragments, double-buffered: unit u of a k-step, in the order of first use: A0, B0..B3, A1..A3.
+  // Fragments, double-buffered: unit u of a k-step, in the order of first use: A0, B0..B3, A1...
   bf16x8 af[2][TM], bfr[2][TN];
   auto fetch_unit = [&](auto u_c, auto buf_c, const bf16_t* at, const bf16_t* bt, auto kk_c) {
     constexpr int u = decltype(u_c)::value, buf = decltype(buf_c)::value, kk = decltype(kk_c)::value;
@@ -363,7 +370,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
     else if constexpr (u <= 4) bfr[buf][u - 1] = fetch_frag<B_T, B_STRIDE>(bt, wn * WN + 32 * (u - 1), kk, lane);
     else af[buf][u - 4] = fetch_frag<A_T, A_STRIDE>(at, wm * WM + 32 * (u - 4), kk, lane);
   };
-  static_for<8>([&](auto u) { fetch_unit(u, C0{}, As, Bs, C0{}); });
+  static_for<NU>([&](auto u) { fetch_unit(u, C0{}, As, Bs, C0{}); });
 
   // One k-tile.  P = parity of the tile = its LDS stage = the staging set that holds tile kt+2
   // (the other set holds tile kt+1).
@@ -375,35 +382,47 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
     const bf16_t* bt = Bs + P * B_SIZE;
     const uint32_t t3 = (uint32_t)min(kt0 + kt + 3, last_tile), t4 = (uint32_t)min(kt0 + kt + 4, last_tile);
     const uint32_t sa3 = t3 * la.kstep, sb3 = t3 * lb.kstep, sa4 = t4 * la.kstep, sb4 = t4 * lb.kstep;
-    // slot m of k-step kk: MFMA block (m / 4, m % 4), preceded by
-    //   m even : the read of fragment unit m/2 of the next k-step (in the last k-step, after the
-    //            barrier, of the next tile's first k-step);
-    //   m odd  : a quarter-step of the tile move, alternately one vector from its staging register
-    //            to LDS and the refill of that register.  k-steps 0..2 move vectors 4..15 of tile
-    //            kt+1 (set P^1 -> the other stage, refilled with tile kt+3); k-step 3, once the
-    //            barrier has freed this tile's own stage, vectors 0..3 of tile kt+2 (set P ->
-    //            this stage, refilled with tile kt+4).
+    // The tile move, vector q of NA + 8 (A vectors, then B vectors).  k-steps 0..2 move vectors
+    // Q3.. of tile kt+1 (set P^1 -> the other stage, refilled with tile kt+3); k-step 3, once the
+    // barrier has freed this tile's own stage, vectors 0..Q3-1 of tile kt+2 (set P -> this stage,
+    // refilled with tile kt+4).
+    auto move_store = [&](auto kk_c, auto q_c) __attribute__((always_inline)) {
+      constexpr int kk = decltype(kk_c)::value, q = decltype(q_c)::value, S = kk == 3 ? P : (P ^ 1);
+      if constexpr (q < NA) la.template store1<S, q>(kk == 3 ? const_cast<bf16_t*>(at) : an, tid);
+      else lb.template store1<S, q - NA>(kk == 3 ? const_cast<bf16_t*>(bt) : bn, tid);
+    };
+    auto move_load = [&](auto kk_c, auto q_c) __attribute__((always_inline)) {
+      constexpr int kk = decltype(kk_c)::value, q = decltype(q_c)::value, S = kk == 3 ? P : (P ^ 1);
+      if constexpr (q < NA) la.template load1<S, q>(ra, kk == 3 ? sa4 : sa3);
+      else lb.template load1<S, q - NA>(rb, kk == 3 ? sb4 : sb3);
+    };
+    // slot m of k-step kk: MFMA block (m / 4, m % 4), preceded by one memory operation.
+    //   TM = 4 (16 slots): even m reads fragment unit m/2 of the next k-step (in the last k-step,
+    //     after the barrier, of the next tile's first k-step); odd m does half a vector move,
+    //     alternately the store to LDS and the refill of the register.
+    //   TM = 3 (12 slots): m = 0, 2, .., 10 and 11 read the seven fragment units; m = 1, 3, .., 9
+    //     each move one whole vector (store, then refill) while vectors remain.
     auto slot = [&](auto kk_c, auto m_c) __attribute__((always_inline)) {
       constexpr int kk = decltype(kk_c)::value, m = decltype(m_c)::value;
       if constexpr (kk == 3 && m == 0) __syncthreads();
-      if constexpr (m % 2 == 0) {
-        using U = std::integral_constant<int, m / 2>;
+      constexpr int unit = (m % 2 == 0) ? m / 2 : ((TM == 3 && m == 11) ? 6 : -1);
+      if constexpr (unit >= 0) {
+        using U = std::integral_constant<int, unit>;
         if constexpr (kk < 3)
           fetch_unit(U{}, std::integral_constant<int, (kk + 1) & 1>{}, at, bt, std::integral_constant<int, kk + 1>{});
         else
           fetch_unit(U{}, C0{}, an, bn, C0{});
+      } else if constexpr (TM == 4) {
+        constexpr int o = (m - 1) / 2;                          // 0..7 within the k-step
+        using Q = std::integral_constant<int, (kk == 3 ? 0 : 4 + 4 * kk) + o / 2>;
+        if constexpr (o % 2 == 0) move_store(kk_c, Q{});
+        else move_load(kk_c, Q{});
       } else {
-        constexpr int o = (m - 1) / 2;                       // 0..7 within the k-step
-        constexpr int q = (kk == 3 ? 0 : 4 + 4 * kk) + o / 2; // vector 0..15: A vectors then B vectors
-        constexpr int S = kk == 3 ? P : (P ^ 1);
-        bf16_t* a_dst = kk == 3 ? const_cast<bf16_t*>(at) : an;
-        bf16_t* b_dst = kk == 3 ? const_cast<bf16_t*>(bt) : bn;
-        if constexpr (o % 2 == 0) {
-          if constexpr (q < 8) la.template store1<S, q>(a_dst, tid);
-          else lb.template store1<S, q - 8>(b_dst, tid);
-        } else {
-          if constexpr (q < 8) la.template load1<S, q>(ra, kk == 3 ? sa4 : sa3);
-          else lb.template load1<S, q - 8>(rb, kk == 3 ? sb4 : sb3);
+        constexpr int o = (m - 1) / 2;                          // 0..4 within the k-step
+        constexpr int q = kk == 3 ? o : Q3 + 5 * kk + o;
+        if constexpr (kk == 3 ? (o < Q3) : (q < NA + 8)) {
+          move_store(kk_c, std::integral_constant<int, q>{});
+          move_load(kk_c, std::integral_constant<int, q>{});
         }
       }
       constexpr int i = m / 4, j = m % 4;
@@ -411,7 +430,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
       __builtin_amdgcn_sched_barrier(0);
     };
     auto step = [&](auto kk_c) __attribute__((always_inline)) {
-      static_for<16>([&](auto m) __attribute__((always_inline)) { slot(kk_c, m); });
+      static_for<NS>([&](auto m) __attribute__((always_inline)) { slot(kk_c, m); });
     };
     step(std::integral_constant<int, 0>{});
     step(std::integral_constant<int, 1>{});
@@ -424,10 +443,11 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   }
   if (nk & 1) iteration(C0{}, nk - 1);
 
+  // the epilogue stages through the B stages (large enough for either tile height)
   constexpr int ST_STRIDE = WN + 4;  // floats
-  static_assert(4 * 32 * ST_STRIDE * 4 <= 2 * A_SIZE * 2, "staging must fit in the A stages");
+  static_assert(4 * 32 * ST_STRIDE * 4 <= 2 * B_SIZE * 2, "staging must fit in the B stages");
   if constexpr (OUT_F32) p.c = reinterpret_cast<float*>(p.c) + blockIdx.y * p.c_split_stride;
-  store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(As) + wave * 32 * ST_STRIDE,
+  store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE,
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
@@ -441,12 +461,27 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   }
   dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits), block(64 * (BM / WM) * (BN / WN));
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
-  // 256x256 tiles with K a positive multiple of 64: the four-wavefront kernel
+  // 256-column tiles with K a positive multiple of 64: the four-wavefront kernel
   if (BM == 256 && BN == 256 && g.k >= BK && g.k % BK == 0) {
     const dim3 block4(256);
+    // 192-row tiles when they save rounds of one-per-CU workgroups.  A round of them has three
+    // quarters of the MFMA work but the same prologue and epilogue: measured at 0.9 of a round
+    // of 256-row tiles for K = 1024..4096.  Only for A stored [M, K] and unsplit problems.
+    const int64_t t192 = ((g.m + 191) / 192) * p.tiles_n, t256 = (int64_t)p.tiles_m * p.tiles_n;
+    const bool rows192 = !at && splits == 1 && 9 * ((t192 + 255) / 256) < 10 * ((t256 + 255) / 256);
+    if (rows192) {
+      p.tiles_m = (int)((g.m + 191) / 192);
+      grid.x = (unsigned)(p.tiles_m * p.tiles_n);
+    }
 #define MLLM_GEMM4_CASE(AT, BT, F32)                                                     \
   if (at == AT && bt == BT && (g.out_fp32 != 0) == F32) {                                \
-    hipLaunchKernelGGL((gemm4_kernel<AT, BT, F32>), grid, block4, 0, s, p);              \
+    if constexpr (!AT) {                                                                 \
+      if (rows192) {                                                                     \
+        hipLaunchKernelGGL((gemm4_kernel<3, AT, BT, F32>), grid, block4, 0, s, p);       \
+        return hipGetLastError();                                                        \
+      }                                                                                  \
+    }                                                                                    \
+    hipLaunchKernelGGL((gemm4_kernel<4, AT, BT, F32>), grid, block4, 0, s, p);           \
     return hipGetLastError();                                                            \
   }
     MLLM_GEMM4_CASE(false, true, false)

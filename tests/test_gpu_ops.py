@@ -114,6 +114,29 @@ def test_gemm_large_tiles_random_shapes(B, seed):
     assert nmax_err(host_f64(c), ref) < (2e-3 if f32 else 1e-2)
 
 
+@pytest.mark.parametrize("k", [64, 192, 1024])
+@pytest.mark.parametrize("b_layout,f32", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_gemm_192_row_tiles(B, k, b_layout, f32):
+    """5640 x 4096 outputs are 368 tiles of 256x256 (two rounds of 256 workgroups, the second
+    mostly empty) and 480 tiles of 192x256: the kernel's 192-row form takes these.  Ragged last
+    row tile, both B layouts, both output types, fused epilogue terms."""
+    m, n = 5640, 4096
+    a = W.draw_tensor(101, m, k)
+    b = W.bf16_round(W.draw_tensor(102, k, n) * np.float32(0.125))
+    b_st = np.ascontiguousarray(b.T) if b_layout else b
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    bias = W.draw_tensor(103, 1, n)
+    if f32:
+        c = torch.zeros(m, n, dtype=torch.float32, device="cuda")
+        B.mllm_op_gemm(dev_bf16(a), dev_bf16(b_st), c, m, n, k, 0, b_layout, out_fp32=1, bias=dev_bf16(bias))
+        assert nmax_err(host_f64(c), ref + bias) < 2e-3
+    else:
+        res = W.draw_tensor(104, m, n)
+        c = empty_bf16(m, n)
+        B.mllm_op_gemm(dev_bf16(a), dev_bf16(b_st), c, m, n, k, 0, b_layout, bias=dev_bf16(bias), residual=dev_bf16(res))
+        assert nmax_err(host_f64(c), ref + bias + res) < 1e-2
+
+
 def test_gemm_epilogues(B):
     m, n, k = 333, 192, 256
     a, b = W.draw_tensor(3, m, k), W.bf16_round(W.draw_tensor(4, k, n) * np.float32(0.1))
