@@ -563,6 +563,9 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   // operands are addressed through 32-bit buffer offsets
   if ((g.a_layout ? g.k : g.m) * g.lda * 2 > GEMM_MAX_OPERAND_BYTES || (g.b_layout ? g.n : g.k) * g.ldb * 2 > GEMM_MAX_OPERAND_BYTES)
     return hipErrorInvalidValue;
+  // the epilogue addresses a sub-tile of up to 128 rows with 32-bit offsets from its first element
+  if (g.ldc * (g.out_fp32 ? 4 : 2) * 128 > 0xFFFFFFFFll || (g.residual && g.ldres * 2 * 128 > 0xFFFFFFFFll))
+    return hipErrorInvalidValue;
   const int64_t big_tiles = ((g.m + 255) / 256) * ((g.n + 255) / 256);
   const SplitPlan sp = plan_split(g.m, g.n, g.k);
   const bool split = sp.splits > 1 && g.out_fp32 && !g.bias && g.ldc == g.n && g.splitk_ws &&

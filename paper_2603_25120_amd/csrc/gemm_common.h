@@ -77,6 +77,7 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   constexpr int WN = 32 * TN, ST_STRIDE = WN + 4;
   const int h = lane >> 5, cl = lane & 31;
   constexpr int EPC = OUT_F32 ? 4 : 8;  // output elements per 16-byte chunk
+  constexpr int ESIZE = OUT_F32 ? 4 : 2;
   constexpr int CHUNKS_PER_ROW = WN / EPC, CHUNKS = 32 * CHUNKS_PER_ROW, PER_BAND = CHUNKS / 64;
   static_assert(64 % CHUNKS_PER_ROW == 0, "a lane keeps its columns from chunk to chunk");
   // chunk t of a band: row rr0 + t * ROWS_PER_PASS of the band, columns [cc, cc + EPC) for every t
@@ -84,6 +85,14 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   const int rr0 = lane / CHUNKS_PER_ROW, cc = (lane % CHUNKS_PER_ROW) * EPC;
   const int64_t col = col0 + cc;
   const bool col_ok = col < p.N;
+  // Addresses: a wavefront-uniform 64-bit base per matrix (the sub-tile's first element) plus a
+  // 32-bit offset of the lane's first chunk plus a uniform multiple of the row pitch (a sub-tile
+  // spans at most 128 rows: the host keeps 128 row pitches below 4 GiB).
+  const int rows_left = (int)min((int64_t)(32 * TM), p.M - row0);   // rows of this sub-tile inside C
+  char* const c_base = reinterpret_cast<char*>(p.c) + (row0 * p.ldc + col0) * ESIZE;
+  const uint32_t c_pitch = (uint32_t)(p.ldc * ESIZE), c_lane = (uint32_t)rr0 * c_pitch + (uint32_t)(cc * ESIZE);
+  const char* const r_base = reinterpret_cast<const char*>(p.res) + (row0 * p.ldres + col0) * 2;
+  const uint32_t r_pitch = (uint32_t)(p.ldres * 2), r_lane = (uint32_t)rr0 * r_pitch + (uint32_t)(cc * 2);
   // the bias of this lane's columns, once for the whole tile
   float bias_f[EPC];
 #pragma unroll
@@ -96,71 +105,79 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
       bias_f[2 * q + 1] = bf16hi(bb);
     }
   }
-  // WAVE_LOCAL callers have registers to spare: the residual of the whole tile is requested up
-  // front, so one memory latency is exposed instead of one per band
-  constexpr bool RES_AHEAD = WAVE_LOCAL && !OUT_F32;
-  uint4 res_ahead[RES_AHEAD ? TM * PER_BAND : 1];
-  if constexpr (RES_AHEAD) {
-    if (p.res) {
+  // FULL: the whole sub-tile lies inside C (wavefront-uniform), no per-chunk predicate.
+  auto emit = [&](auto full_c) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_c)::value;
+    // WAVE_LOCAL callers have registers to spare: the residual of the whole tile is requested up
+    // front, so one memory latency is exposed instead of one per band
+    constexpr bool RES_AHEAD = WAVE_LOCAL && !OUT_F32;
+    uint4 res_ahead[RES_AHEAD ? TM * PER_BAND : 1];
+    if constexpr (RES_AHEAD) {
+      if (p.res) {
 #pragma unroll
-      for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int t = 0; t < PER_BAND; t++) {
-          const int64_t row = row0 + 32 * i + rr0 + t * ROWS_PER_PASS;
-          res_ahead[i * PER_BAND + t] = (row < p.M && col_ok)
-              ? *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col) : make_uint4(0, 0, 0, 0);
-        }
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < TM; i++) {
-    // the band staged before (or the last tile's fragments) has been read; a wavefront's own
-    // LDS accesses execute in order, so after the first band only its own order matters
-    if (!WAVE_LOCAL || i == 0) __syncthreads();
-    else __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; g4++)
-        *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
-            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
-    if (!WAVE_LOCAL) __syncthreads();
-    else __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int t = 0; t < PER_BAND; t++) {
-      const int rr = rr0 + t * ROWS_PER_PASS;
-      const int64_t row = row0 + 32 * i + rr;
-      if (row >= p.M || !col_ok) continue;
-      float f[EPC];
-#pragma unroll
-      for (int q = 0; q < EPC / 4; q++) {
-        const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
-        f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
-      }
-      if (p.bias) {
-#pragma unroll
-        for (int q = 0; q < EPC; q++) f[q] += bias_f[q];
-      }
-      if constexpr (OUT_F32) {
-        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.c) + row * p.ldc + col);
-        if (p.accumulate) {
-          const float4 old = *dst;
-          f[0] += old.x; f[1] += old.y; f[2] += old.z; f[3] += old.w;
-        }
-        *dst = make_float4(f[0], f[1], f[2], f[3]);
-      } else {
-        if (p.res) {
-          uint4 r;
-          if constexpr (RES_AHEAD) r = res_ahead[i * PER_BAND + t];
-          else r = *reinterpret_cast<const uint4*>(p.res + row * p.ldres + col);
-          f[0] += bf16lo(r.x); f[1] += bf16hi(r.x); f[2] += bf16lo(r.y); f[3] += bf16hi(r.y);
-          f[4] += bf16lo(r.z); f[5] += bf16hi(r.z); f[6] += bf16lo(r.w); f[7] += bf16hi(r.w);
-        }
-        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + row * p.ldc + col) =
-            make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+          for (int t = 0; t < PER_BAND; t++) {
+            const int r = 32 * i + t * ROWS_PER_PASS;   // + rr0: the lane's row inside the sub-tile
+            const bool ok = FULL || (r + rr0 < rows_left && col_ok);
+            res_ahead[i * PER_BAND + t] =
+                ok ? *reinterpret_cast<const uint4*>(r_base + (r_lane + (uint32_t)r * r_pitch)) : make_uint4(0, 0, 0, 0);
+          }
       }
     }
-  }
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      // the band staged before (or the last tile's fragments) has been read; a wavefront's own
+      // LDS accesses execute in order, so after the first band only its own order matters
+      if (!WAVE_LOCAL || i == 0) __syncthreads();
+      else __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++)
+          *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
+              make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
+      if (!WAVE_LOCAL) __syncthreads();
+      else __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int t = 0; t < PER_BAND; t++) {
+        const int rr = rr0 + t * ROWS_PER_PASS;
+        const int r = 32 * i + t * ROWS_PER_PASS;
+        if (!FULL && !(r + rr0 < rows_left && col_ok)) continue;
+        float f[EPC];
+#pragma unroll
+        for (int q = 0; q < EPC / 4; q++) {
+          const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
+          f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
+        }
+        if (p.bias) {
+#pragma unroll
+          for (int q = 0; q < EPC; q++) f[q] += bias_f[q];
+        }
+        char* const dst_b = c_base + (c_lane + (uint32_t)r * c_pitch);
+        if constexpr (OUT_F32) {
+          float4* dst = reinterpret_cast<float4*>(dst_b);
+          if (p.accumulate) {
+            const float4 old = *dst;
+            f[0] += old.x; f[1] += old.y; f[2] += old.z; f[3] += old.w;
+          }
+          *dst = make_float4(f[0], f[1], f[2], f[3]);
+        } else {
+          if (p.res) {
+            uint4 rv;
+            if constexpr (RES_AHEAD) rv = res_ahead[i * PER_BAND + t];
+            else rv = *reinterpret_cast<const uint4*>(r_base + (r_lane + (uint32_t)r * r_pitch));
+            f[0] += bf16lo(rv.x); f[1] += bf16hi(rv.x); f[2] += bf16lo(rv.y); f[3] += bf16hi(rv.y);
+            f[4] += bf16lo(rv.z); f[5] += bf16hi(rv.z); f[6] += bf16lo(rv.w); f[7] += bf16hi(rv.w);
+          }
+          *reinterpret_cast<uint4*>(dst_b) =
+              make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+        }
+      }
+    }
+  };
+  if (rows_left >= 32 * TM && col0 + WN <= p.N) emit(std::true_type{});
+  else emit(std::false_type{});
 }
 
 }  // namespace mllm
