@@ -519,16 +519,16 @@ def main():
     gemm_cls = max(("gemm_fwd", "gemm_dx", "gemm_dw"), key=lambda c: prof[c][1])
     n, ms, work = prof[gemm_cls]
     achieved = work / (ms * 1e-3) if ms > 0 else 0.0
-    gemm_all = ("gemm_fwd", "gemm_dx", "gemm_dw", "gemm_small")
+    gemm_all = ("gemm_fwd", "gemm_dx", "gemm_dw", "gemm_small", "gemm_rows192")
     all_gemm_ms = sum(prof[c][1] for c in gemm_all)
     all_gemm_work = sum(prof[c][2] for c in gemm_all)
-    kernel_names = {"gemm_fwd": "gemm4_kernel<false, true, false> (Y = X.W, 256x256x64 tiles)",
-                    "gemm_dx": "gemm4_kernel<false, false, false> (dX = dY.W^T, 256x256x64 tiles)",
-                    "gemm_dw": "gemm4_kernel<true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
+    kernel_names = {"gemm_fwd": "gemm4_kernel<4, false, true, false> (Y = X.W, 256x256x64 tiles)",
+                    "gemm_dx": "gemm4_kernel<4, false, false, false> (dX = dY.W^T, 256x256x64 tiles)",
+                    "gemm_dw": "gemm4_kernel<4, true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
     # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
     # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
-    traffic_table = {"gemm_fwd": (767631 * 2.0 + 247320) * 1024, "gemm_dx": (752778 * 2.0 + 164530) * 1024,
-                     "gemm_dw": (1073460 * 2.0 + 134505) * 1024}
+    traffic_table = {"gemm_fwd": (1121310 * 2.0 + 367256) * 1024, "gemm_dx": (1526520 * 2.0 + 320439) * 1024,
+                     "gemm_dw": (1074080 * 2.0 + 134506) * 1024}
     traffic = traffic_table[gemm_cls] if args.workload == "full_stage_32k" else None
     out = {
         "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",

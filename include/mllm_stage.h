@@ -360,8 +360,9 @@ mllm_status_t mllm_optimize_parallelism(const mllm_module_profile_t* enc, const 
  * mllm_profile_end stops recording, waits for the recorded events, and sums per class
  * (0 / 1 / 2: the 256x256-tile GEMM kernel in its Y=X.W / dX / dW layouts, 3 attention forward,
  * 4 attention backward, 5 the norm / rotary / activation / reduction / copy kernels, 6 the
- * 128x128-tile GEMM kernel in any layout): launches[7], milliseconds[7] and work[7] (algorithmic
- * FLOPs for the GEMM and attention classes, algorithmic bytes for class 5) are host arrays.
+ * 128x128-tile GEMM kernel in any layout, 7 the 192x256-tile form of the large GEMM kernel in any
+ * layout): launches[8], milliseconds[8] and work[8] (algorithmic FLOPs for the GEMM and attention
+ * classes, algorithmic bytes for class 5) are host arrays.
  * Not thread-safe; records beyond max_records are dropped and counted in *dropped.
  * ------------------------------------------------------------------------------------------ */
 mllm_status_t mllm_profile_begin(int32_t max_records);

@@ -28,7 +28,8 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
            "mllm_find_combs", "mllm_evaluate_parallelism", "mllm_optimize_parallelism"]
 
-PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise", "gemm_small"]
+PROFILE_CLASSES = ["gemm_fwd", "gemm_dx", "gemm_dw", "attn_fwd", "attn_bwd", "elementwise", "gemm_small",
+                   "gemm_rows192"]
 
 
 class MllmError(RuntimeError):

@@ -451,6 +451,17 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
+// The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64.
+bool takes_gemm4(const GemmArgs& g) { return g.k >= BK && g.k % BK == 0; }
+// Its 192-row form when that saves rounds of one-per-CU workgroups.  A round of 192-row tiles
+// has three quarters of the MFMA work but the same prologue and epilogue: measured at 0.9 of a
+// round of 256-row tiles for K = 1024..4096.  Only for A stored [M, K] and unsplit problems.
+bool takes_rows192(const GemmArgs& g, int splits) {
+  if (!takes_gemm4(g) || g.a_layout != 0 || splits != 1) return false;
+  const int64_t tn = (g.n + 255) / 256, t192 = ((g.m + 191) / 192) * tn, t256 = ((g.m + 255) / 256) * tn;
+  return 9 * ((t192 + 255) / 256) < 10 * ((t256 + 255) / 256);
+}
+
 template <int BM, int BN, int WM, int WN, int BKT = 64>
 hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   GemmParams p = make_gemm_params(g, BM, BN);
@@ -461,14 +472,9 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   }
   dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits), block(64 * (BM / WM) * (BN / WN));
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
-  // 256-column tiles with K a positive multiple of 64: the four-wavefront kernel
-  if (BM == 256 && BN == 256 && g.k >= BK && g.k % BK == 0) {
+  if (BM == 256 && BN == 256 && takes_gemm4(g)) {
     const dim3 block4(256);
-    // 192-row tiles when they save rounds of one-per-CU workgroups.  A round of them has three
-    // quarters of the MFMA work but the same prologue and epilogue: measured at 0.9 of a round
-    // of 256-row tiles for K = 1024..4096.  Only for A stored [M, K] and unsplit problems.
-    const int64_t t192 = ((g.m + 191) / 192) * p.tiles_n, t256 = (int64_t)p.tiles_m * p.tiles_n;
-    const bool rows192 = !at && splits == 1 && 9 * ((t192 + 255) / 256) < 10 * ((t256 + 255) / 256);
+    const bool rows192 = takes_rows192(g, splits);
     if (rows192) {
       p.tiles_m = (int)((g.m + 191) / 192);
       grid.x = (unsigned)(p.tiles_m * p.tiles_n);
@@ -571,8 +577,9 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   const bool split = sp.splits > 1 && g.out_fp32 && !g.bias && g.ldc == g.n && g.splitk_ws &&
                      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4;
   const bool large = big_tiles >= 200 || (split && sp.big_tile);
-  // timing classes: the three layouts of the 256x256 kernel, and the 128x128 kernel
-  const int cls = !large ? PROF_GEMM_SMALL : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
+  // timing classes: the three layouts of the 256x256 kernel, its 192-row form, and the 128x128 kernel
+  const int cls = !large ? PROF_GEMM_SMALL : (!split && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
+                  : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   const double flops = 2.0 * (double)g.m * (double)g.n * (double)g.k;
   // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep
   // 128x128 tiles so that more workgroups exist.

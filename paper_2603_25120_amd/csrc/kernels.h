@@ -85,7 +85,8 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 // Optional per-launch timing with HIP events on the launch stream (off by default).  Classes:
 enum ProfClass { PROF_GEMM_FWD = 0, PROF_GEMM_DX = 1, PROF_GEMM_DW = 2, PROF_ATTN_FWD = 3,
-                 PROF_ATTN_BWD = 4, PROF_ELEMENTWISE = 5, PROF_GEMM_SMALL = 6, PROF_N_CLASSES = 7 };
+                 PROF_ATTN_BWD = 4, PROF_ELEMENTWISE = 5, PROF_GEMM_SMALL = 6, PROF_GEMM_ROWS192 = 7,
+                 PROF_N_CLASSES = 8 };
 struct ProfScope {   // records a start event now and a stop event when it goes out of scope
   ProfScope(int cls, double work, hipStream_t s);
   ~ProfScope();
