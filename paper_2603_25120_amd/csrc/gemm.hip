@@ -18,7 +18,8 @@
 // share that XCD's L2) on neighbouring tiles of a GROUP_M-tall panel.
 //
 // Two kernels.  gemm4_kernel: 256x256 tiles on four wavefronts of 128x128 with a hand-placed
-// k-loop, for every problem that fills the chip with such tiles and whose K is a multiple of 64.
+// k-loop, for every problem that fills the chip with such tiles and whose K is a multiple of 64
+// (also with 192x256 tiles, when those need fewer rounds of one-per-CU workgroups).
 // gemm_kernel: the general template (128x128 tiles on four wavefronts of 64x64 for small
 // problems, 256x256 tiles on eight wavefronts of 128x64 when K has a ragged tail).
 #include <algorithm>
