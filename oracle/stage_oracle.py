@@ -237,6 +237,25 @@ def attention_bwd(do, q, k, v, cu, mask_kind):
 
 
 # ---------------------------------------------------------------------------
+# QK normalisation (layer variant of the evaluated encoders, Evaluation, Table 4: InternViT).  The
+# query row of a token (all its heads side by side) and its key row each pass through an RMSNorm
+# with a gain vector of their own; in a decoder layer this comes before the rotary embedding.
+# ---------------------------------------------------------------------------
+def qk_norm_fwd(q, k, gq, gk, eps):
+    T = q.shape[0]
+    qn, cq = rmsnorm_fwd(q.reshape(T, -1), gq, eps)
+    kn, ck = rmsnorm_fwd(k.reshape(T, -1), gk, eps)
+    return qn.reshape(q.shape), kn.reshape(k.shape), cq, ck
+
+
+def qk_norm_bwd(dq, dk, cq, ck, gq, gk):
+    T = dq.shape[0]
+    dqp, d_gq = rmsnorm_bwd(dq.reshape(T, -1), cq, gq)
+    dkp, d_gk = rmsnorm_bwd(dk.reshape(T, -1), ck, gk)
+    return dqp.reshape(dq.shape), dkp.reshape(dk.shape), d_gq, d_gk
+
+
+# ---------------------------------------------------------------------------
 # layers
 # ---------------------------------------------------------------------------
 def _f64(a):
@@ -254,7 +273,7 @@ def _act_grad(act, h):
 def vit_layer_fwd(L, P, x, cu, mask_kind):
     """n = LN1(x); qkv = n.Wqkv + b; o = Attn(q,k,v); x1 = x + o.Wo + bo;
     n2 = LN2(x1); y = x1 + GELU(n2.W1 + b1).W2 + b2."""
-    g1, b1n, wqkv, bqkv, wo, bo, g2, b2n, w1, bb1, w2, bb2 = P
+    g1, b1n, wqkv, bqkv, wo, bo, g2, b2n, w1, bb1, w2, bb2 = P[:12]
     H, hd = L.n_q_heads, L.head_dim
     T = x.shape[0]
     n1, c1 = layernorm_fwd(x, g1, b1n, L.norm_eps)
@@ -262,17 +281,20 @@ def vit_layer_fwd(L, P, x, cu, mask_kind):
     q = qkv[:, :H * hd].reshape(T, H, hd)
     k = qkv[:, H * hd:2 * H * hd].reshape(T, H, hd)
     v = qkv[:, 2 * H * hd:].reshape(T, H, hd)
+    cq = ck = None
+    if L.qk_norm:
+        q, k, cq, ck = qk_norm_fwd(q, k, P[12], P[13], L.norm_eps)
     o = attention_fwd(q, k, v, cu, mask_kind).reshape(T, H * hd)
     x1 = x + o @ wo + bo
     n2, c2 = layernorm_fwd(x1, g2, b2n, L.norm_eps)
     h = n2 @ w1 + bb1
     a = _act_fwd(L.act, h)
     y = x1 + a @ w2 + bb2
-    return y, dict(c1=c1, n1=n1, q=q, k=k, v=v, o=o, c2=c2, n2=n2, h=h, a=a)
+    return y, dict(c1=c1, n1=n1, q=q, k=k, v=v, o=o, c2=c2, n2=n2, h=h, a=a, cq=cq, ck=ck)
 
 
 def vit_layer_bwd(L, P, C, dy, cu, mask_kind):
-    g1, b1n, wqkv, bqkv, wo, bo, g2, b2n, w1, bb1, w2, bb2 = P
+    g1, b1n, wqkv, bqkv, wo, bo, g2, b2n, w1, bb1, w2, bb2 = P[:12]
     T = dy.shape[0]
     H, hd = L.n_q_heads, L.head_dim
     d_b2 = dy.sum(axis=0, keepdims=True)
@@ -288,23 +310,28 @@ def vit_layer_bwd(L, P, C, dy, cu, mask_kind):
     d_wo = C["o"].T @ dx1
     do = (dx1 @ wo.T).reshape(T, H, hd)
     dq, dk, dv = attention_bwd(do, C["q"], C["k"], C["v"], cu, mask_kind)
+    d_qkn = []
+    if L.qk_norm:
+        dq, dk, d_gq, d_gk = qk_norm_bwd(dq, dk, C["cq"], C["ck"], P[12], P[13])
+        d_qkn = [d_gq, d_gk]
     dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
     d_bqkv = dqkv.sum(axis=0, keepdims=True)
     d_wqkv = C["n1"].T @ dqkv
     dn1 = dqkv @ wqkv.T
     dx_n, d_g1, d_b1n = layernorm_bwd(dn1, C["c1"], g1)
     dx = dx1 + dx_n
-    return dx, [d_g1, d_b1n, d_wqkv, d_bqkv, d_wo, d_bo, d_g2, d_b2n, d_w1, d_b1, d_w2, d_b2]
+    return dx, [d_g1, d_b1n, d_wqkv, d_bqkv, d_wo, d_bo, d_g2, d_b2n, d_w1, d_b1, d_w2, d_b2] + d_qkn
 
 
 def decoder_layer_fwd(L, P, x, cu, mask_kind):
     """n = RMS1(x); q,k,v = n.[Wq|Wk|Wv] (+ [bq|bk|bv] when the layer has a QKV bias);
     q,k <- RoPE; o = causal GQA attention; x1 = x + o.Wo; n2 = RMS2(x1);
     y = x1 + (SiLU(n2.Wg) * (n2.Wu)).Wd."""
+    nb = 7 if L.has_bias else 6
     if L.has_bias:
-        g1, wqkv, bqkv, wo, g2, wgu, wd = P
+        g1, wqkv, bqkv, wo, g2, wgu, wd = P[:nb]
     else:
-        g1, wqkv, wo, g2, wgu, wd = P
+        g1, wqkv, wo, g2, wgu, wd = P[:nb]
         bqkv = 0.0
     Hq, Hkv, hd, f = L.n_q_heads, L.n_kv_heads, L.head_dim, L.d_ff
     T = x.shape[0]
@@ -313,6 +340,9 @@ def decoder_layer_fwd(L, P, x, cu, mask_kind):
     q = qkv[:, :Hq * hd].reshape(T, Hq, hd)
     k = qkv[:, Hq * hd:(Hq + Hkv) * hd].reshape(T, Hkv, hd)
     v = qkv[:, (Hq + Hkv) * hd:].reshape(T, Hkv, hd)
+    cq = ck = None
+    if L.qk_norm:
+        q, k, cq, ck = qk_norm_fwd(q, k, P[nb], P[nb + 1], L.norm_eps)
     cos, sin = rope_tables(segment_positions(cu), hd, L.rope_base)
     q = rope_apply(q, cos, sin)
     k = rope_apply(k, cos, sin)
@@ -324,14 +354,15 @@ def decoder_layer_fwd(L, P, x, cu, mask_kind):
     a = swiglu_fwd(gate, up)
     y = x1 + a @ wd
     return y, dict(c1=c1, n1=n1, q=q, k=k, v=v, o=o, c2=c2, n2=n2, gate=gate, up=up, a=a,
-                   cos=cos, sin=sin)
+                   cos=cos, sin=sin, cq=cq, ck=ck)
 
 
 def decoder_layer_bwd(L, P, C, dy, cu, mask_kind):
+    nb = 7 if L.has_bias else 6
     if L.has_bias:
-        g1, wqkv, _bqkv, wo, g2, wgu, wd = P
+        g1, wqkv, _bqkv, wo, g2, wgu, wd = P[:nb]
     else:
-        g1, wqkv, wo, g2, wgu, wd = P
+        g1, wqkv, wo, g2, wgu, wd = P[:nb]
     Hq, Hkv, hd, f = L.n_q_heads, L.n_kv_heads, L.head_dim, L.d_ff
     T = dy.shape[0]
     d_wd = C["a"].T @ dy
@@ -347,14 +378,18 @@ def decoder_layer_bwd(L, P, C, dy, cu, mask_kind):
     dq, dk, dv = attention_bwd(do, C["q"], C["k"], C["v"], cu, mask_kind)
     dq = rope_apply_inverse(dq, C["cos"], C["sin"])
     dk = rope_apply_inverse(dk, C["cos"], C["sin"])
+    d_qkn = []
+    if L.qk_norm:
+        dq, dk, d_gq, d_gk = qk_norm_bwd(dq, dk, C["cq"], C["ck"], P[nb], P[nb + 1])
+        d_qkn = [d_gq, d_gk]
     dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
     d_wqkv = C["n1"].T @ dqkv
     dn1 = dqkv @ wqkv.T
     dx_n, d_g1 = rmsnorm_bwd(dn1, C["c1"], g1)
     dx = dx1 + dx_n
     if L.has_bias:
-        return dx, [d_g1, d_wqkv, dqkv.sum(axis=0, keepdims=True), d_wo, d_g2, d_wgu, d_wd]
-    return dx, [d_g1, d_wqkv, d_wo, d_g2, d_wgu, d_wd]
+        return dx, [d_g1, d_wqkv, dqkv.sum(axis=0, keepdims=True), d_wo, d_g2, d_wgu, d_wd] + d_qkn
+    return dx, [d_g1, d_wqkv, d_wo, d_g2, d_wgu, d_wd] + d_qkn
 
 
 def pool_windows(cu, pool):
@@ -442,10 +477,11 @@ def projector_bwd(L, P, C, dp, cu=None):
 # stage = ViT layers -> projector (+ scatter into the packed sequence) -> decoder layers
 # ---------------------------------------------------------------------------
 def n_params(layer) -> int:
+    qkn = 2 if getattr(layer, "qk_norm", 0) else 0
     if layer.kind == LAYER_VIT:
-        return 12
+        return 12 + qkn
     if layer.kind == LAYER_DECODER:
-        return 7 if layer.has_bias else 6
+        return (7 if layer.has_bias else 6) + qkn
     return 4 if layer.d_ff else 2
 
 

@@ -266,9 +266,10 @@ def _fwd(wl, params=None, x_img=None, x_seq=None):
                        wl.x_seq if x_seq is None else x_seq)
 
 
-@pytest.mark.parametrize("seed,variant", [(0, 0), (3, 0), (1, 1), (2, 2), (4, 3)])
+@pytest.mark.parametrize("seed,variant", [(0, 0), (3, 0), (1, 1), (2, 2), (4, 3), (5, 4)])
 def test_stage_gradients_by_central_differences(seed, variant):
-    wl = (_tiny, W.workload_tiny_variant, W.workload_tiny_pooled, W.workload_tiny_merged)[variant](seed)
+    wl = (_tiny, W.workload_tiny_variant, W.workload_tiny_pooled, W.workload_tiny_merged,
+          W.workload_tiny_qknorm)[variant](seed)
     y, caches = _fwd(wl)
     dy = wl.dy.astype(np.float64)
     dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, dy)
@@ -278,7 +279,9 @@ def test_stage_gradients_by_central_differences(seed, variant):
     def check(num, ana, what):
         assert abs(num - ana) <= 2e-6 * max(abs(ana), 1e-3), (what, num, ana)
 
-    h = 1e-5
+    # the normalised q and k rows are small before the norm, so the same step is a larger relative
+    # perturbation there: a smaller step keeps the truncation error under the bound
+    h = 2e-6 if variant == 4 else 1e-5
     v = rng.standard_normal(wl.x_img.shape)
     num = np.sum(dy * (_fwd(wl, x_img=wl.x_img + h * v)[0] - _fwd(wl, x_img=wl.x_img - h * v)[0])) / (2 * h)
     check(num, np.sum(dx_img * v), "x_img")
@@ -488,6 +491,97 @@ def test_variant_stage_against_torch_cpu_autograd():
     assert rel(dx_seq, x_seq.grad.numpy()) < 1e-10
     for g, p in zip(dparams, P):
         assert rel(g, p.grad.numpy()) < 1e-10
+
+
+def test_qk_norm_stage_against_torch_cpu_autograd():
+    """QK normalisation in the encoder layer and in a grouped-query decoder layer (before the rotary
+    embedding) against PyTorch CPU fp64 autograd with the library's own rms_norm, sample by sample."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    wl = W.workload_tiny_qknorm(7)
+    t64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    P = [t64(p) for p in wl.params]
+    assert len(P) == 14 + 2 + 8
+    x_img, x_seq = t64(wl.x_img), t64(wl.x_seq)
+    vit, proj, dec = wl.layers
+    outs = []
+    cu = wl.batch.seq.cu_seqlens
+    for s, (k, t) in enumerate(wl.batch.samples):
+        xi = x_img[64 * s:64 * (s + 1)]
+        g1, b1, wqkv, bqkv, wo, bo, g2, b2, w1, bb1, w2, bb2, gq, gk = P[:14]
+        n = F.layer_norm(xi, (192,), g1[0], b1[0], vit.norm_eps)
+        qkv = n @ wqkv + bqkv
+        heads = lambda z, h: z.reshape(z.shape[0], h, 64).permute(1, 0, 2)
+        q = heads(F.rms_norm(qkv[:, :192], (192,), gq[0], vit.norm_eps), 3)
+        kk = heads(F.rms_norm(qkv[:, 192:384], (192,), gk[0], vit.norm_eps), 3)
+        o = F.scaled_dot_product_attention(q, kk, heads(qkv[:, 384:], 3))
+        x1 = xi + o.permute(1, 0, 2).reshape(64, 192) @ wo + bo
+        n2 = F.layer_norm(x1, (192,), g2[0], b2[0], vit.norm_eps)
+        yv = x1 + F.gelu(n2 @ w1 + bb1) @ w2 + bb2
+        pr = yv @ P[14] + P[15]
+        xs = torch.cat([pr, x_seq[cu[s] + 64:cu[s + 1]]], dim=0)
+        Ls = xs.shape[0]
+        r1, wqkv, wo, r2, wgu, wd, gq, gk = P[16:]
+        n = F.rms_norm(xs, (256,), r1[0], dec.norm_eps)
+        qkv = n @ wqkv
+        q = heads(F.rms_norm(qkv[:, :256], (256,), gq[0], dec.norm_eps), 4)
+        kk = heads(F.rms_norm(qkv[:, 256:384], (128,), gk[0], dec.norm_eps), 2)
+        v = heads(qkv[:, 384:], 2)
+        inv = 10000.0 ** (-torch.arange(0, 32, dtype=torch.float64) * 2 / 64)
+        ang = torch.arange(Ls, dtype=torch.float64)[:, None] * inv[None, :]
+        cos, sin = torch.cos(ang), torch.sin(ang)
+        rot = lambda z: torch.cat([z[..., :32] * cos - z[..., 32:] * sin,
+                                   z[..., 32:] * cos + z[..., :32] * sin], dim=-1)
+        o = F.scaled_dot_product_attention(rot(q), rot(kk).repeat_interleave(2, dim=0),
+                                           v.repeat_interleave(2, dim=0), is_causal=True)
+        x1 = xs + o.permute(1, 0, 2).reshape(Ls, 256) @ wo
+        n2 = F.rms_norm(x1, (256,), r2[0], dec.norm_eps)
+        gu = n2 @ wgu
+        outs.append(x1 + (F.silu(gu[:, :1024]) * gu[:, 1024:]) @ wd)
+    y_t = torch.cat(outs, dim=0)
+    y_t.backward(torch.tensor(wl.dy.astype(np.float64)))
+    y, caches = _fwd(wl)
+    dx_img, dx_seq, dparams = O.stage_bwd(wl.layers, wl.params, wl.batch, caches, wl.dy.astype(np.float64))
+    rel = lambda a, b: np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30)
+    assert rel(y, y_t.detach().numpy()) < 1e-11
+    assert rel(dx_img, x_img.grad.numpy()) < 1e-10
+    assert rel(dx_seq, x_seq.grad.numpy()) < 1e-10
+    for g, p in zip(dparams, P):
+        assert rel(g, p.grad.numpy()) < 1e-10
+
+
+def test_qk_norm_with_unit_gains_makes_rows_unit_rms_and_scale_free():
+    """With gains of one every normalised q and k row has mean square 1 (up to eps), and scaling the
+    columns of W_qkv that produce q and k by any positive factor leaves the stage output unchanged."""
+    wl = W.workload_tiny_qknorm(8)
+    names = [n for L in wl.layers for n, _, _ in W.param_specs(L)]
+    params = [p.astype(np.float64) for p in wl.params]
+    for i, n in enumerate(names):
+        if n.startswith("qkn_"):
+            params[i] = np.ones_like(params[i])
+    y, caches = _fwd(wl, params=params)
+    for c in (caches[0], caches[2]):
+        for z in (c["q"], c["k"]):
+            if "cos" in c:
+                continue                     # rotated afterwards: norm preserved, checked below
+            ms = (z.reshape(z.shape[0], -1) ** 2).mean(axis=1)
+            assert np.max(np.abs(ms - 1.0)) < 1e-3
+    c = caches[2]
+    for z in (c["q"], c["k"]):               # rotation keeps each row's norm
+        ms = (z.reshape(z.shape[0], -1) ** 2).mean(axis=1)
+        assert np.max(np.abs(ms - 1.0)) < 1e-3
+    scaled = [p.copy() for p in params]
+    eps_free = [p.copy() for p in params]
+    iw = names.index("w_qkv")
+    ib = names.index("b_qkv")
+    for P in (scaled,):
+        P[iw][:, :384] *= 64.0
+        P[ib][:, :384] *= 64.0
+    eps_free[iw][:, :384] *= 8.0
+    eps_free[ib][:, :384] *= 8.0
+    y64 = _fwd(wl, params=scaled)[0]
+    y8 = _fwd(wl, params=eps_free)[0]
+    assert np.max(np.abs(y64 - y8)) < 1e-4 * np.max(np.abs(y8))   # equal but for eps under the root
 
 
 def test_variant_reductions():

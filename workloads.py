@@ -69,15 +69,20 @@ class LayerDesc:
     rope_base: float = 10000.0
     pool: int = 0           # projector: average-pool this many consecutive encoder tokens first (0/1: none)
     merge: int = 0          # projector: concatenate this many consecutive encoder tokens into one row (0/1: none)
+    qk_norm: int = 0        # ViT / decoder: RMS-normalise the q rows and the k rows (all heads together) before attention
 
 
-def vit_layer(d, heads, head_dim, d_ff, eps=1e-5, act=ACT_GELU_ERF) -> LayerDesc:
-    return LayerDesc(LAYER_VIT, d, heads, heads, head_dim, d_ff, 0, act, 1, eps, 0.0)
+def vit_layer(d, heads, head_dim, d_ff, eps=1e-5, act=ACT_GELU_ERF, qk_norm=0) -> LayerDesc:
+    """qk_norm = 1: the query rows and the key rows (all heads of a token together) pass through an
+    RMSNorm with a gain of their own before attention (the InternViT kind of QK normalisation)."""
+    return LayerDesc(LAYER_VIT, d, heads, heads, head_dim, d_ff, 0, act, 1, eps, 0.0, qk_norm=qk_norm)
 
 
-def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5, qkv_bias=0) -> LayerDesc:
-    """has_bias = 1 on a decoder layer: the QKV projection (and only it) has a bias."""
-    return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, qkv_bias, eps, rope_base)
+def decoder_layer(d, hq, hkv, head_dim, d_ff, rope_base, eps=1e-5, qkv_bias=0, qk_norm=0) -> LayerDesc:
+    """has_bias = 1 on a decoder layer: the QKV projection (and only it) has a bias.  qk_norm = 1:
+    as for vit_layer, applied before the rotary embedding."""
+    return LayerDesc(LAYER_DECODER, d, hq, hkv, head_dim, d_ff, 0, ACT_SWIGLU, qkv_bias, eps, rope_base,
+                     qk_norm=qk_norm)
 
 
 def projector_layer(d_in, d_out, d_hidden=0, act=ACT_GELU_ERF, pool=0, merge=0) -> LayerDesc:
@@ -101,15 +106,17 @@ def param_specs(layer: LayerDesc) -> List[Tuple[str, int, int]]:
         nqkv = (layer.n_q_heads + 2 * layer.n_kv_heads) * layer.head_dim
         no = layer.n_q_heads * layer.head_dim
         f = layer.d_ff
+        qkn = [("qkn_q_g", 1, no), ("qkn_k_g", 1, layer.n_kv_heads * layer.head_dim)] if layer.qk_norm else []
         return [("ln1_g", 1, d), ("ln1_b", 1, d), ("w_qkv", d, nqkv), ("b_qkv", 1, nqkv),
                 ("w_o", no, d), ("b_o", 1, d), ("ln2_g", 1, d), ("ln2_b", 1, d),
-                ("w_1", d, f), ("b_1", 1, f), ("w_2", f, d), ("b_2", 1, d)]
+                ("w_1", d, f), ("b_1", 1, f), ("w_2", f, d), ("b_2", 1, d)] + qkn
     if layer.kind == LAYER_DECODER:
         nqkv = (layer.n_q_heads + 2 * layer.n_kv_heads) * layer.head_dim
         no = layer.n_q_heads * layer.head_dim
         f = layer.d_ff
         qkv = [("w_qkv", d, nqkv), ("b_qkv", 1, nqkv)] if layer.has_bias else [("w_qkv", d, nqkv)]
-        return [("rms1_g", 1, d)] + qkv + [("w_o", no, d), ("rms2_g", 1, d), ("w_gu", d, 2 * f), ("w_d", f, d)]
+        qkn = [("qkn_q_g", 1, no), ("qkn_k_g", 1, layer.n_kv_heads * layer.head_dim)] if layer.qk_norm else []
+        return [("rms1_g", 1, d)] + qkv + [("w_o", no, d), ("rms2_g", 1, d), ("w_gu", d, 2 * f), ("w_d", f, d)] + qkn
     if layer.kind == LAYER_PROJECTOR:
         d_in = d * max(1, layer.merge)
         if layer.d_ff:
@@ -316,6 +323,19 @@ def workload_tiny_variant(seed: int) -> Workload:
     samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
     batch = batch_from_samples(samples, img_tokens=64)
     return make_workload("tiny_variant", tiny_variant_layers(), batch, seed)
+
+
+def tiny_qknorm_layers() -> List[LayerDesc]:
+    """The tiny stage with QK normalisation in the encoder layer and in a grouped-query decoder layer."""
+    return [vit_layer(192, 3, 64, 768, qk_norm=1), projector_layer(192, 256),
+            decoder_layer(256, 4, 2, 64, 1024, 10000.0, qk_norm=1)]
+
+
+def workload_tiny_qknorm(seed: int) -> Workload:
+    rng = np.random.default_rng(seed)
+    samples = [(1, int(rng.integers(32, 97))) for _ in range(2)]
+    batch = batch_from_samples(samples, img_tokens=64)
+    return make_workload("tiny_qknorm", tiny_qknorm_layers(), batch, seed)
 
 
 def tiny_pooled_layers() -> List[LayerDesc]:
