@@ -79,12 +79,18 @@ enum { MLLM_ACT_GELU_ERF = 0, MLLM_ACT_GELU_TANH = 1, MLLM_ACT_SWIGLU = 2 };
  *              caller orders patches so that those to be merged are adjacent): every img segment
  *              length must be a multiple of r, the connector has total / r rows of width r * d_model
  *              and its first matrix is [r * d_model, .].
+ *   qk_norm = 1 (VIT, DECODER): QK normalisation as in the InternViT encoders of the evaluated
+ *              models (Evaluation, Table 4).  After the QKV projection the q row of a token (its
+ *              n_q_heads * head_dim values, all heads together) is replaced by
+ *              q * rsqrt(mean(q^2) + norm_eps) * qkn_q_g, and the k row (n_kv_heads * head_dim values)
+ *              likewise with qkn_k_g; in a DECODER layer this comes before the rotary positions.
  * Parameter tensors per layer, in order (all bf16, matrices [in, out], vectors [n]):
  *   VIT:       ln1_g, ln1_b, w_qkv [d, 3d], b_qkv, w_o [d, d], b_o, ln2_g, ln2_b,
  *              w_1 [d, f], b_1, w_2 [f, d], b_2
  *   DECODER:   rms1_g, w_qkv [d, (n_q + 2 n_kv) hd], (b_qkv when has_bias = 1,) w_o [n_q hd, d],
  *              rms2_g, w_gu [d, 2f] = [W_gate | W_up], w_d [f, d]
  *   PROJECTOR: w_p [d_model, d_out], b_p; or w_p1 [d_model, d_ff], b_p1, w_p2 [d_ff, d_out], b_p2
+ *   with qk_norm = 1 a VIT / DECODER layer's list ends with qkn_q_g [n_q hd], qkn_k_g [n_kv hd]
  * Limits: head_dim in {64, 128}; d_model == n_q_heads * head_dim for VIT / DECODER; every width
  * a multiple of 64; n_q_heads a multiple of n_kv_heads; act GELU_* for VIT and for a two-layer
  * PROJECTOR, SWIGLU for DECODER.
@@ -107,6 +113,8 @@ typedef struct {
                          before the connector's map (0 or 1: none)  */
   int32_t merge;      /* PROJECTOR only: concatenate this many consecutive encoder tokens of a segment
                          into one connector row of width merge * d_model (0 or 1: none; not with pool) */
+  int32_t qk_norm;    /* VIT / DECODER: 1 = RMS-normalise the q row and the k row of every token before
+                         attention (0: none; PROJECTOR: must be 0) */
 } mllm_layer_desc_t;
 
 /* Layers in execution order: zero or more VIT, then at most one PROJECTOR, then zero or more

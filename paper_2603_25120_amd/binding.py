@@ -43,7 +43,7 @@ class LayerDescC(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("has_bias", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("pool", C.c_int32),
-                ("merge", C.c_int32)]
+                ("merge", C.c_int32), ("qk_norm", C.c_int32)]
 
 
 class StageDescC(C.Structure):
@@ -205,7 +205,7 @@ def mllm_stage_create(layers: Sequence) -> int:
     arr = (LayerDescC * len(layers))()
     for i, l in enumerate(layers):
         for f, _ in LayerDescC._fields_:
-            setattr(arr[i], f, getattr(l, f))
+            setattr(arr[i], f, getattr(l, f, 0) if f == "qk_norm" else getattr(l, f))
     desc = StageDescC(len(layers), arr)
     out = C.c_void_p()
     _check(lib().mllm_stage_create(C.byref(desc), C.byref(out)))

@@ -23,14 +23,15 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 // ---------------------------------------------------------------------------------------------
 // normalisation forward: y = (x - mean) * rstd * gamma + beta   (LayerNorm, KIND 0)
 //                        y = x * rstd * gamma                   (RMSNorm,   KIND 1)
-// NV = 16-byte vectors per lane; the row lives in registers between the passes.
+// NV = 16-byte vectors per lane; the row lives in registers between the passes.  Rows of x and y
+// are ld elements apart (ld = d for a dense matrix, more for a column slice of a wider one).
 // ---------------------------------------------------------------------------------------------
 template <int KIND, int NV>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict__ x,
                                                        const bf16_t* __restrict__ gamma,
                                                        const bf16_t* __restrict__ beta,
                                                        bf16_t* __restrict__ y, float* __restrict__ stats,
-                                                       int64_t T, int d, float eps) {
+                                                       int64_t T, int d, int64_t ld, float eps) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
   if (row >= T) return;
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
   for (int j = 0; j < NV; j++) {
     int c = lane + 64 * j;
     if (c < nvec) {
-      uint4 u = *reinterpret_cast<const uint4*>(x + row * d + 8 * c);
+      uint4 u = *reinterpret_cast<const uint4*>(x + row * ld + 8 * c);
       unpack8(u, v[j]);
 #pragma unroll
       for (int e = 0; e < 8; e++) sum += v[j][e];
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
         o[e] = (v[j][e] - mean) * rstd * g[e];
         if (KIND == 0) o[e] += b[e];
       }
-      *reinterpret_cast<uint4*>(y + row * d + 8 * c) = pack8(o);
+      *reinterpret_cast<uint4*>(y + row * ld + 8 * c) = pack8(o);
     }
   }
 }
@@ -90,7 +91,8 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
 // normalisation backward.  With xhat = (x - mean) * rstd and dxh = dy * gamma:
 //   LayerNorm: dx = (dxh - mean(dxh) - xhat * mean(dxh * xhat)) * rstd
 //   RMSNorm:   dx = (dxh - xhat * mean(dxh * xhat)) * rstd
-// plus the residual branch's gradient dres.  A workgroup of 256 threads owns one row at a time
+// plus the residual branch's gradient dres.  Rows of dy, x, dres and dx are ld elements apart.
+// A workgroup of 256 threads owns one row at a time
 // (rows b, b + B, ...); a thread keeps NV 16-byte vectors of the row and its own column sums of
 // dy * xhat (and of dy) in registers; they go to partial[b][*] at the end.
 // ---------------------------------------------------------------------------------------------
@@ -98,7 +100,7 @@ template <int KIND, int NV>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(
     const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
-    float* __restrict__ partial, int64_t T, int d) {
+    float* __restrict__ partial, int64_t T, int d, int64_t ld) {
   __shared__ float red[2][2][4];  // [row parity][which sum][wavefront]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int B = gridDim.x, b = blockIdx.x;
@@ -122,8 +124,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
       const int c = tid + 256 * j;
       if (c < nvec) {
         float xv[8], dv[8];
-        unpack8(*reinterpret_cast<const uint4*>(x + row * d + 8 * c), xv);
-        unpack8(*reinterpret_cast<const uint4*>(dy + row * d + 8 * c), dv);
+        unpack8(*reinterpret_cast<const uint4*>(x + row * ld + 8 * c), xv);
+        unpack8(*reinterpret_cast<const uint4*>(dy + row * ld + 8 * c), dv);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           xh[j][e] = (xv[e] - mean) * rstd;
@@ -147,13 +149,13 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
       const int c = tid + 256 * j;
       if (c < nvec) {
         float o[8], r[8];
-        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * d + 8 * c), r);
+        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * ld + 8 * c), r);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd;
           if (dres) o[e] += r[e];
         }
-        *reinterpret_cast<uint4*>(dx + row * d + 8 * c) = pack8(o);
+        *reinterpret_cast<uint4*>(dx + row * ld + 8 * c) = pack8(o);
       }
     }
   }
@@ -408,16 +410,16 @@ inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) /
   else { CALL(16) }
 
 hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const void* beta, void* y,
-                           float* stats, int64_t t, int64_t d, float eps, hipStream_t s) {
+                           float* stats, int64_t t, int64_t d, int64_t ld, float eps, hipStream_t s) {
   if (t == 0) return hipSuccess;
-  if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
+  if (d % 8 != 0 || d > 8192 || ld < d || ld % 8 != 0) return hipErrorInvalidValue;
   ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)t * (double)d, s);
   dim3 grid(blocks_for(t, ROWS_PER_BLOCK)), block(256);
 #define CALL(NV)                                                                                  \
   if (kind == 0) hipLaunchKernelGGL((norm_fwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)x, \
-      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, eps);              \
+      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, ld, eps);              \
   else hipLaunchKernelGGL((norm_fwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)x,           \
-      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, eps);
+      (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats, t, (int)d, ld, eps);
   MLLM_NV_DISPATCH(d / 8, CALL)
 #undef CALL
   return hipGetLastError();
@@ -429,7 +431,7 @@ template <int KIND, int NV>
 __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
     const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
-    float* __restrict__ partial, int64_t T, int d) {
+    float* __restrict__ partial, int64_t T, int d, int64_t ld) {
   __shared__ float red[2][4][1024];  // [d gamma | d beta][wavefront][column]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int B = gridDim.x, b = blockIdx.x;
@@ -454,8 +456,8 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
       for (int e = 0; e < 8; e++) { xh[j][e] = 0.f; dxh[j][e] = 0.f; }
       if (c < nvec) {
         float xv[8], dv[8];
-        unpack8(*reinterpret_cast<const uint4*>(x + row * d + 8 * c), xv);
-        unpack8(*reinterpret_cast<const uint4*>(dy + row * d + 8 * c), dv);
+        unpack8(*reinterpret_cast<const uint4*>(x + row * ld + 8 * c), xv);
+        unpack8(*reinterpret_cast<const uint4*>(dy + row * ld + 8 * c), dv);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           xh[j][e] = (xv[e] - mean) * rstd;
@@ -474,13 +476,13 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
       const int c = lane + 64 * j;
       if (c < nvec) {
         float o[8], r[8];
-        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * d + 8 * c), r);
+        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * ld + 8 * c), r);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd;
           if (dres) o[e] += r[e];
         }
-        *reinterpret_cast<uint4*>(dx + row * d + 8 * c) = pack8(o);
+        *reinterpret_cast<uint4*>(dx + row * ld + 8 * c) = pack8(o);
       }
     }
   }
@@ -507,22 +509,22 @@ int64_t norm_bwd_partial_rows(int64_t t) {
 hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
                            const float* stats, const void* dres, void* dx, float* dgamma,
                            float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
-                           hipStream_t s) {
-  if (d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
+                           int64_t ld, hipStream_t s) {
+  if (d % 8 != 0 || d > 8192 || ld < d || ld % 8 != 0) return hipErrorInvalidValue;
   const int64_t W = norm_bwd_partial_rows(t);
   ProfScope prof(PROF_ELEMENTWISE, (dres ? 8.0 : 6.0) * (double)t * (double)d, s);
   dim3 grid((unsigned)W), block(256);
 #define CALL(NV)                                                                                   \
   if (kind == 0) hipLaunchKernelGGL((norm_bwd_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
-      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d); \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
   else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
-      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld);
   const int64_t nvec = d / 8;
 #define CALL_WAVE(NV)                                                                                   \
   if (kind == 0) hipLaunchKernelGGL((norm_bwd_wave_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
-      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d); \
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
   else hipLaunchKernelGGL((norm_bwd_wave_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
-      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d);
+      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld);
   if (nvec <= 64) { CALL_WAVE(1) } else if (nvec <= 128) { CALL_WAVE(2) }
   else if (nvec <= 256) { CALL(1) } else if (nvec <= 512) { CALL(2) } else { CALL(4) }
 #undef CALL_WAVE

@@ -52,14 +52,15 @@ constexpr int ATTN_BWD_KV_TILE = 128;  // key rows per workgroup, dK/dV pass
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 
-// kind 0 LayerNorm, 1 RMSNorm.  stats: [2][T] fp32 (rstd, mean).
+// kind 0 LayerNorm, 1 RMSNorm.  stats: [2][T] fp32 (rstd, mean).  ld = elements between rows of
+// every [t, d] operand (d for dense matrices; more when they are column slices of a wider one).
 hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const void* beta, void* y,
-                           float* stats, int64_t t, int64_t d, float eps, hipStream_t s);
+                           float* stats, int64_t t, int64_t d, int64_t ld, float eps, hipStream_t s);
 int64_t norm_bwd_partial_rows(int64_t t);
 hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
                            const float* stats, const void* dres, void* dx, float* dgamma,
                            float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
-                           hipStream_t s);
+                           int64_t ld, hipStream_t s);
 hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride, int64_t col0,
                        int32_t n_heads, int32_t head_dim, float rope_base, int inverse,
                        hipStream_t s);

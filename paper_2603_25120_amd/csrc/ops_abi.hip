@@ -183,7 +183,7 @@ mllm_status_t mllm_op_norm_fwd(int kind, const void* x, const void* gamma, const
   if (!x || !gamma || !y || !stats || (kind == 0 && !beta)) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
   if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
   if (t < 0 || d <= 0 || d % 8 || d > 8192) return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 8192");
-  OP_TRY(launch_norm_fwd(kind, x, gamma, beta, y, stats, t, d, eps, (hipStream_t)hip_stream));
+  OP_TRY(launch_norm_fwd(kind, x, gamma, beta, y, stats, t, d, d, eps, (hipStream_t)hip_stream));
   return MLLM_OK;
 }
 
@@ -198,7 +198,7 @@ mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const vo
   if (!dy || !x || !gamma || !stats || !dx || !dgamma || !partial || (kind == 0 && !dbeta)) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
   if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
   if (t < 0 || d <= 0 || d % 8 || d > 8192) return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 8192");
-  OP_TRY(launch_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d, (hipStream_t)hip_stream));
+  OP_TRY(launch_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d, d, (hipStream_t)hip_stream));
   return MLLM_OK;
 }
 

@@ -82,6 +82,7 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
     if (L.pool < 0 || L.pool > 64) return fail(MLLM_ERR_DESC, "layer %d: the connector's pooling width must be in 0..64", i);
     if (L.merge < 0 || L.merge > 64) return fail(MLLM_ERR_DESC, "layer %d: the connector's merge width must be in 0..64", i);
     if (L.merge > 1 && L.pool > 1) return fail(MLLM_ERR_DESC, "layer %d: a connector either pools or merges", i);
+    if (L.qk_norm != 0) return fail(MLLM_ERR_DESC, "layer %d: a connector has no QK normalisation", i);
     if (L.d_ff != 0) {
       if (!m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: the connector's hidden width must be 0 or a positive multiple of 64", i);
       if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: an MLP connector's activation must be GELU", i);
@@ -96,6 +97,7 @@ mllm_status_t check_layer(const mllm_layer_desc_t& L, int i) {
   if (!m64(L.d_model) || !m64(L.d_ff)) return fail(MLLM_ERR_DESC, "layer %d: widths must be positive multiples of 64", i);
   if (L.d_model > 8192) return fail(MLLM_ERR_DESC, "layer %d: d_model above 8192", i);
   if (!(L.norm_eps > 0.f)) return fail(MLLM_ERR_DESC, "layer %d: norm_eps must be positive", i);
+  if (L.qk_norm != 0 && L.qk_norm != 1) return fail(MLLM_ERR_DESC, "layer %d: qk_norm must be 0 or 1", i);
   if (L.kind == MLLM_LAYER_VIT) {
     if (L.has_bias != 1) return fail(MLLM_ERR_DESC, "layer %d: ViT layer needs has_bias = 1", i);
     if (L.act != MLLM_ACT_GELU_ERF && L.act != MLLM_ACT_GELU_TANH) return fail(MLLM_ERR_DESC, "layer %d: ViT activation must be GELU", i);
@@ -179,6 +181,9 @@ struct Bump {
 
 struct LayerSaved {  // byte offsets into `saved`
   size_t x, stats1, n1, qkv, o, lse, x1, stats2, n2, pre, act;
+  // QK normalisation only: qkv then keeps the projection's q and k, and qkn [T, nq] holds the
+  // normalised (and rotated) q and k in the same columns (its v columns are unused)
+  size_t qkn, statsq, statsk;
 };
 
 struct Meta {  // byte offsets into the metadata blob at the head of the workspace
@@ -204,6 +209,7 @@ struct Plan {
   // workspace offsets (after the metadata)
   size_t w_partial = 0;           // fp32 partial sums of norm / bias gradients
   size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0, w_split = 0;
+  size_t w_qkn = 0;               // QK normalisation: gradient of the normalised q, k  [T, nq]
   size_t split_bytes = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
@@ -255,6 +261,11 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     S.stats1 = sv.take(T * 2 * 4);
     S.n1 = sv.take(T * d * 2);
     S.qkv = sv.take(T * nqkv_of(L) * 2);
+    if (L.qk_norm) {
+      S.qkn = sv.take(T * nqkv_of(L) * 2);
+      S.statsq = sv.take(T * 2 * 4);
+      S.statsk = sv.take(T * 2 * 4);
+    }
     S.o = sv.take(T * d * 2);
     S.lse = sv.take(T * L.n_q_heads * 4);
     S.x1 = sv.take(T * d * 2);
@@ -288,7 +299,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   }
   M.bytes = ws.off;
 
-  size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0, split = 0;
+  size_t part = 0, a = 0, bb = 0, c = 0, e = 0, delta = 0, g = 0, proj = 0, split = 0, qkn = 0;
   for (const mllm_layer_desc_t& L : st->layers) {
     if (L.kind == MLLM_LAYER_PROJECTOR) {
       const int64_t d_in = (int64_t)L.d_model * std::max(1, (int)L.merge);
@@ -319,6 +330,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     bb = std::max(bb, L.kind == MLLM_LAYER_DECODER ? T * 2 * f * 2 : 0);
     c = std::max(c, T * d * 2);
     e = std::max(e, T * nq * 2);
+    if (L.qk_norm) qkn = std::max(qkn, T * nq * 2);
     delta = std::max(delta, T * L.n_q_heads * 4);
     g = std::max(g, T * d * 2);
     const int64_t fup = L.kind == MLLM_LAYER_VIT ? f : 2 * f;
@@ -335,6 +347,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
   P.w_c = ws.take(c);
   P.w_d = ws.take(c);
   P.w_e = ws.take(e);
+  P.w_qkn = ws.take(qkn);
   P.w_delta = ws.take(delta);
   P.w_g0 = ws.take(g);
   P.w_g1 = ws.take(g);
@@ -441,14 +454,16 @@ hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t
   return gemm(x, k, 1, dy, n, 0, dw, n, k, n, T, 1, accumulate, nullptr, nullptr, 0, s, ws.p, ws.bytes);
 }
 
-AttnArgs attn_args(const mllm_layer_desc_t& L, char* qkv, int64_t T, const char* ws, const Plan& P, bool img) {
+// qk: the [T, nq] matrix whose q and k columns attention reads; v: the one whose v columns it reads
+// (the same matrix unless the layer normalises q and k).
+AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, const char* ws, const Plan& P, bool img) {
   const Meta& M = P.meta;
   AttnArgs a;
   memset(&a, 0, sizeof a);
   const int64_t nq = nqkv_of(L);
-  a.q = qkv;
-  a.k = qkv + (int64_t)L.n_q_heads * L.head_dim * 2;
-  a.v = qkv + (int64_t)(L.n_q_heads + L.n_kv_heads) * L.head_dim * 2;
+  a.q = qk;
+  a.k = qk + (int64_t)L.n_q_heads * L.head_dim * 2;
+  a.v = v + (int64_t)(L.n_q_heads + L.n_kv_heads) * L.head_dim * 2;
   a.q_stride = a.kv_stride = nq;
   a.o_stride = L.d_model;
   a.total_tokens = (int32_t)T;
@@ -490,18 +505,27 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
              g2 = prm[6]; b2n = prm[7]; wup = prm[8]; bup = prm[9]; wdn = prm[10]; bdn = prm[11]; }
   else if (L.has_bias) { g1 = prm[0]; wqkv = prm[1]; bqkv = prm[2]; wo = prm[3]; g2 = prm[4]; wup = prm[5]; wdn = prm[6]; }
   else { g1 = prm[0]; wqkv = prm[1]; wo = prm[2]; g2 = prm[3]; wup = prm[4]; wdn = prm[5]; }
+  const int n_base = vit ? 12 : (L.has_bias ? 7 : 6);   // the QK-norm gains follow the layer's other tensors
+  const int64_t q_cols = (int64_t)L.n_q_heads * L.head_dim, k_cols = (int64_t)L.n_kv_heads * L.head_dim;
 
-  K_TRY(launch_norm_fwd(vit ? 0 : 1, x, g1, b1n, n1, (float*)(saved + S.stats1), T, d, L.norm_eps, s));
+  K_TRY(launch_norm_fwd(vit ? 0 : 1, x, g1, b1n, n1, (float*)(saved + S.stats1), T, d, d, L.norm_eps, s));
   K_TRY(linear_fwd(n1, wqkv, qkv, T, d, nq, bqkv, nullptr, s));
+  char* qk = qkv;
+  if (L.qk_norm) {
+    qk = saved + S.qkn;
+    K_TRY(launch_norm_fwd(1, qkv, prm[n_base], nullptr, qk, (float*)(saved + S.statsq), T, q_cols, nq, L.norm_eps, s));
+    K_TRY(launch_norm_fwd(1, qkv + q_cols * 2, prm[n_base + 1], nullptr, qk + q_cols * 2,
+                          (float*)(saved + S.statsk), T, k_cols, nq, L.norm_eps, s));
+  }
   if (!vit)
-    K_TRY(launch_rope(qkv, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
+    K_TRY(launch_rope(qk, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 0, s));
-  AttnArgs a = attn_args(L, qkv, T, ws, P, vit);
+  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit);
   a.o = o;
   a.lse = (float*)(saved + S.lse);
   K_TRY(launch_attn_fwd(a, s));
   K_TRY(linear_fwd(o, wo, x1, T, d, d, bo, x, s));
-  K_TRY(launch_norm_fwd(vit ? 0 : 1, x1, g2, b2n, n2, (float*)(saved + S.stats2), T, d, L.norm_eps, s));
+  K_TRY(launch_norm_fwd(vit ? 0 : 1, x1, g2, b2n, n2, (float*)(saved + S.stats2), T, d, d, L.norm_eps, s));
   K_TRY(linear_fwd(n2, wup, pre, T, d, vit ? f : 2 * f, bup, nullptr, s));
   K_TRY(launch_act_fwd(L.act, pre, act, T, f, s));
   K_TRY(linear_fwd(act, wdn, y, T, f, d, bdn, x1, s));
@@ -545,28 +569,42 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   if (vit) K_TRY(launch_colsum(dpre, fup, (float*)dprm[ibup], accumulate, partial, T, fup, s));
   K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x1, prm[ig2], (const float*)(saved + S.stats2), dy, wd,
-                        (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, s));
+                        (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, d, s));
   // attention block
   K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
   K_TRY(linear_dx(wd, prm[iwo], wc, T, d, d, s));
-  AttnArgs a = attn_args(L, qkv, T, ws, P, vit);
+  // With QK normalisation the gradient of the normalised q, k goes to a matrix of its own (same
+  // columns as in d qkv); the norm's backward then writes the gradient of the projection's q, k
+  // beside dV in d qkv.
+  const int n_base = vit ? 12 : (L.has_bias ? 7 : 6);
+  const int64_t q_cols = (int64_t)L.n_q_heads * L.head_dim, k_cols = (int64_t)L.n_kv_heads * L.head_dim;
+  char* qk = L.qk_norm ? const_cast<char*>(saved + S.qkn) : qkv;
+  char* dqk = L.qk_norm ? ws + P.w_qkn : we;
+  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit);
   a.o = const_cast<char*>(o);
   a.lse = (float*)const_cast<char*>(saved + S.lse);
   a.d_o = wc;
-  a.dq = we;
-  a.dk = we + (int64_t)L.n_q_heads * L.head_dim * 2;
-  a.dv = we + (int64_t)(L.n_q_heads + L.n_kv_heads) * L.head_dim * 2;
+  a.dq = dqk;
+  a.dk = dqk + q_cols * 2;
+  a.dv = we + (q_cols + k_cols) * 2;
   a.delta = (float*)(ws + P.w_delta);
   K_TRY(launch_attn_bwd(a, s));
   if (!vit)
-    K_TRY(launch_rope(we, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
+    K_TRY(launch_rope(dqk, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 1, s));
+  if (L.qk_norm) {
+    K_TRY(launch_norm_bwd(1, dqk, qkv, prm[n_base], (const float*)(saved + S.statsq), nullptr, we,
+                          (float*)dprm[n_base], nullptr, accumulate, partial, T, q_cols, nq, s));
+    K_TRY(launch_norm_bwd(1, dqk + q_cols * 2, qkv + q_cols * 2, prm[n_base + 1], (const float*)(saved + S.statsk),
+                          nullptr, we + q_cols * 2, (float*)dprm[n_base + 1], nullptr, accumulate, partial,
+                          T, k_cols, nq, s));
+  }
   K_TRY(linear_dw(n1, we, dprm[iwqkv], T, d, nq, accumulate, s, split));
   if (ibqkv >= 0) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
   K_TRY(linear_dx(we, prm[iwqkv], wc, T, d, nq, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x, prm[ig1], (const float*)(saved + S.stats1), wd, dx,
-                        (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, s));
+                        (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, d, s));
   return MLLM_OK;
 }
 
@@ -649,6 +687,10 @@ mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** ou
       const int64_t d_in = d * std::max(1, (int)L.merge);
       const ParamInfo ps[] = {{"w_p", i, d_in, L.d_out}, {"b_p", i, 1, L.d_out}};
       st->params.insert(st->params.end(), std::begin(ps), std::end(ps));
+    }
+    if (L.kind != MLLM_LAYER_PROJECTOR && L.qk_norm) {
+      st->params.push_back({"qkn_q_g", i, 1, (int64_t)L.n_q_heads * L.head_dim});
+      st->params.push_back({"qkn_k_g", i, 1, (int64_t)L.n_kv_heads * L.head_dim});
     }
   }
   *out = st;

@@ -35,7 +35,8 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_param_table_matches_the_generator(B):
     for layers in (W.tiny_stage_layers(), W.full_stage_layers(2, 2), [W.dec7b_layer()], [W.vit_l_layer()],
-                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()], W.tiny_pooled_layers(), W.tiny_merged_layers()):
+                   W.tiny_variant_layers(), [W.dec_qkvbias_7b_layer()], W.tiny_pooled_layers(), W.tiny_merged_layers(),
+                   W.tiny_qknorm_layers(), [W.decoder_layer(256, 4, 2, 64, 512, 1e4, qkv_bias=1, qk_norm=1)]):
         h = B.mllm_stage_create(layers)
         got = [B.mllm_stage_param_info(h, i) for i in range(B.mllm_stage_param_count(h))]
         want = [(n, li, r, c) for li, L in enumerate(layers) for n, r, c in W.param_specs(L)]
@@ -67,6 +68,8 @@ def test_descriptor_validation(B):
         [vit, _bad(proj, d_ff=128, act=W.ACT_SWIGLU), dec],        # MLP connector needs a GELU
         [vit, _bad(proj, pool=-1), dec],                           # pooling width out of range
         [vit, _bad(proj, pool=2, merge=2), dec],                   # a connector either pools or merges
+        [_bad(dec, qk_norm=2)],                                    # QK normalisation is 0 or 1
+        [vit, _bad(proj, qk_norm=1), dec],                         # a connector has none
         [],
     ]
     for layers in cases:

@@ -1,7 +1,9 @@
 """Seeded random stage configurations against the fp64 oracle: head geometry, widths, layer kinds,
-connector kinds and ragged segment mixes that the hand-picked cases do not reach (odd segment
+connector kinds, QK normalisation and ragged segment mixes that the hand-picked cases do not reach (odd segment
 lengths, empty segments, single-token samples, text-only and image-only samples, tile tails of
 every size).  Every output and every gradient is held to the stated tolerances."""
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -69,6 +71,8 @@ def random_case(seed):
         if sum(k for k, _ in samples) == 0:
             samples.append((1, 0))                # an image-only sample
         batch = W.batch_from_samples(samples, img_tokens=img_tokens, pool=max(1, reduce[0], reduce[1]))
+    if seed % 4 == 1:                             # QK normalisation in every transformer layer of the case
+        layers = [l if l.kind == W.LAYER_PROJECTOR else dataclasses.replace(l, qk_norm=1) for l in layers]
     return layers, batch
 
 

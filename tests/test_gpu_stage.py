@@ -66,6 +66,48 @@ def test_tiny_merged_stage_matches_oracle(B, seed):
         st.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_qknorm_stage_matches_oracle(B, seed):
+    """RMS-normalised q and k rows in the encoder layer and in a grouped-query decoder layer."""
+    wl = W.workload_tiny_qknorm(seed)
+    st = GpuStage(B, wl.layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
+@pytest.mark.parametrize("case", ["vit_wide", "dec_gqa_hd128", "dec_bias_two_layers"])
+def test_qk_norm_layer_shapes(B, case):
+    """QK normalisation at widths that take each form of the norm kernels (rows of 128 to 2048
+    values inside a wider QKV matrix), ragged segments with an empty and a one-token one."""
+    if case == "vit_wide":
+        layers = [W.vit_layer(1280, 20, 64, 512, qk_norm=1)]
+        batch = W.Batch(W.make_pack([130, 0, 1, 77], W.MASK_BIDIR), None, None, [])
+    elif case == "dec_gqa_hd128":
+        layers = [W.decoder_layer(2048, 16, 2, 128, 512, 500000.0, qk_norm=1)]
+        batch = W.Batch(None, W.make_pack([150, 1, 0, 93], W.MASK_CAUSAL), None, [])
+    else:
+        first = W.decoder_layer(512, 8, 1, 64, 256, 10000.0, qkv_bias=1, qk_norm=1)
+        layers = [first, W.decoder_layer(512, 8, 8, 64, 320, 10000.0, qk_norm=1)]
+        batch = W.Batch(None, W.make_pack([260, 3], W.MASK_CAUSAL), None, [])
+    _layer_case(B, layers, batch, 41)
+
+
+def test_qk_norm_gradients_accumulate(B):
+    wl = W.workload_tiny_qknorm(3)
+    st = GpuStage(B, wl.layers)
+    try:
+        a = st.run(wl)
+        acc = [torch.zeros_like(g) for g in a[3]]
+        st.run(wl, accumulate=1, dparams=acc)
+        st.run(wl, accumulate=1, dparams=acc)
+        for g2, g1 in zip(acc, a[3]):
+            assert nmax_err(host_f64(g2), 2 * host_f64(g1)) < 1e-5
+    finally:
+        st.close()
+
+
 def test_pooled_mlp_connector_ragged_segments(B):
     """Pooling by 4 over encoder segments of 1, 4, 9 and 130 tokens, MLP connector, image-only and
     text-only samples."""
