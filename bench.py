@@ -62,6 +62,9 @@ def build_workload(name: str):
     elif name == "vit_l":
         wl = W.workload_vit_l(100, with_data=False)
         desc = "one ViT-L/14-336 layer, 16 samples x 1..4 images of 576 tokens, seed 100"
+    elif name == "internvit_6b":
+        wl = W.workload_internvit_6b(700, with_data=False)
+        desc = "one QK-normalised encoder layer of the large InternViT shape (d 3200, 25 heads of 128, MLP 12800), 23 tiles of 1025 tokens, seed 700"
     else:
         raise SystemExit("unknown workload %r" % name)
     return wl, desc

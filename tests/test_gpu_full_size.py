@@ -76,6 +76,19 @@ def test_variant_stage_full_width(B):
         st.close()
 
 
+def test_internvit_6b_layer_full_width(B):
+    """QK-normalised encoder layer at the large InternViT width (d = 3200, 25 heads of 128, MLP
+    12800) on one whole tile of 1025 tokens and a ragged one of 300: every output and gradient."""
+    layers = [W.internvit_6b_layer()]
+    batch = W.Batch(W.make_pack([W.INTERNVIT_TILE_TOKENS, 300], W.MASK_BIDIR), None, None, [])
+    wl = W.make_workload("internvit_6b", layers, batch, 701)
+    st = GpuStage(B, layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec8b_layer_sampled_samples(B):
     wl = W.workload_dec8b(300)                       # 32768 packed tokens, GQA 32/8, SwiGLU 14336
     st = GpuStage(B, wl.layers)

@@ -395,6 +395,33 @@ def dec_qkvbias_7b_layer() -> LayerDesc:
     return decoder_layer(3584, 28, 4, 128, 18944, 1000000.0, eps=1e-6, qkv_bias=1)
 
 
+def internvit_6b_layer() -> LayerDesc:
+    """Encoder layer with the attention and MLP shape of the large InternViT of the evaluated
+    InternVL model (Table 4): d = 3200, 25 heads of 128, MLP 12800, QK normalisation."""
+    return vit_layer(3200, 25, 128, 12800, eps=1e-6, qk_norm=1)
+
+
+INTERNVIT_TILE_TOKENS = 1025      # a 448 x 448 tile in 14 x 14 patches plus the class token
+
+
+def workload_internvit_6b(seed: int, budget: int = 24576, with_data=True) -> Workload:
+    """One such layer on a microbatch of dynamic-resolution images: every image is cut into 1..12
+    tiles plus a thumbnail tile (each tile a bidirectional segment of 1025 tokens), images are
+    drawn until the token budget is reached."""
+    rng = np.random.default_rng(seed)
+    tiles, total = [], 0
+    while True:
+        n = int(rng.integers(1, 13)) + 1
+        if total + n * INTERNVIT_TILE_TOKENS > budget:
+            n = (budget - total) // INTERNVIT_TILE_TOKENS
+        if n <= 0:
+            break
+        tiles.append(n)
+        total += n * INTERNVIT_TILE_TOKENS
+    batch = Batch(make_pack([INTERNVIT_TILE_TOKENS] * sum(tiles), MASK_BIDIR), None, None, [])
+    return make_workload("internvit_6b", [internvit_6b_layer()], batch, seed, with_data)
+
+
 def workload_vit_l(seed: int, n_images: Optional[int] = None, with_data=True) -> Workload:
     n = n_images if n_images is not None else sum(draw_images_vit(seed))
     batch = Batch(make_pack([IMG_TOKENS] * n, MASK_BIDIR), None, None, [])
