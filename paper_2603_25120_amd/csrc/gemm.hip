@@ -251,9 +251,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_kernel(GemmPa
 // With a single wavefront per SIMD nothing else hides a stall, so the k-loop is written slot by
 // slot: every MFMA slot names the LDS read, LDS store and global load that issue in front of it and
 // a scheduling barrier after every slot keeps that order.  Two sets of staging registers: a
-// global load has two whole iterations to land.  Needs K to be a multiple of 64: the k-advance of
-// the global loads is a scalar offset (no per-load address arithmetic), clamped to the last tile
-// so that no address leaves the operand.
+// global load has two whole iterations to land.  The k-advance of the global loads is a scalar
+// offset (no per-load address arithmetic), clamped to the last tile so that no address leaves the
+// operand; that needs K to be a multiple of 64, except in the ragged-K form for operands stored
+// [K, .], which sends the last tile's advance through the range-checked lane offsets.
 template <class F, int... Is>
 __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, Is...>) {
   (f(std::integral_constant<int, Is>{}), ...);
@@ -288,6 +289,14 @@ struct ScalarStepLoader {
   __device__ __forceinline__ void load1(__amdgpu_buffer_rsrc_t rsrc, uint32_t soff) {
     r[S][I] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off[I], (int)soff, 0);
   }
+  // The same with part of the k-advance in the lane's own offset, which the buffer's range check
+  // sees (the scalar offset it does not): rows past the operand's end then read as zeros.
+  template <int S, int I>
+  __device__ __forceinline__ void load1_checked(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_adv, uint32_t soff) {
+    uint32_t v = off[I] + lane_adv;
+    v = v < lane_adv ? OOB : v;   // an offset that is OOB already stays so instead of wrapping
+    r[S][I] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)v, (int)soff, 0);
+  }
   template <int S, int I>
   __device__ __forceinline__ void store1(bf16_t* lds, int tid) const {
     const int v = tid + I * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
@@ -295,11 +304,23 @@ struct ScalarStepLoader {
   }
 };
 
-template <int TM, bool A_T, bool B_T, bool OUT_F32>
-__global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
+// k-advance of the loads of k-tile t: all of it in the scalar offset, except (RAGGED_K) for the
+// last, partial k-tile, where it goes through the lanes' offsets so that the range check applies.
+struct KAdvance { uint32_t lane, scalar; };
+template <bool RAGGED_K>
+__device__ __forceinline__ KAdvance k_advance(uint32_t t, uint32_t last_tile, uint32_t kstep) {
+  if (RAGGED_K && t == last_tile) return {t * kstep, 0u};
+  return {0u, t * kstep};
+}
+
+template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K>
+__device__ __forceinline__ void gemm4_tile(GemmParams p) {
   // TM = 4: 256x256 tiles, wavefronts of 128x128.  TM = 3: 192x256 tiles, wavefronts of 96x128,
   // for problems whose 256-row tiles would leave the last round of workgroups mostly empty.
   static_assert(TM == 4 || (TM == 3 && !A_T), "192-row tiles only for an A operand stored [M, K]");
+  // RAGGED_K: K need not be a multiple of 64.  Only when k runs along the rows of both operands:
+  // the rows of the last k-tile that lie past K are then past the end of the operand.
+  static_assert(!RAGGED_K || (A_T && B_T), "a ragged K needs both operands stored [K, .]");
   constexpr int BM = 64 * TM, BN = 256, WM = 32 * TM, WN = 128, NT = 256, TN = 4;
   constexpr int NA = 2 * TM;          // A vectors per thread and k-tile (B: 8)
   constexpr int NU = TM + 4;          // fragment units per k-step
@@ -332,14 +353,32 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   f32x16 acc[TM][TN];
 
   const int kt0 = blockIdx.y * p.kt_per_split;
-  const int last_tile = (int)(p.K / BK) - 1;
+  const int last_tile = (int)((p.K + BK - 1) / BK) - 1;
   // a split past the end of K (the last ones, when K does not divide evenly) has no k-tiles: zeros
   const int nk = max(0, min(p.kt_per_split, last_tile + 1 - kt0));
+  auto load_a = [&](auto s_c, auto i_c, uint32_t t) __attribute__((always_inline)) {
+    constexpr int S = decltype(s_c)::value, I = decltype(i_c)::value;
+    if constexpr (RAGGED_K) {
+      const KAdvance k = k_advance<true>(t, (uint32_t)last_tile, la.kstep);
+      la.template load1_checked<S, I>(ra, k.lane, k.scalar);
+    } else {
+      la.template load1<S, I>(ra, t * la.kstep);
+    }
+  };
+  auto load_b = [&](auto s_c, auto i_c, uint32_t t) __attribute__((always_inline)) {
+    constexpr int S = decltype(s_c)::value, I = decltype(i_c)::value;
+    if constexpr (RAGGED_K) {
+      const KAdvance k = k_advance<true>(t, (uint32_t)last_tile, lb.kstep);
+      lb.template load1_checked<S, I>(rb, k.lane, k.scalar);
+    } else {
+      lb.template load1<S, I>(rb, t * lb.kstep);
+    }
+  };
   auto load_all = [&](auto s_c, int kt) {
     constexpr int S = decltype(s_c)::value;
     const uint32_t t = (uint32_t)min(kt, last_tile);
-    static_for<NA>([&](auto i) { la.template load1<S, decltype(i)::value>(ra, t * la.kstep); });
-    static_for<8>([&](auto i) { lb.template load1<S, decltype(i)::value>(rb, t * lb.kstep); });
+    static_for<NA>([&](auto i) { load_a(s_c, i, t); });
+    static_for<8>([&](auto i) { load_b(s_c, i, t); });
   };
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
@@ -355,7 +394,7 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
   {
     const uint32_t t = (uint32_t)min(kt0 + 3, last_tile);
     static_for<Q3>([&](auto i) { la.template store1<1, decltype(i)::value>(As + A_SIZE, tid); });
-    static_for<Q3>([&](auto i) { la.template load1<1, decltype(i)::value>(ra, t * la.kstep); });
+    static_for<Q3>([&](auto i) { load_a(C1{}, i, t); });
   }
   __syncthreads();
 
@@ -379,7 +418,6 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
     const bf16_t* at = As + P * A_SIZE;
     const bf16_t* bt = Bs + P * B_SIZE;
     const uint32_t t3 = (uint32_t)min(kt0 + kt + 3, last_tile), t4 = (uint32_t)min(kt0 + kt + 4, last_tile);
-    const uint32_t sa3 = t3 * la.kstep, sb3 = t3 * lb.kstep, sa4 = t4 * la.kstep, sb4 = t4 * lb.kstep;
     // The tile move, vector q of NA + 8 (A vectors, then B vectors).  k-steps 0..2 move vectors
     // Q3.. of tile kt+1 (set P^1 -> the other stage, refilled with tile kt+3); k-step 3, once the
     // barrier has freed this tile's own stage, vectors 0..Q3-1 of tile kt+2 (set P -> this stage,
@@ -391,8 +429,9 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
     };
     auto move_load = [&](auto kk_c, auto q_c) __attribute__((always_inline)) {
       constexpr int kk = decltype(kk_c)::value, q = decltype(q_c)::value, S = kk == 3 ? P : (P ^ 1);
-      if constexpr (q < NA) la.template load1<S, q>(ra, kk == 3 ? sa4 : sa3);
-      else lb.template load1<S, q - NA>(rb, kk == 3 ? sb4 : sb3);
+      using SC = std::integral_constant<int, S>;
+      if constexpr (q < NA) load_a(SC{}, q_c, kk == 3 ? t4 : t3);
+      else load_b(SC{}, std::integral_constant<int, q - NA>{}, kk == 3 ? t4 : t3);
     };
     // slot m of k-step kk: MFMA block (m / 4, m % 4), preceded by one memory operation.
     //   TM = 4 (16 slots): even m reads fragment unit m/2 of the next k-step (in the last k-step,
@@ -464,8 +503,21 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
-// The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64.
-bool takes_gemm4(const GemmArgs& g) { return g.k >= BK && g.k % BK == 0; }
+template <int TM, bool A_T, bool B_T, bool OUT_F32>
+__global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
+  gemm4_tile<TM, A_T, B_T, OUT_F32, false>(p);
+}
+// Weight gradients over a token count that is no multiple of 64.
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void gemm4_ragged_k_kernel(GemmParams p) {
+  gemm4_tile<4, true, true, OUT_F32, true>(p);
+}
+
+// The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64,
+// or any K >= 64 when k runs along the rows of both operands (the weight-gradient layout).
+bool takes_gemm4(const GemmArgs& g) {
+  return g.k >= BK && (g.k % BK == 0 || (g.a_layout != 0 && g.b_layout == 0));
+}
 // Its 192-row form when that saves rounds of one-per-CU workgroups.  A round of 192-row tiles
 // has three quarters of the MFMA work but the same prologue and epilogue: measured at 0.9 of a
 // round of 256-row tiles for K = 1024..4096.  Only for A stored [M, K] and unsplit problems.
@@ -497,6 +549,12 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
     if constexpr (!AT) {                                                                 \
       if (rows192) {                                                                     \
         hipLaunchKernelGGL((gemm4_kernel<3, AT, BT, F32>), grid, block4, 0, s, p);       \
+        return hipGetLastError();                                                        \
+      }                                                                                  \
+    }                                                                                    \
+    if constexpr (AT && BT) {                                                            \
+      if (g.k % BK != 0) {                                                               \
+        hipLaunchKernelGGL((gemm4_ragged_k_kernel<F32>), grid, block4, 0, s, p);         \
         return hipGetLastError();                                                        \
       }                                                                                  \
     }                                                                                    \

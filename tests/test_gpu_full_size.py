@@ -56,6 +56,20 @@ def test_weight_gradient_split_with_empty_last_parts(B):
         st.close()
 
 
+def test_weight_gradient_split_over_ragged_token_count(B):
+    """ViT-L layer on 7 images of 577 tokens: 4039 tokens are 63 k-tiles of 64 and one of 7 rows, and
+    the layer's weight gradients are cut along the tokens into parts, the last of which holds the
+    partial k-tile."""
+    layers = [W.vit_l_layer()]
+    batch = W.Batch(W.make_pack([577] * 7, W.MASK_BIDIR), None, None, [])
+    wl = W.make_workload("vit_ragged_tokens", layers, batch, 911)
+    st = GpuStage(B, layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec7b_layer_full(B):
     wl = W.workload_dec7b(200)                       # 8192 packed tokens, d = 4096, MHA, SwiGLU 11008
     st = GpuStage(B, wl.layers)

@@ -96,6 +96,31 @@ def test_gemm_large_tiles_k_multiple_of_64(B, k, a_layout, b_layout, f32):
         assert nmax_err(host_f64(c), ref + bias + res) < 1e-2
 
 
+@pytest.mark.parametrize("k", [65, 127, 129, 200, 1000, 2350])
+@pytest.mark.parametrize("f32", [1, 0])
+def test_gemm_large_tiles_weight_gradient_ragged_k(B, k, f32):
+    """The weight-gradient layout (both operands stored [K, .]) keeps the four-wavefront kernel when
+    K is no multiple of 64: the rows of the last k-tile past K must read as zeros.  The operands are
+    the leading K rows of longer buffers whose later rows hold large values, so a row read past K
+    would show."""
+    m, n = 3512, 4104
+    a = W.draw_tensor(171, k + 64, m)
+    b = W.bf16_round(W.draw_tensor(172, k + 64, n) * np.float32(0.125))
+    a[k:] = 1000.0
+    b[k:] = 1000.0
+    ref = a[:k].T.astype(np.float64) @ b[:k].astype(np.float64)
+    a_dev, b_dev = dev_bf16(a), dev_bf16(b)
+    if f32:
+        init = np.random.default_rng(174).standard_normal((m, n)).astype(np.float32)
+        c = torch.from_numpy(init.copy()).cuda()
+        B.mllm_op_gemm(a_dev, b_dev, c, m, n, k, 1, 0, out_fp32=1, accumulate=1)
+        assert nmax_err(host_f64(c), ref + init) < 2e-3
+    else:
+        c = empty_bf16(m, n)
+        B.mllm_op_gemm(a_dev, b_dev, c, m, n, k, 1, 0)
+        assert nmax_err(host_f64(c), ref) < 1e-2
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_gemm_large_tiles_random_shapes(B, seed):
     """Seeded random problems that take the four-wavefront kernel: ragged M and N in every
