@@ -306,24 +306,51 @@ __global__ void swiglu_bwd_kernel(const bf16_t* __restrict__ da, const bf16_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
-// column sums (bias gradients), stage 1: row chunk blockIdx.y, 8 columns per thread
+// column sums (bias gradients), stage 1: a workgroup owns 512 columns (8 per lane) and row chunk
+// blockIdx.y; its four wavefronts take every fourth row of the chunk, four loads in flight each,
+// and their sums are added through LDS in a fixed order.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void colsum_partial_kernel(const bf16_t* __restrict__ x, int64_t ldx,
-                                                            float* __restrict__ partial, int64_t T,
-                                                            int64_t n) {
-  const int64_t c = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 8;
-  if (c >= n) return;
-  const int P = gridDim.y;
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ x, int64_t ldx,
+                                                             float* __restrict__ partial, int64_t T,
+                                                             int64_t n) {
+  __shared__ float red[3][64][8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * 8;
+  const bool valid = c < n;
+  const int64_t step = (int64_t)gridDim.y * 4;
   float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int64_t r = blockIdx.y; r < T; r += P) {
-    float v[8];
-    unpack8(*reinterpret_cast<const uint4*>(x + r * ldx + c), v);
+  if (valid) {
+    const bf16_t* col = x + c;
+    int64_t r = (int64_t)blockIdx.y * 4 + wave;
+    for (; r + 3 * step < T; r += 4 * step) {
+      const uint4 u0 = *reinterpret_cast<const uint4*>(col + r * ldx);
+      const uint4 u1 = *reinterpret_cast<const uint4*>(col + (r + step) * ldx);
+      const uint4 u2 = *reinterpret_cast<const uint4*>(col + (r + 2 * step) * ldx);
+      const uint4 u3 = *reinterpret_cast<const uint4*>(col + (r + 3 * step) * ldx);
+      float v0[8], v1[8], v2[8], v3[8];
+      unpack8(u0, v0); unpack8(u1, v1); unpack8(u2, v2); unpack8(u3, v3);
 #pragma unroll
-    for (int e = 0; e < 8; e++) s[e] += v[e];
+      for (int e = 0; e < 8; e++) s[e] += (v0[e] + v1[e]) + (v2[e] + v3[e]);
+    }
+    for (; r < T; r += step) {
+      float v[8];
+      unpack8(*reinterpret_cast<const uint4*>(col + r * ldx), v);
+#pragma unroll
+      for (int e = 0; e < 8; e++) s[e] += v[e];
+    }
   }
-  float* p = partial + (int64_t)blockIdx.y * n + c;
-  *reinterpret_cast<float4*>(p) = make_float4(s[0], s[1], s[2], s[3]);
-  *reinterpret_cast<float4*>(p + 4) = make_float4(s[4], s[5], s[6], s[7]);
+  if (wave > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) red[wave - 1][lane][e] = s[e];
+  }
+  __syncthreads();
+  if (wave == 0 && valid) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) s[e] = (s[e] + red[0][lane][e]) + (red[1][lane][e] + red[2][lane][e]);
+    float* p = partial + (int64_t)blockIdx.y * n + c;
+    *reinterpret_cast<float4*>(p) = make_float4(s[0], s[1], s[2], s[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(s[4], s[5], s[6], s[7]);
+  }
 }
 
 __global__ void scatter_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
@@ -580,9 +607,9 @@ hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, 
   return hipGetLastError();
 }
 
-int64_t colsum_partial_rows(int64_t t) {
-  if (t < 1) return 1;
-  return t < 512 ? t : 512;
+int64_t colsum_partial_rows(int64_t t) {   // row chunks of (at least) four rows, at most 512
+  if (t < 4) return 1;
+  return t < 2048 ? t / 4 : 512;
 }
 
 hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate, float* partial,
@@ -590,7 +617,7 @@ hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate,
   if (n % 8 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
   const int64_t P = colsum_partial_rows(t);
   ProfScope prof(PROF_ELEMENTWISE, 2.0 * (double)t * (double)n, s);
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks_for(n, 512), (unsigned)P), dim3(64), 0, s,
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks_for(n, 512), (unsigned)P), dim3(256), 0, s,
                      (const bf16_t*)x, ldx, partial, t, n);
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(n, RED_COLS)), dim3(256), 0, s, partial,
                      out, (int)P, n, accumulate);
