@@ -471,20 +471,36 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
 #pragma unroll
     for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; if (c >= nvec) g[j][e] = 0.f; }
   }
-  for (int64_t row = (int64_t)b * 4 + wave; row < T; row += (int64_t)4 * B) {
+  // The next row's loads are issued before this row's arithmetic: two rows in flight per wavefront.
+  uint4 nx[NV], ndy[NV], nres[NV];
+  auto fetch = [&](int64_t row) {
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        nx[j] = *reinterpret_cast<const uint4*>(x + row * ld + 8 * c);
+        ndy[j] = *reinterpret_cast<const uint4*>(dy + row * ld + 8 * c);
+        if (dres) nres[j] = *reinterpret_cast<const uint4*>(dres + row * ld + 8 * c);
+      }
+    }
+  };
+  const int64_t row0 = (int64_t)b * 4 + wave, row_step = (int64_t)4 * B;
+  if (row0 < T) fetch(row0);
+  for (int64_t row = row0; row < T; row += row_step) {
     const float rstd = stats[row];
     const float mean = KIND == 0 ? stats[T + row] : 0.f;
-    float xh[NV][8], dxh[NV][8];
+    float xh[NV][8], dxh[NV][8], r[NV][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; j++) {
       const int c = lane + 64 * j;
 #pragma unroll
-      for (int e = 0; e < 8; e++) { xh[j][e] = 0.f; dxh[j][e] = 0.f; }
+      for (int e = 0; e < 8; e++) { xh[j][e] = 0.f; dxh[j][e] = 0.f; r[j][e] = 0.f; }
       if (c < nvec) {
         float xv[8], dv[8];
-        unpack8(*reinterpret_cast<const uint4*>(x + row * ld + 8 * c), xv);
-        unpack8(*reinterpret_cast<const uint4*>(dy + row * ld + 8 * c), dv);
+        unpack8(nx[j], xv);
+        unpack8(ndy[j], dv);
+        if (dres) unpack8(nres[j], r[j]);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           xh[j][e] = (xv[e] - mean) * rstd;
@@ -496,19 +512,16 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
         }
       }
     }
+    if (row + row_step < T) fetch(row + row_step);
     const float m2 = wave_sum(s2) / (float)d;
     const float m1 = KIND == 0 ? wave_sum(s1) / (float)d : 0.f;
 #pragma unroll
     for (int j = 0; j < NV; j++) {
       const int c = lane + 64 * j;
       if (c < nvec) {
-        float o[8], r[8];
-        if (dres) unpack8(*reinterpret_cast<const uint4*>(dres + row * ld + 8 * c), r);
+        float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-          o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd;
-          if (dres) o[e] += r[e];
-        }
+        for (int e = 0; e < 8; e++) o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd + r[j][e];
         *reinterpret_cast<uint4*>(dx + row * ld + 8 * c) = pack8(o);
       }
     }
@@ -538,7 +551,11 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
                            float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
                            int64_t ld, hipStream_t s) {
   if (d % 8 != 0 || d > 8192 || ld < d || ld % 8 != 0) return hipErrorInvalidValue;
-  const int64_t W = norm_bwd_partial_rows(t);
+  const int64_t nvec = d / 8;
+  // Workgroups (= rows of partial sums).  The wavefront-per-row kernel with two vectors per lane
+  // keeps three workgroups per CU resident: a grid of 768 runs in one round.
+  int64_t W = norm_bwd_partial_rows(t);
+  if (nvec > 64 && nvec <= 128) W = std::min<int64_t>(W, 768);
   ProfScope prof(PROF_ELEMENTWISE, (dres ? 8.0 : 6.0) * (double)t * (double)d, s);
   dim3 grid((unsigned)W), block(256);
 #define CALL(NV)                                                                                   \
@@ -546,7 +563,6 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
   else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld);
-  const int64_t nvec = d / 8;
 #define CALL_WAVE(NV)                                                                                   \
   if (kind == 0) hipLaunchKernelGGL((norm_bwd_wave_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
