@@ -175,31 +175,47 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
   }
 }
 
-// out[c] (+)= sum_p partial[p][c].  A workgroup owns 16 columns: 64 row slices x 4 float4 column
-// groups; slice s adds rows s, s+64, ... in order, then the 64 slice sums are added in order:
-// a fixed association, so the result is bitwise reproducible.
-constexpr int RED_COLS = 16, RED_SLICES = 64;
+// out[c] (+)= sum_p partial[p][c].  A workgroup owns 8 columns: 128 row slices x 2 float4 column
+// groups; slice s adds rows s, s+128, ... in order (four loads in flight), then the slice sums are
+// added pairwise (s with s+64, then s with s+32, ...): a fixed association, so the result is
+// bitwise reproducible.
+constexpr int RED_COLS = 8, RED_SLICES = 128;
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
                                                               float* __restrict__ out, int P,
                                                               int64_t n, int accumulate) {
   __shared__ float4 part[RED_SLICES][RED_COLS / 4];
-  const int cg = threadIdx.x & 3, slice = threadIdx.x >> 2;
+  const int cg = threadIdx.x & 1, slice = threadIdx.x >> 1;
   const int64_t c = ((int64_t)blockIdx.x * (RED_COLS / 4) + cg) * 4;
+  const bool valid = c < n;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (c < n) {
-    for (int p = slice; p < P; p += RED_SLICES) {
-      const float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * n + c);
+  if (valid) {
+    const float* col = partial + c;
+    int p = slice;
+    for (; p + 3 * RED_SLICES < P; p += 4 * RED_SLICES) {
+      const float4 v0 = *reinterpret_cast<const float4*>(col + (int64_t)p * n);
+      const float4 v1 = *reinterpret_cast<const float4*>(col + (int64_t)(p + RED_SLICES) * n);
+      const float4 v2 = *reinterpret_cast<const float4*>(col + (int64_t)(p + 2 * RED_SLICES) * n);
+      const float4 v3 = *reinterpret_cast<const float4*>(col + (int64_t)(p + 3 * RED_SLICES) * n);
+      s.x += (v0.x + v1.x) + (v2.x + v3.x); s.y += (v0.y + v1.y) + (v2.y + v3.y);
+      s.z += (v0.z + v1.z) + (v2.z + v3.z); s.w += (v0.w + v1.w) + (v2.w + v3.w);
+    }
+    for (; p < P; p += RED_SLICES) {
+      const float4 v = *reinterpret_cast<const float4*>(col + (int64_t)p * n);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
   }
   part[slice][cg] = s;
   __syncthreads();
-  if (slice == 0 && c < n) {
-    float4 t = part[0][cg];
-    for (int i = 1; i < RED_SLICES; i++) {
-      const float4 v = part[i][cg];
-      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+#pragma unroll
+  for (int half = RED_SLICES / 2; half >= 1; half >>= 1) {
+    if (slice < half) {
+      const float4 a = part[slice][cg], b = part[slice + half][cg];
+      part[slice][cg] = make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
     }
+    __syncthreads();
+  }
+  if (slice == 0 && valid) {
+    float4 t = part[0][cg];
     float4* o = reinterpret_cast<float4*>(out + c);
     if (accumulate) {
       const float4 old = *o;
