@@ -162,11 +162,13 @@ def test_full_width_stack_32k_one_sample_through_all_layers(B, n_vit, n_dec):
     assert np.all(dx_seq[a:a + W.IMG_TOKENS * k] == 0.0)      # rows the connector overwrote
 
 
-@pytest.mark.parametrize("what", ["fwd_up", "dx_down", "dw_up", "dw_qkv"])
+@pytest.mark.parametrize("what", ["fwd_up", "dx_down", "dw_up", "dw_qkv", "dw_ragged_tokens"])
 def test_gemm_full_shapes_sampled(B, what):
     T, d, f, nq = 32768, 4096, 14336, 6144
     rng = np.random.default_rng(7)
-    if what == "fwd_up":       # [T,d] . [d,2f]
+    if what == "dw_ragged_tokens":   # the InternViT-shaped MLP weight gradient over 23575 tokens (368 k-tiles + 23 rows)
+        m, n, k, al, bl, f32 = 3200, 12800, 23575, 1, 0, 1
+    elif what == "fwd_up":     # [T,d] . [d,2f]
         m, n, k, al, bl, f32 = T, 2 * f, d, 0, 0, 0
     elif what == "dx_down":    # dY[T,d] . W_d[f,d]^T
         m, n, k, al, bl, f32 = T, f, d, 0, 1, 0
