@@ -169,6 +169,23 @@ def test_sizes_grow_with_tokens_and_are_aligned(B):
     B.mllm_stage_destroy(h)
 
 
+def test_qk_norm_adds_its_buffers_to_the_sizes(B):
+    """QK normalisation keeps a second [T, nq] matrix and two statistics arrays per layer in `saved`
+    and one more [T, nq] gradient matrix in the workspace (each rounded up to 256 bytes)."""
+    import dataclasses
+    base = W.decoder_layer(512, 8, 2, 64, 1024, 10000.0)
+    batch = W.Batch(None, W.make_pack([300, 212], W.MASK_CAUSAL), None, [])
+    T, nq = 512, (8 + 2 * 2) * 64
+    sizes = []
+    for layers in ([base, base], [dataclasses.replace(base, qk_norm=1)] * 2):
+        h = B.mllm_stage_create(layers)
+        sizes.append(B.mllm_stage_sizes(h, batch))
+        B.mllm_stage_destroy(h)
+    up = lambda v: (v + 255) // 256 * 256
+    assert sizes[1][0] - sizes[0][0] == 2 * (up(T * nq * 2) + 2 * up(T * 2 * 4))
+    assert sizes[1][1] - sizes[0][1] == up(T * nq * 2)
+
+
 def test_workload_recipes():
     for seed in range(300, 304):
         s = W.draw_samples_mix8b(seed)
