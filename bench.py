@@ -528,6 +528,10 @@ def main():
     kernel_names = {"gemm_fwd": "gemm4_kernel<4, false, true, false> (Y = X.W, 256x256x64 tiles)",
                     "gemm_dx": "gemm4_kernel<4, false, false, false> (dX = dY.W^T, 256x256x64 tiles)",
                     "gemm_dw": "gemm4_kernel<4, true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
+    # weight gradients contract over the tokens: a token count that is no multiple of 64 takes the ragged-K form
+    ragged = any(pk is not None and pk.total_tokens % 64 for pk in (wl.batch.img, wl.batch.seq))
+    if ragged:
+        kernel_names["gemm_dw"] = "gemm4_ragged_k_kernel<true> (dW = X^T.dY, fp32, 256x256x64 tiles, token count no multiple of 64)"
     # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
     # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
     traffic_table = {"gemm_fwd": (1121310 * 2.0 + 367256) * 1024, "gemm_dx": (1526520 * 2.0 + 320439) * 1024,
