@@ -22,6 +22,10 @@ ViT encoder layer, RMSNorm / rotary positions (half-split pairing, positions
 restart at every sample) / grouped-query attention / SwiGLU for the decoder
 layer, a biased linear connector whose rows are scattered into the packed LLM
 sequence.  Backward is the hand-derived reverse mode of exactly these formulas.
+Variants of the evaluated model families (Evaluation, Table 4) are flags of a
+layer: tanh-GELU, a QKV bias in the decoder, a two-layer MLP connector, average
+pooling or token merging in front of the connector, RMS normalisation of the
+q and k rows.  Every function is pinned in tests/test_oracle_pins.py.
 
 Everything is float64 NumPy.  A BLAS matmul is used as a step for the dense
 contractions; attention materialises the score matrix per (segment, head,
