@@ -375,7 +375,6 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
     }
   };
   auto load_all = [&](auto s_c, int kt) {
-    constexpr int S = decltype(s_c)::value;
     const uint32_t t = (uint32_t)min(kt, last_tile);
     static_for<NA>([&](auto i) { load_a(s_c, i, t); });
     static_for<8>([&](auto i) { load_b(s_c, i, t); });

@@ -19,12 +19,6 @@ namespace {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
-int count_tiles(const mllm_pack_t& p, int tile) {
-  int n = 0;
-  for (int s = 0; s < p.n_segments; s++) n += (p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s] + tile - 1) / tile;
-  return n;
-}
-
 void build_tiles(const mllm_pack_t& p, int tile, bool kv_major, std::vector<AttnTile>& out) {
   struct Item { AttnTile t; int64_t work; };
   std::vector<Item> items;
