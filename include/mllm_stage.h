@@ -212,6 +212,16 @@ mllm_status_t mllm_op_gemm(const void* a, const void* b, void* c, int64_t m, int
                            int a_layout, int b_layout, int out_fp32, int accumulate,
                            const void* bias, const void* residual, void* hip_stream);
 
+/* The decoder's MLP up-projection with its activation in one pass (the linear operations of the
+ * LLM run over the whole packed sequence: Model Profiler, "Throughput Profiling"):
+ * pre [M, 2f] = x [M, K] . w_gu [K, 2f] with w_gu = [W_gate | W_up], and
+ * act [M, f] = silu(pre[:, :f]) * pre[:, f:], all bf16 row-major, act computed from the fp32
+ * accumulators.  The stage takes this form whenever it applies: f a multiple of 128, K a multiple
+ * of 64, at least 200 output tiles of 256 x 256; otherwise MLLM_ERR_UNSUPPORTED (then
+ * mllm_op_gemm followed by mllm_op_act_fwd computes the same). */
+mllm_status_t mllm_op_gemm_swiglu(const void* x, const void* w_gu, void* pre, void* act, int64_t m,
+                                  int64_t f, int64_t k, void* hip_stream);
+
 /* Per-instance attention over a packed sequence (Model Profiler, "Throughput Profiling").
  *   q [T, n_q, hd], k, v [T, n_kv, hd] bf16 with row strides (in elements) q_stride / kv_stride,
  *   o [T, n_q, hd] bf16 (row stride o_stride), lse fp32 [n_q, T] (natural log-sum-exp of the

@@ -275,12 +275,20 @@ struct ScalarStepLoader {
   uint32_t off[PER_THREAD];   // byte offset of this thread's vectors in k-tile 0, OOB if never valid
   uint32_t kstep;             // bytes per k-tile
 
-  __device__ __forceinline__ void init(int64_t ld, int64_t fixed0, int64_t nfixed, int tid) {
+  // pair_half > 0 (operands stored [K, N] only): the tile's 256 columns are, in blocks of 64,
+  // columns [c, c + 64) of the left half of the matrix, the same columns of the right half
+  // (+ pair_half), then [c + 64, c + 128) of the left half and of the right half, with
+  // c = fixed0 / 2: each wavefront's 128 columns then hold matching gate and up columns.
+  __device__ __forceinline__ void init(int64_t ld, int64_t fixed0, int64_t nfixed, int tid, int64_t pair_half = 0) {
     kstep = (uint32_t)(K_ROWS ? BK * ld * 2 : BK * 2);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; i++) {
       const int v = tid + i * NT, rr = v / VEC_PER_ROW, cc = (v % VEC_PER_ROW) * 8;
-      const int64_t fx = fixed0 + (K_ROWS ? cc : rr);
+      int64_t fx = fixed0 + (K_ROWS ? cc : rr);
+      if (K_ROWS && pair_half > 0) {
+        const int blk = cc >> 6;
+        fx = (blk & 1) * pair_half + (fixed0 >> 1) + 64 * (blk >> 1) + (cc & 63);
+      }
       const int64_t lin = K_ROWS ? (int64_t)rr * ld + fx : fx * ld + cc;
       off[i] = fx < nfixed ? (uint32_t)(lin * 2) : OOB;
     }
@@ -313,7 +321,7 @@ __device__ __forceinline__ KAdvance k_advance(uint32_t t, uint32_t last_tile, ui
   return {0u, t * kstep};
 }
 
-template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K>
+template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K, bool SWIGLU = false>
 __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   // TM = 4: 256x256 tiles, wavefronts of 128x128.  TM = 3: 192x256 tiles, wavefronts of 96x128,
   // for problems whose 256-row tiles would leave the last round of workgroups mostly empty.
@@ -321,6 +329,8 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   // RAGGED_K: K need not be a multiple of 64.  Only when k runs along the rows of both operands:
   // the rows of the last k-tile that lie past K are then past the end of the operand.
   static_assert(!RAGGED_K || (A_T && B_T), "a ragged K needs both operands stored [K, .]");
+  // SWIGLU: C = [gate | up]; the epilogue also writes silu(gate) * up (forward layout only).
+  static_assert(!SWIGLU || (TM == 4 && !A_T && B_T && !OUT_F32), "fused SwiGLU: Y = X.W with W stored [K, N], bf16");
   constexpr int BM = 64 * TM, BN = 256, WM = 32 * TM, WN = 128, NT = 256, TN = 4;
   constexpr int NA = 2 * TM;          // A vectors per thread and k-tile (B: 8)
   constexpr int NU = TM + 4;          // fragment units per k-step
@@ -345,7 +355,7 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   LA la;
   LB lb;
   la.init(p.lda, m0, p.M, tid);
-  lb.init(p.ldb, n0, p.N, tid);
+  lb.init(p.ldb, n0, p.N, tid, SWIGLU ? p.N >> 1 : 0);
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes), rb = make_rsrc(p.b, p.b_bytes);
 
   // The accumulators are not cleared: the first k-step of the first k-tile multiplies into a
@@ -498,8 +508,12 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   constexpr int ST_STRIDE = WN + 4;  // floats
   static_assert(4 * 32 * ST_STRIDE * 4 <= 2 * B_SIZE * 2, "staging must fit in the B stages");
   if constexpr (OUT_F32) p.c = reinterpret_cast<float*>(p.c) + blockIdx.y * p.c_split_stride;
-  store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE,
-                              m0 + wm * WM, n0 + wn * WN, lane);
+  if constexpr (SWIGLU)
+    store_tile_swiglu<TM>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE, m0 + wm * WM,
+                          (n0 >> 1) + 64 * wn, lane);
+  else
+    store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE,
+                                      m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int TM, bool A_T, bool B_T, bool OUT_F32>
@@ -510,6 +524,11 @@ __global__ __launch_bounds__(256) void gemm4_kernel(GemmParams p) {
 template <bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm4_ragged_k_kernel(GemmParams p) {
   gemm4_tile<4, true, true, OUT_F32, true>(p);
+}
+
+// Y = [gate | up] = X.W and silu(gate) * up in one pass (the decoder's MLP up-projection).
+__global__ __launch_bounds__(256) void gemm4_swiglu_kernel(GemmParams p) {
+  gemm4_tile<4, false, true, false, false, true>(p);
 }
 
 // The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64,
@@ -538,6 +557,10 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
   const bool at = g.a_layout != 0, bt = g.b_layout == 0;  // b_layout 0 = [K,N] = transposing reads
   if (BM == 256 && BN == 256 && takes_gemm4(g)) {
     const dim3 block4(256);
+    if (g.swiglu_act) {   // launch_gemm has checked gemm_swiglu_fusable()
+      hipLaunchKernelGGL(gemm4_swiglu_kernel, grid, block4, 0, s, p);
+      return hipGetLastError();
+    }
     const bool rows192 = takes_rows192(g, splits);
     if (rows192) {
       p.tiles_m = (int)((g.m + 191) / 192);
@@ -634,8 +657,16 @@ size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k) {
   return sp.splits > 1 ? (size_t)sp.splits * (size_t)m * (size_t)n * 4 : 0;
 }
 
+bool gemm_swiglu_fusable(int64_t m, int64_t n, int64_t k) {
+  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
+  return big_tiles >= 200 && n % 256 == 0 && k >= BK && k % BK == 0;
+}
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  if (g.swiglu_act && (!gemm_swiglu_fusable(g.m, g.n, g.k) || g.a_layout != 0 || g.b_layout != 0 || g.out_fp32 ||
+                       g.bias || g.residual || g.ldc != g.n))
+    return hipErrorInvalidValue;
   // operands are addressed through 32-bit buffer offsets
   if ((g.a_layout ? g.k : g.m) * g.lda * 2 > GEMM_MAX_OPERAND_BYTES || (g.b_layout ? g.n : g.k) * g.ldb * 2 > GEMM_MAX_OPERAND_BYTES)
     return hipErrorInvalidValue;
@@ -648,7 +679,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
                      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4;
   const bool large = big_tiles >= 200 || (split && sp.big_tile);
   // timing classes: the three layouts of the 256x256 kernel, its 192-row form, and the 128x128 kernel
-  const int cls = !large ? PROF_GEMM_SMALL : (!split && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
+  const int cls = !large ? PROF_GEMM_SMALL : (!split && !g.swiglu_act && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
                   : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   const double flops = 2.0 * (double)g.m * (double)g.n * (double)g.k;
   // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep

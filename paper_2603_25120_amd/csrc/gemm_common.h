@@ -29,6 +29,7 @@ struct GemmParams {
   int tiles_m, tiles_n;
   int kt_per_split;         // k-tiles handled by one workgroup row (gridDim.y splits of the K loop)
   int64_t c_split_stride;   // elements between the partial outputs of consecutive splits
+  bf16_t* act;              // fused SwiGLU: silu(gate) * up, [M, N / 2]
 };
 
 inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
@@ -43,6 +44,7 @@ inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
   p.tiles_n = (int)((g.n + bn - 1) / bn);
   p.kt_per_split = (int)((g.k + BK - 1) / BK);
   p.c_split_stride = 0;
+  p.act = (bf16_t*)g.swiglu_act;
   return p;
 }
 
@@ -178,6 +180,62 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   };
   if (rows_left >= 32 * TM && col0 + WN <= p.N) emit(std::true_type{});
   else emit(std::false_type{});
+}
+
+// Epilogue of the fused SwiGLU product.  The wavefront's 32*TM x 128 sub-tile holds 64 gate
+// columns (accumulator blocks 0, 1) and the 64 up columns of the same indices (blocks 2, 3):
+// columns gcol0 .. gcol0 + 63 of gate and of up.  Each band of 32 rows is staged through LDS
+// like in store_tile; a lane then takes a gate chunk of 8 columns and its up chunk of the same
+// row and writes three 16-byte pieces: gate and up into C = [gate | up] ([M, N], up at column
+// N / 2 + gcol) and silu(gate) * up into act ([M, N / 2]).  The sub-tile's columns all exist
+// (N / 2 is a multiple of 128); rows past M are skipped.
+template <int TM>
+__device__ __forceinline__ void store_tile_swiglu(const GemmParams& p, f32x16 (&acc)[TM][4], float* stage,
+                                                  int64_t row0, int64_t gcol0, int lane) {
+  constexpr int ST_STRIDE = 128 + 4;
+  const int h = lane >> 5, cl = lane & 31;
+  const int rr0 = lane >> 3, cc = (lane & 7) * 8;          // 8 rows per pass, 8 gate chunks per row
+  const int64_t half = p.N >> 1;
+  const int rows_left = (int)min((int64_t)(32 * TM), p.M - row0);
+  char* const c_base = reinterpret_cast<char*>(p.c) + (row0 * p.ldc + gcol0) * 2;
+  char* const a_base = reinterpret_cast<char*>(p.act) + (row0 * half + gcol0) * 2;
+  const uint32_t c_pitch = (uint32_t)(p.ldc * 2), a_pitch = (uint32_t)(half * 2);
+  const uint32_t up_off = (uint32_t)(half * 2);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    if (i == 0) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++)
+        *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
+            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      const int rr = rr0 + 8 * t, r = 32 * i + rr;
+      if (r >= rows_left) continue;
+      float g[8], u[8], a[8];
+#pragma unroll
+      for (int q = 0; q < 2; q++) {
+        const float4 vg = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
+        const float4 vu = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + 64 + cc + 4 * q);
+        g[4 * q] = vg.x; g[4 * q + 1] = vg.y; g[4 * q + 2] = vg.z; g[4 * q + 3] = vg.w;
+        u[4 * q] = vu.x; u[4 * q + 1] = vu.y; u[4 * q + 2] = vu.z; u[4 * q + 3] = vu.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e++)   // silu through the hardware exp2 and reciprocal (1 ulp each; the result is rounded to bf16)
+        a[e] = g[e] * u[e] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(g[e] * -1.44269504088896340736f));
+      char* const dst = c_base + ((uint32_t)r * c_pitch + (uint32_t)(cc * 2));
+      *reinterpret_cast<uint4*>(dst) = make_uint4(pack_bf16x2(g[0], g[1]), pack_bf16x2(g[2], g[3]),
+                                                  pack_bf16x2(g[4], g[5]), pack_bf16x2(g[6], g[7]));
+      *reinterpret_cast<uint4*>(dst + up_off) = make_uint4(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]),
+                                                           pack_bf16x2(u[4], u[5]), pack_bf16x2(u[6], u[7]));
+      *reinterpret_cast<uint4*>(a_base + ((uint32_t)r * a_pitch + (uint32_t)(cc * 2))) =
+          make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+    }
+  }
 }
 
 }  // namespace mllm

@@ -21,7 +21,13 @@ struct GemmArgs {
   int64_t ldres;
   void* splitk_ws;         // optional fp32 scratch for split-K partial products (null: never split)
   size_t splitk_ws_bytes;
+  // SwiGLU fused into the product's epilogue: C = [gate | up] is [M, N] bf16 as usual and
+  // swiglu_act [M, N/2] bf16 also receives silu(gate) * up.  Only where gemm_swiglu_fusable().
+  void* swiglu_act = nullptr;
 };
+// Whether launch_gemm can write the SwiGLU activation of a forward product X[M,K].W[K,N] along
+// with it (large-tile kernel, N/2 a multiple of 128, K a multiple of 64).
+bool gemm_swiglu_fusable(int64_t m, int64_t n, int64_t k);
 // A and B are addressed through 32-bit byte offsets: each operand must stay below this size.
 constexpr int64_t GEMM_MAX_OPERAND_BYTES = 0xFFFFFFF0ll - 16;
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);

@@ -443,6 +443,17 @@ hipError_t linear_fwd(const void* x, const void* w, void* y, int64_t T, int64_t 
                       const void* bias, const void* res, hipStream_t s) {
   return gemm(x, k, 0, w, n, 0, y, n, T, n, k, 0, 0, bias, res, n, s);
 }
+// [gate | up][T,2f] = X[T,k].W[k,2f] and act[T,f] = silu(gate) * up in the same pass
+hipError_t linear_fwd_swiglu(const void* x, const void* w, void* pre, void* act, int64_t T, int64_t k,
+                             int64_t n, hipStream_t s) {
+  GemmArgs g;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
+  g.a = x; g.b = w; g.c = pre; g.m = T; g.n = n; g.k = k; g.lda = k; g.ldb = n; g.ldc = n;
+  g.a_layout = 0; g.b_layout = 0; g.out_fp32 = 0; g.accumulate = 0;
+  g.bias = nullptr; g.residual = nullptr; g.ldres = 0;
+  g.swiglu_act = act;
+  return launch_gemm(g, s);
+}
 // dX[T,k] = dY[T,n].W[k,n]^T
 hipError_t linear_dx(const void* dy, const void* w, void* dx, int64_t T, int64_t k, int64_t n, hipStream_t s) {
   return gemm(dy, n, 0, w, n, 1, dx, k, T, k, n, 0, 0, nullptr, nullptr, 0, s);
@@ -526,8 +537,12 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
   K_TRY(launch_attn_fwd(a, s));
   K_TRY(linear_fwd(o, wo, x1, T, d, d, bo, x, s));
   K_TRY(launch_norm_fwd(vit ? 0 : 1, x1, g2, b2n, n2, (float*)(saved + S.stats2), T, d, d, L.norm_eps, s));
-  K_TRY(linear_fwd(n2, wup, pre, T, d, vit ? f : 2 * f, bup, nullptr, s));
-  K_TRY(launch_act_fwd(L.act, pre, act, T, f, s));
+  if (!vit && gemm_swiglu_fusable(T, 2 * f, d)) {
+    K_TRY(linear_fwd_swiglu(n2, wup, pre, act, T, d, 2 * f, s));
+  } else {
+    K_TRY(linear_fwd(n2, wup, pre, T, d, vit ? f : 2 * f, bup, nullptr, s));
+    K_TRY(launch_act_fwd(L.act, pre, act, T, f, s));
+  }
   K_TRY(linear_fwd(act, wdn, y, T, f, d, bdn, x1, s));
   return MLLM_OK;
 }

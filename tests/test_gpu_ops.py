@@ -121,6 +121,28 @@ def test_gemm_large_tiles_weight_gradient_ragged_k(B, k, f32):
         assert nmax_err(host_f64(c), ref) < 1e-2
 
 
+@pytest.mark.parametrize("m,f,k", [(4200, 1536, 320), (4352, 1664, 64), (6401, 1024, 192)])
+def test_gemm_swiglu_fused(B, m, f, k):
+    """Up-projection with the activation in the same pass: [gate | up] = x.W and silu(gate) * up,
+    ragged rows, one to five k-tiles; the unfused pair of operations must agree with it too."""
+    x = W.draw_tensor(181, m, k)
+    w = W.bf16_round(W.draw_tensor(182, k, 2 * f) * np.float32(0.125))
+    pre_ref = x.astype(np.float64) @ w.astype(np.float64)
+    g, u = pre_ref[:, :f], pre_ref[:, f:]
+    act_ref = g / (1.0 + np.exp(-g)) * u
+    pre = torch.full((m, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    act = torch.full((m, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    B.mllm_op_gemm_swiglu(xd, wd, pre, act, m, f, k)
+    assert nmax_err(host_f64(pre), pre_ref) < 1e-2
+    assert nmax_err(host_f64(act), act_ref) < 2e-2
+    pre2, act2 = empty_bf16(m, 2 * f), empty_bf16(m, f)
+    B.mllm_op_gemm(xd, wd, pre2, m, 2 * f, k)
+    B.mllm_op_act_fwd(W.ACT_SWIGLU, pre2, act2, m, f)
+    assert torch.equal(pre, pre2)                       # the same accumulators, the same rounding
+    assert nmax_err(host_f64(act), host_f64(act2)) < 2e-2
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_gemm_large_tiles_random_shapes(B, seed):
     """Seeded random problems that take the four-wavefront kernel: ragged M and N in every
