@@ -526,7 +526,7 @@ def main():
     all_gemm_ms = sum(prof[c][1] for c in gemm_all)
     all_gemm_work = sum(prof[c][2] for c in gemm_all)
     kernel_names = {"gemm_fwd": "gemm4_kernel<4, false, true, false> and gemm4_swiglu_kernel (Y = X.W, 256x256x64 tiles)",
-                    "gemm_dx": "gemm4_kernel<4, false, false, false> (dX = dY.W^T, 256x256x64 tiles)",
+                    "gemm_dx": "gemm4_kernel<4, false, false, false> and gemm4_swiglu_bwd_kernel (dX = dY.W^T, 256x256x64 tiles)",
                     "gemm_dw": "gemm4_kernel<4, true, true, true> (dW = X^T.dY, fp32, 256x256x64 tiles)"}
     # weight gradients contract over the tokens: a token count that is no multiple of 64 takes the ragged-K form
     ragged = any(pk is not None and pk.total_tokens % 64 for pk in (wl.batch.img, wl.batch.seq))

@@ -222,6 +222,15 @@ mllm_status_t mllm_op_gemm(const void* a, const void* b, void* c, int64_t m, int
 mllm_status_t mllm_op_gemm_swiglu(const void* x, const void* w_gu, void* pre, void* act, int64_t m,
                                   int64_t f, int64_t k, void* hip_stream);
 
+/* The backward counterpart: with dy [M, K] (gradient of the MLP output), w_d [f, K] (the
+ * down-projection, stored [in, out]) and pre [M, 2f] = [gate | up], writes
+ * dpre [M, 2f] = [d gate | d up], where dA = dy . w_d^T [M, f] is kept in fp32 and never stored:
+ * d gate = dA * up * s * (1 + gate * (1 - s)), d up = dA * gate * s, s = sigmoid(gate).
+ * All bf16 row-major.  Applies with K a multiple of 64 and at least 200 tiles of 256 x 256 in
+ * [M, f]; otherwise MLLM_ERR_UNSUPPORTED (mllm_op_gemm followed by mllm_op_act_bwd computes the same). */
+mllm_status_t mllm_op_gemm_swiglu_bwd(const void* dy, const void* w_d, const void* pre, void* dpre,
+                                      int64_t m, int64_t f, int64_t k, void* hip_stream);
+
 /* Per-instance attention over a packed sequence (Model Profiler, "Throughput Profiling").
  *   q [T, n_q, hd], k, v [T, n_kv, hd] bf16 with row strides (in elements) q_stride / kv_stride,
  *   o [T, n_q, hd] bf16 (row stride o_stride), lse fp32 [n_q, T] (natural log-sum-exp of the

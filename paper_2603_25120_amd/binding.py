@@ -22,7 +22,7 @@ STATUS_NAMES = ["MLLM_OK", "MLLM_ERR_NULL", "MLLM_ERR_DESC", "MLLM_ERR_SHAPE", "
 
 EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", "mllm_stage_param_info",
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
-           "mllm_op_gemm_swiglu", "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
+           "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
@@ -100,6 +100,7 @@ def lib() -> C.CDLL:
     L.mllm_stage_bwd.argtypes = [vp, C.POINTER(BatchC), C.POINTER(vp), vp, vp, sz, vp, vp, C.POINTER(vp), C.c_int, vp, sz, vp]
     L.mllm_op_gemm.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     L.mllm_op_gemm_swiglu.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
+    L.mllm_op_gemm_swiglu_bwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
     L.mllm_op_attn_workspace_bytes.argtypes = [i32, i32]
     L.mllm_op_attn_workspace_bytes.restype = sz
     L.mllm_op_attn_fwd.argtypes = [vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, sz, vp]
@@ -267,6 +268,10 @@ def mllm_op_gemm(a, b, c, m, n, k, a_layout=0, b_layout=0, out_fp32=0, accumulat
 
 def mllm_op_gemm_swiglu(x, w_gu, pre, act, m, f, k, stream=None) -> None:
     _check(lib().mllm_op_gemm_swiglu(_ptr(x), _ptr(w_gu), _ptr(pre), _ptr(act), m, f, k, _stream(stream)))
+
+
+def mllm_op_gemm_swiglu_bwd(dy, w_d, pre, dpre, m, f, k, stream=None) -> None:
+    _check(lib().mllm_op_gemm_swiglu_bwd(_ptr(dy), _ptr(w_d), _ptr(pre), _ptr(dpre), m, f, k, _stream(stream)))
 
 
 def mllm_op_attn_workspace_bytes(n_segments: int, total_tokens: int) -> int:

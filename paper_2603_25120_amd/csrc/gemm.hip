@@ -321,8 +321,10 @@ __device__ __forceinline__ KAdvance k_advance(uint32_t t, uint32_t last_tile, ui
   return {0u, t * kstep};
 }
 
-template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K, bool SWIGLU = false>
+// EPI: 0 plain epilogue; 1 SwiGLU forward fused; 2 SwiGLU gradient fused.
+template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K, int EPI = 0>
 __device__ __forceinline__ void gemm4_tile(GemmParams p) {
+  constexpr bool SWIGLU = EPI == 1;
   // TM = 4: 256x256 tiles, wavefronts of 128x128.  TM = 3: 192x256 tiles, wavefronts of 96x128,
   // for problems whose 256-row tiles would leave the last round of workgroups mostly empty.
   static_assert(TM == 4 || (TM == 3 && !A_T), "192-row tiles only for an A operand stored [M, K]");
@@ -331,6 +333,7 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   static_assert(!RAGGED_K || (A_T && B_T), "a ragged K needs both operands stored [K, .]");
   // SWIGLU: C = [gate | up]; the epilogue also writes silu(gate) * up (forward layout only).
   static_assert(!SWIGLU || (TM == 4 && !A_T && B_T && !OUT_F32), "fused SwiGLU: Y = X.W with W stored [K, N], bf16");
+  static_assert(EPI != 2 || (TM == 4 && !A_T && !B_T && !OUT_F32), "fused SwiGLU gradient: dA = dY.W^T with W stored [N, K], bf16");
   constexpr int BM = 64 * TM, BN = 256, WM = 32 * TM, WN = 128, NT = 256, TN = 4;
   constexpr int NA = 2 * TM;          // A vectors per thread and k-tile (B: 8)
   constexpr int NU = TM + 4;          // fragment units per k-step
@@ -511,6 +514,9 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   if constexpr (SWIGLU)
     store_tile_swiglu<TM>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE, m0 + wm * WM,
                           (n0 >> 1) + 64 * wn, lane);
+  else if constexpr (EPI == 2)
+    store_tile_swiglu_bwd<TM>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE, m0 + wm * WM,
+                              n0 + wn * WN, lane);
   else
     store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE,
                                       m0 + wm * WM, n0 + wn * WN, lane);
@@ -528,7 +534,11 @@ __global__ __launch_bounds__(256) void gemm4_ragged_k_kernel(GemmParams p) {
 
 // Y = [gate | up] = X.W and silu(gate) * up in one pass (the decoder's MLP up-projection).
 __global__ __launch_bounds__(256) void gemm4_swiglu_kernel(GemmParams p) {
-  gemm4_tile<4, false, true, false, false, true>(p);
+  gemm4_tile<4, false, true, false, false, 1>(p);
+}
+// dA = dY.W_d^T kept in registers; [d gate | d up] written (the decoder's MLP down-projection, backward).
+__global__ __launch_bounds__(256) void gemm4_swiglu_bwd_kernel(GemmParams p) {
+  gemm4_tile<4, false, false, false, false, 2>(p);
 }
 
 // The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64,
@@ -559,6 +569,10 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
     const dim3 block4(256);
     if (g.swiglu_act) {   // launch_gemm has checked gemm_swiglu_fusable()
       hipLaunchKernelGGL(gemm4_swiglu_kernel, grid, block4, 0, s, p);
+      return hipGetLastError();
+    }
+    if (g.swiglu_dpre) {
+      hipLaunchKernelGGL(gemm4_swiglu_bwd_kernel, grid, block4, 0, s, p);
       return hipGetLastError();
     }
     const bool rows192 = takes_rows192(g, splits);
@@ -662,8 +676,17 @@ bool gemm_swiglu_fusable(int64_t m, int64_t n, int64_t k) {
   return big_tiles >= 200 && n % 256 == 0 && k >= BK && k % BK == 0;
 }
 
+bool gemm_swiglu_bwd_fusable(int64_t m, int64_t n, int64_t k) {
+  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
+  return big_tiles >= 200 && n % 8 == 0 && k >= BK && k % BK == 0;
+}
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  if ((g.swiglu_dpre || g.swiglu_pre) &&
+      (!g.swiglu_dpre || !g.swiglu_pre || g.swiglu_act || !gemm_swiglu_bwd_fusable(g.m, g.n, g.k) || g.a_layout != 0 ||
+       g.b_layout != 1 || g.out_fp32 || g.bias || g.residual || g.ldc != 2 * g.n))
+    return hipErrorInvalidValue;
   if (g.swiglu_act && (!gemm_swiglu_fusable(g.m, g.n, g.k) || g.a_layout != 0 || g.b_layout != 0 || g.out_fp32 ||
                        g.bias || g.residual || g.ldc != g.n))
     return hipErrorInvalidValue;
@@ -679,7 +702,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
                      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4;
   const bool large = big_tiles >= 200 || (split && sp.big_tile);
   // timing classes: the three layouts of the 256x256 kernel, its 192-row form, and the 128x128 kernel
-  const int cls = !large ? PROF_GEMM_SMALL : (!split && !g.swiglu_act && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
+  const int cls = !large ? PROF_GEMM_SMALL : (!split && !g.swiglu_act && !g.swiglu_dpre && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
                   : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   const double flops = 2.0 * (double)g.m * (double)g.n * (double)g.k;
   // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep

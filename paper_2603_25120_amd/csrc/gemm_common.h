@@ -30,6 +30,8 @@ struct GemmParams {
   int kt_per_split;         // k-tiles handled by one workgroup row (gridDim.y splits of the K loop)
   int64_t c_split_stride;   // elements between the partial outputs of consecutive splits
   bf16_t* act;              // fused SwiGLU: silu(gate) * up, [M, N / 2]
+  const bf16_t* pre;        // fused SwiGLU gradient: [gate | up], [M, 2 N]
+  bf16_t* dpre;             //                        [d gate | d up], [M, 2 N]
 };
 
 inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
@@ -45,6 +47,8 @@ inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
   p.kt_per_split = (int)((g.k + BK - 1) / BK);
   p.c_split_stride = 0;
   p.act = (bf16_t*)g.swiglu_act;
+  p.pre = (const bf16_t*)g.swiglu_pre;
+  p.dpre = (bf16_t*)g.swiglu_dpre;
   return p;
 }
 
@@ -234,6 +238,74 @@ __device__ __forceinline__ void store_tile_swiglu(const GemmParams& p, f32x16 (&
                                                            pack_bf16x2(u[4], u[5]), pack_bf16x2(u[6], u[7]));
       *reinterpret_cast<uint4*>(a_base + ((uint32_t)r * a_pitch + (uint32_t)(cc * 2))) =
           make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+    }
+  }
+}
+
+// Epilogue of dA = dY.W_d^T with SwiGLU's gradient: the sub-tile of dA (32*TM x 128, columns from
+// col0) never reaches memory.  Band by band it is staged through LDS like in store_tile; a lane
+// takes a chunk of 8 columns of dA, the gate and up chunks of the same row and columns from
+// pre = [gate | up] ([M, 2N], requested for the whole band before the staging), and writes
+//   d gate = dA * up * s * (1 + gate * (1 - s)),  d up = dA * gate * s,  s = sigmoid(gate)
+// to dpre = [d gate | d up] ([M, 2N]).  Rows past M and columns past N are skipped.
+template <int TM>
+__device__ __forceinline__ void store_tile_swiglu_bwd(const GemmParams& p, f32x16 (&acc)[TM][4], float* stage,
+                                                      int64_t row0, int64_t col0, int lane) {
+  constexpr int ST_STRIDE = 128 + 4, PER_BAND = 8, ROWS_PER_PASS = 4;
+  const int h = lane >> 5, cl = lane & 31;
+  const int rr0 = lane >> 4, cc = (lane & 15) * 8;
+  const bool col_ok = col0 + cc < p.N;
+  const int rows_left = (int)min((int64_t)(32 * TM), p.M - row0);
+  const uint32_t pitch = (uint32_t)(p.N * 4), up_off = (uint32_t)(p.N * 2);   // bytes: a row of [M, 2N] bf16; the up half
+  const char* const pre_base = reinterpret_cast<const char*>(p.pre) + (row0 * 2 * p.N + col0) * 2;
+  char* const dpre_base = reinterpret_cast<char*>(p.dpre) + (row0 * 2 * p.N + col0) * 2;
+  const uint32_t lane_off = (uint32_t)rr0 * pitch + (uint32_t)(cc * 2);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    uint4 gq[PER_BAND], uq[PER_BAND];
+#pragma unroll
+    for (int t = 0; t < PER_BAND; t++) {
+      const int r = 32 * i + t * ROWS_PER_PASS;
+      const bool ok = r + rr0 < rows_left && col_ok;
+      const char* src = pre_base + (lane_off + (uint32_t)r * pitch);
+      gq[t] = ok ? *reinterpret_cast<const uint4*>(src) : make_uint4(0, 0, 0, 0);
+      uq[t] = ok ? *reinterpret_cast<const uint4*>(src + up_off) : make_uint4(0, 0, 0, 0);
+    }
+    if (i == 0) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++)
+        *reinterpret_cast<float4*>(stage + cl * ST_STRIDE + 32 * j + 8 * g4 + 4 * h) =
+            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < PER_BAND; t++) {
+      const int rr = rr0 + t * ROWS_PER_PASS, r = 32 * i + t * ROWS_PER_PASS;
+      if (!(r + rr0 < rows_left && col_ok)) continue;
+      float d[8], g[8], u[8], og[8], ou[8];
+#pragma unroll
+      for (int q = 0; q < 2; q++) {
+        const float4 v = *reinterpret_cast<const float4*>(stage + rr * ST_STRIDE + cc + 4 * q);
+        d[4 * q] = v.x; d[4 * q + 1] = v.y; d[4 * q + 2] = v.z; d[4 * q + 3] = v.w;
+      }
+      g[0] = bf16lo(gq[t].x); g[1] = bf16hi(gq[t].x); g[2] = bf16lo(gq[t].y); g[3] = bf16hi(gq[t].y);
+      g[4] = bf16lo(gq[t].z); g[5] = bf16hi(gq[t].z); g[6] = bf16lo(gq[t].w); g[7] = bf16hi(gq[t].w);
+      u[0] = bf16lo(uq[t].x); u[1] = bf16hi(uq[t].x); u[2] = bf16lo(uq[t].y); u[3] = bf16hi(uq[t].y);
+      u[4] = bf16lo(uq[t].z); u[5] = bf16hi(uq[t].z); u[6] = bf16lo(uq[t].w); u[7] = bf16hi(uq[t].w);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float s = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(g[e] * -1.44269504088896340736f));
+        const float gs = g[e] * s;
+        og[e] = d[e] * u[e] * (s + gs * (1.f - s));
+        ou[e] = d[e] * gs;
+      }
+      char* const dst = dpre_base + (lane_off + (uint32_t)r * pitch);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(pack_bf16x2(og[0], og[1]), pack_bf16x2(og[2], og[3]),
+                                                  pack_bf16x2(og[4], og[5]), pack_bf16x2(og[6], og[7]));
+      *reinterpret_cast<uint4*>(dst + up_off) = make_uint4(pack_bf16x2(ou[0], ou[1]), pack_bf16x2(ou[2], ou[3]),
+                                                           pack_bf16x2(ou[4], ou[5]), pack_bf16x2(ou[6], ou[7]));
     }
   }
 }

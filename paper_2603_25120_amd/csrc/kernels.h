@@ -24,7 +24,13 @@ struct GemmArgs {
   // SwiGLU fused into the product's epilogue: C = [gate | up] is [M, N] bf16 as usual and
   // swiglu_act [M, N/2] bf16 also receives silu(gate) * up.  Only where gemm_swiglu_fusable().
   void* swiglu_act = nullptr;
+  // SwiGLU's gradient fused into the epilogue of dA = dY.W_d^T ([M, N], N = f): with
+  // swiglu_pre = [gate | up] ([M, 2N] bf16) the product itself is not stored; swiglu_dpre
+  // ([M, 2N] bf16) receives [d gate | d up].  C is unused.  Only where gemm_swiglu_bwd_fusable().
+  const void* swiglu_pre = nullptr;
+  void* swiglu_dpre = nullptr;
 };
+bool gemm_swiglu_bwd_fusable(int64_t m, int64_t n, int64_t k);
 // Whether launch_gemm can write the SwiGLU activation of a forward product X[M,K].W[K,N] along
 // with it (large-tile kernel, N/2 a multiple of 128, K a multiple of 64).
 bool gemm_swiglu_fusable(int64_t m, int64_t n, int64_t k);

@@ -146,6 +146,22 @@ mllm_status_t mllm_op_gemm_swiglu(const void* x, const void* w_gu, void* pre, vo
   return MLLM_OK;
 }
 
+mllm_status_t mllm_op_gemm_swiglu_bwd(const void* dy, const void* w_d, const void* pre, void* dpre,
+                                      int64_t m, int64_t f, int64_t k, void* hip_stream) {
+  if (!dy || !w_d || !pre || !dpre) return op_fail(MLLM_ERR_NULL, "a tensor pointer is NULL");
+  if (m < 0 || f <= 0 || k <= 0) return op_fail(MLLM_ERR_SHAPE, "sizes must be positive");
+  if (!gemm_swiglu_bwd_fusable(m, f, k))
+    return op_fail(MLLM_ERR_UNSUPPORTED, "the fused form needs f a multiple of 8, k a multiple of 64 and at least 200 tiles of 256 x 256 of [m, f]");
+  GemmArgs g;
+  g.a = dy; g.b = w_d; g.c = nullptr; g.m = m; g.n = f; g.k = k; g.lda = k; g.ldb = k; g.ldc = 2 * f;
+  g.a_layout = 0; g.b_layout = 1; g.out_fp32 = 0; g.accumulate = 0;
+  g.bias = nullptr; g.residual = nullptr; g.ldres = 0;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
+  g.swiglu_pre = pre; g.swiglu_dpre = dpre;
+  OP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
 size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens) {
   const size_t max_tiles = (size_t)std::max(0, total_tokens) / 128 + (size_t)std::max(0, n_segments) + 1;
   return 2 * align_up(sizeof(AttnTile) * max_tiles);

@@ -458,6 +458,17 @@ hipError_t linear_fwd_swiglu(const void* x, const void* w, void* pre, void* act,
 hipError_t linear_dx(const void* dy, const void* w, void* dx, int64_t T, int64_t k, int64_t n, hipStream_t s) {
   return gemm(dy, n, 0, w, n, 1, dx, k, T, k, n, 0, 0, nullptr, nullptr, 0, s);
 }
+// [d gate | d up][T,2f] from dY[T,d], W_d[f,d] and pre = [gate | up][T,2f]: dA = dY.W_d^T stays in registers
+hipError_t linear_dx_swiglu(const void* dy, const void* w, const void* pre, void* dpre, int64_t T, int64_t f,
+                            int64_t d, hipStream_t s) {
+  GemmArgs g;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
+  g.a = dy; g.b = w; g.c = nullptr; g.m = T; g.n = f; g.k = d; g.lda = d; g.ldb = d; g.ldc = 2 * f;
+  g.a_layout = 0; g.b_layout = 1; g.out_fp32 = 0; g.accumulate = 0;
+  g.bias = nullptr; g.residual = nullptr; g.ldres = 0;
+  g.swiglu_pre = pre; g.swiglu_dpre = dpre;
+  return launch_gemm(g, s);
+}
 // dW[k,n] (+)= X[T,k]^T.dY[T,n]
 struct SplitWs { void* p; size_t bytes; };
 hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t k, int64_t n, int accumulate,
@@ -577,9 +588,13 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   // MLP
   K_TRY(linear_dw(act, dy, dprm[iwdn], T, f, d, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(dy, d, (float*)dprm[ibdn], accumulate, partial, T, d, s));
-  K_TRY(linear_dx(dy, prm[iwdn], wa, T, f, d, s));
   char* dpre = vit ? wa : wb;
-  K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
+  if (!vit && gemm_swiglu_bwd_fusable(T, f, d)) {
+    K_TRY(linear_dx_swiglu(dy, prm[iwdn], pre, dpre, T, f, d, s));
+  } else {
+    K_TRY(linear_dx(dy, prm[iwdn], wa, T, f, d, s));
+    K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
+  }
   K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s, split));
   if (vit) K_TRY(launch_colsum(dpre, fup, (float*)dprm[ibup], accumulate, partial, T, fup, s));
   K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));

@@ -159,6 +159,10 @@ def test_op_argument_checks(B):
     with pytest.raises(B.MllmError) as e:
         B.mllm_op_gemm_swiglu(fake, fake, fake, None, 100000, 128, 64, stream=1)
     assert e.value.status == 1
+    for m, f, k in ((256, 256, 64), (100000, 256, 96)):                     # too few tiles; ragged K
+        with pytest.raises(B.MllmError) as e:
+            B.mllm_op_gemm_swiglu_bwd(fake, fake, fake, fake, m, f, k, stream=1)
+        assert e.value.status == 8
     with pytest.raises(B.MllmError) as e:
         B.mllm_op_rope(fake, fake, 4, 64, 0, 2, 64, 10000.0, stream=1)     # 2 heads of 64 do not fit a 64-wide row
     assert e.value.status == 3

@@ -143,6 +143,27 @@ def test_gemm_swiglu_fused(B, m, f, k):
     assert nmax_err(host_f64(act), host_f64(act2)) < 2e-2
 
 
+@pytest.mark.parametrize("m,f,k", [(4200, 3080, 320), (4352, 3328, 64), (6401, 2048, 192)])
+def test_gemm_swiglu_gradient_fused(B, m, f, k):
+    """Down-projection's input gradient with SwiGLU's gradient in the same pass: dA = dy.W_d^T is
+    never stored, [d gate | d up] is; ragged rows and (first case) a ragged last tile column."""
+    dy = W.draw_tensor(191, m, k)
+    w = W.bf16_round(W.draw_tensor(192, f, k) * np.float32(0.125))
+    pre = W.draw_tensor(193, m, 2 * f)
+    da = dy.astype(np.float64) @ w.astype(np.float64).T
+    g, u = pre[:, :f].astype(np.float64), pre[:, f:].astype(np.float64)
+    s = 1.0 / (1.0 + np.exp(-g))
+    ref = np.concatenate([da * u * s * (1.0 + g * (1.0 - s)), da * g * s], axis=1)
+    dpre = torch.full((m, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dyd, wd, pred = dev_bf16(dy), dev_bf16(w), dev_bf16(pre)
+    B.mllm_op_gemm_swiglu_bwd(dyd, wd, pred, dpre, m, f, k)
+    assert nmax_err(host_f64(dpre), ref) < 2e-2
+    da2, dpre2 = empty_bf16(m, f), empty_bf16(m, 2 * f)
+    B.mllm_op_gemm(dyd, wd, da2, m, f, k, 0, 1)
+    B.mllm_op_act_bwd(W.ACT_SWIGLU, da2, pred, dpre2, m, f)
+    assert nmax_err(host_f64(dpre), host_f64(dpre2)) < 2e-2
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_gemm_large_tiles_random_shapes(B, seed):
     """Seeded random problems that take the four-wavefront kernel: ragged M and N in every
