@@ -534,8 +534,9 @@ def main():
         kernel_names["gemm_dw"] = "gemm4_ragged_k_kernel<true> (dW = X^T.dY, fp32, 256x256x64 tiles, token count no multiple of 64)"
     # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
     # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
-    traffic_table = {"gemm_fwd": (1121310 * 2.0 + 367256) * 1024, "gemm_dx": (1526520 * 2.0 + 320439) * 1024,
-                     "gemm_dw": (1074080 * 2.0 + 134506) * 1024}
+    # (per class: launch-weighted mean over its kernels, the fused SwiGLU forms included)
+    traffic_table = {"gemm_fwd": (1122881 * 2.0 + 457873) * 1024, "gemm_dx": (1657537 * 2.0 + 451511) * 1024,
+                     "gemm_dw": (1071560 * 2.0 + 134505) * 1024}
     traffic = traffic_table[gemm_cls] if args.workload == "full_stage_32k" else None
     out = {
         "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",
