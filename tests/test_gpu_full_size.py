@@ -70,6 +70,20 @@ def test_weight_gradient_split_over_ragged_token_count(B):
         st.close()
 
 
+def test_decoder_layer_with_only_the_gradient_epilogue_fused(B):
+    """SwiGLU width 3264 = 51 x 64 on 4096 tokens: the up-projection cannot take the fused forward
+    form (f is no multiple of 128) and runs GEMM + activation kernel, the down-projection's input
+    gradient has 208 tiles and takes the fused form, with a last tile column of 192 valid columns."""
+    layers = [W.decoder_layer(512, 8, 2, 64, 3264, 10000.0)]
+    batch = W.Batch(None, W.make_pack([1500, 700, 1, 1895], W.MASK_CAUSAL), None, [])
+    wl = W.make_workload("dec_f3264", layers, batch, 913)
+    st = GpuStage(B, layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec7b_layer_full(B):
     wl = W.workload_dec7b(200)                       # 8192 packed tokens, d = 4096, MHA, SwiGLU 11008
     st = GpuStage(B, wl.layers)
