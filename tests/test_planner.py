@@ -8,6 +8,11 @@ Pins (none of them re-types the oracle's formulas):
   * FindCombs: the count of ordered factorisations n = tp.pp.dp is multiplicative with
     C(a+2, 2) for a prime power p^a (12 -> 18, 64 -> 28, 30 -> 27); every triple multiplies to n;
   * Eq. 1 on hand-worked numbers;
+  * Eq. 4, Eq. 5 and the body of Algorithm 1's Phase 2 on a toy table worked by hand (the
+    (E_pp + L_pp) and L_pp multipliers of the activation states, layers per stage, the microbatch
+    shapes t_bsz and t_seq_len, FLOPs per microbatch, throughput times tp times pp, the strict
+    memory comparison): every expected number below is written out, none is computed with the
+    oracle's formulas;
   * Algorithm 1 against a search that enumerates the whole box of 7-tuples and applies Eq. 2-5
     itself, and against the closed-form optimum for flat throughput and no memory pressure.
 """
@@ -173,6 +178,75 @@ def test_algorithm1_memory_forces_pipelining_or_fails():
     assert P.optimize(enc, llm, 8, 1, 1.0, 8, 1.0, 1.0) == (None, math.inf)
 
 
+# --------------------------------------------------------------------------------- Eq. 4, Eq. 5, Phase 2 by hand
+def toy_tables():
+    """Two TP degrees, profiled at 2 and 4 layers, two grid points each.
+    Encoder: model states 20 + 40 l bytes at TP 1 (100 at 2 layers, 180 at 4) and 20 + 20 l at TP 2;
+    activation states 5 l x bytes at TP 1 (2 layers: 10, 30 at x = 1, 3; 4 layers: 20, 60), half at TP 2;
+    throughput 100 x at TP 1, 80 x at TP 2.
+    LLM: model states 60 + 20 l at TP 1, 20 + 20 l at TP 2; activation states at TP 2: 2 layers 5, 15 and
+    4 layers 10, 30 at x = 100, 300 (twice that at TP 1); throughput 0.3 x at TP 1, 20 + 0.2 x at TP 2."""
+    enc = dict(tp=[1, 2], x=[1.0, 3.0], thr=[[100.0, 300.0], [80.0, 240.0]], layers_lo=2.0, layers_hi=4.0,
+               model_state=[[100.0, 180.0], [60.0, 100.0]],
+               act_state=[[[10.0, 30.0], [20.0, 60.0]], [[5.0, 15.0], [10.0, 30.0]]],
+               n_layers=8, flop_per_item=600.0)
+    llm = dict(tp=[1, 2], x=[100.0, 300.0], thr=[[30.0, 90.0], [40.0, 80.0]], layers_lo=2.0, layers_hi=4.0,
+               model_state=[[100.0, 140.0], [60.0, 100.0]],
+               act_state=[[[10.0, 30.0], [20.0, 60.0]], [[5.0, 15.0], [10.0, 30.0]]],
+               n_layers=6, flop_per_item=270.0)
+    return enc, llm
+
+
+def test_memory_equations_hand_worked():
+    enc, llm = toy_tables()
+    # Eq. 4, encoder of 8 layers on E_pp = 2 stages (4 layers per stage), TP 1, effective batch 2, L_pp = 3:
+    # model states 180; activation states of 4 layers at x = 2 are midway between 20 and 60 = 40, kept for
+    # E_pp + L_pp = 5 microbatches in flight: 180 + 5 * 40 = 380  (E_pp alone would give 260, L_pp alone 300)
+    assert P.mem_e(enc, 1, 2, 2.0, 3) == pytest.approx(380.0, rel=1e-14)
+    # the same stage behind a one-stage LLM: 180 + 3 * 40
+    assert P.mem_e(enc, 1, 2, 2.0, 1) == pytest.approx(300.0, rel=1e-14)
+    # E_pp = 4: 2 layers per stage: 100 + (4 + 3) * 20 = 240;  TP 2 halves the activations: 60 + 7 * 10 = 130
+    assert P.mem_e(enc, 1, 4, 2.0, 3) == pytest.approx(240.0, rel=1e-14)
+    assert P.mem_e(enc, 2, 4, 2.0, 3) == pytest.approx(130.0, rel=1e-14)
+    # E_pp = 1: 8 layers per stage lie beyond the profiled 2 and 4: the line continues, 20 + 40 * 8 = 340
+    # model states and 5 * 8 * 2 = 80 activation states: 340 + (1 + 3) * 80 = 660
+    assert P.mem_e(enc, 1, 1, 2.0, 3) == pytest.approx(660.0, rel=1e-14)
+    # Eq. 5, LLM of 6 layers on L_pp = 3 stages (2 layers per stage), TP 2, 200 packed tokens:
+    # model states 60, activation states midway between 5 and 15 = 10, times L_pp = 3: 90 (not 60 + 10)
+    assert P.mem_l(llm, 2, 3, 200.0) == pytest.approx(90.0, rel=1e-14)
+    # TP 1, L_pp = 2: 3 layers per stage: model states 120, activations at 200 tokens midway between the
+    # 2-layer 20 and the 4-layer 40 = 30, times 2: 180
+    assert P.mem_l(llm, 1, 2, 200.0) == pytest.approx(180.0, rel=1e-14)
+
+
+HAND_THETA = (1, 2, 3, 2, 3, 1, 4)      # E_tp, E_pp, E_dp, L_tp, L_pp, L_dp, N_mb: 6 + 6 GPUs
+
+
+def test_phase2_body_hand_worked():
+    """GBS 16, mean effective batch 1.5, mean sequence length 50, N_mb = 4:
+    t_bsz = 1.5 * 16 / (4 * 3) = 2, t_seq_len = 50 * 16 / (4 * 1) = 200, so the memory figures are the
+    380 and 90 of the test above.  Encoder FLOPs per microbatch 600 * 16 / 12 = 800 at 200 FLOP/s per GPU
+    on 1 * 2 GPUs: 2 s.  LLM 270 * 16 / 4 = 1080 at 60 FLOP/s per GPU on 2 * 3 GPUs: 3 s.
+    T = (4 + 2 + 3 - 1) * 3 = 24 s."""
+    enc, llm = toy_tables()
+    assert P.evaluate(enc, llm, HAND_THETA, 1e9, 16, 1.5, 50.0) == pytest.approx(24.0, rel=1e-14)
+    assert P.evaluate(enc, llm, HAND_THETA, 380.0, 16, 1.5, 50.0) == pytest.approx(24.0, rel=1e-14)   # equal still fits
+    assert P.evaluate(enc, llm, HAND_THETA, 379.9, 16, 1.5, 50.0) is None                             # Mem_E = 380
+    # N_mb = 2 doubles both microbatch shapes: t_bsz = 4 lies beyond the grid, throughput holds 300, the
+    # activation line continues to 80: Mem_E = 180 + 5 * 80 = 580; t_seq_len = 400: throughput holds 80,
+    # activations 2 layers at TP 2 continue to 20: Mem_L = 60 + 3 * 20 = 120.
+    # E_dur = 1600 / (300 * 2) = 8 / 3, L_dur = 2160 / (80 * 6) = 4.5, T = (2 + 4) * 4.5 = 27
+    theta2 = HAND_THETA[:6] + (2,)
+    assert P.evaluate(enc, llm, theta2, 580.0, 16, 1.5, 50.0) == pytest.approx(27.0, rel=1e-14)
+    assert P.evaluate(enc, llm, theta2, 579.0, 16, 1.5, 50.0) is None
+    # an LLM five times as memory-hungry is what binds: Mem_L = 5 * 90 = 450 > 400 >= Mem_E
+    big = dict(llm, model_state=[[5 * v for v in r] for r in llm["model_state"]],
+               act_state=[[[5 * v for v in row] for row in per_l] for per_l in llm["act_state"]])
+    assert P.evaluate(enc, big, HAND_THETA, 400.0, 16, 1.5, 50.0) is None
+    assert P.evaluate(enc, big, HAND_THETA, 450.0, 16, 1.5, 50.0) == pytest.approx(24.0, rel=1e-14)
+
+
+
 # --------------------------------------------------------------------------------- library vs oracle
 @pytest.fixture(scope="module")
 def B():
@@ -248,3 +322,17 @@ def test_library_planner_rejects_bad_arguments(B):
     bad = dict(enc, layers_hi=enc["layers_lo"])
     with pytest.raises(B.MllmError):
         B.mllm_optimize_parallelism(bad, llm, 4, 8, 1e30, 8, 1.0, 1.0)
+
+
+def test_library_evaluation_hand_worked(B):
+    """The library's single-configuration evaluation on the same toy tables: the hand-worked 24 s, 380 and
+    90 bytes, and the strict comparison with the capacity."""
+    enc, llm = toy_tables()
+    span, em, lm, ok = B.mllm_evaluate_parallelism(enc, llm, HAND_THETA, 380.0, 16, 1.5, 50.0)
+    assert ok and span == pytest.approx(24.0, rel=1e-13)
+    assert em == pytest.approx(380.0, rel=1e-13) and lm == pytest.approx(90.0, rel=1e-13)
+    _, em, lm, ok = B.mllm_evaluate_parallelism(enc, llm, HAND_THETA, 379.9, 16, 1.5, 50.0)
+    assert not ok and em == pytest.approx(380.0, rel=1e-13)
+    span, em, lm, ok = B.mllm_evaluate_parallelism(enc, llm, HAND_THETA[:6] + (2,), 580.0, 16, 1.5, 50.0)
+    assert ok and span == pytest.approx(27.0, rel=1e-13)
+    assert em == pytest.approx(580.0, rel=1e-13) and lm == pytest.approx(120.0, rel=1e-13)
