@@ -392,8 +392,8 @@ def plan_experiment(args):
     enc, llm = MP.StageRunner(enc_layers), MP.StageRunner(llm_layers)
     b_grid = [1, 2, 4, 8, 16, 32, 56]
     s_grid = [128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768]
-    bx, e_thr, e_ms = MP.profile_encoder(enc, b_grid)
-    sx, lin_thr, attn_thr, l_ms, l_attn_ms, l_attn_packed_ms = MP.profile_llm(llm, s_grid)
+    bx, e_thr, e_ms = MP.profile_encoder(enc, b_grid, lambda b: W.batch_from_samples([(b, 1)]))
+    sx, lin_thr, attn_thr, l_ms, l_attn_ms, l_attn_packed_ms = MP.profile_llm(llm, s_grid, W.equal_partition_batch)
     print("## Throughput profiling (forward + backward, model FLOPs)\n")
     print("| images | encoder stage ms | E_thr TFLOP/s |\n|---|---|---|")
     for b, ms, thr in zip(b_grid, e_ms, e_thr):

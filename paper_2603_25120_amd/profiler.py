@@ -7,6 +7,10 @@ encoder is profiled against its effective batch size (images per microbatch) and
 the sequence length, attention and the linear operations separately ("Throughput Profiling").
 Only TP degree 1 can be measured on one GPU.
 
+The caller supplies the microbatches: `make_images(b)` builds a microbatch of b images,
+`make_partition(total, n)` one of `total` packed tokens cut into n equal samples.  A microbatch is
+any object with the fields of mllm_batch_t (img / seq packs with cu_seqlens and mask_kind).
+
 FLOP convention: 2mnk per GEMM, backward = 2 x forward, causal attention at half the square, no
 credit for recomputation.
 """
@@ -16,15 +20,18 @@ from typing import Callable, List, Sequence, Tuple
 
 import numpy as np
 
-import workloads as W
 from . import binding as B
+
+# values of the C ABI's enums (mllm_stage.h)
+LAYER_VIT, LAYER_DECODER, LAYER_PROJECTOR = 0, 1, 2
+MASK_CAUSAL = 1
 
 BYTES_PER_PARAM_STATE = 18.0   # bf16 weight + fp32 gradient + fp32 master copy and two Adam moments
 
 
 def visible_pairs(pack) -> float:
     lens = np.diff(pack.cu_seqlens).astype(np.float64)
-    w = np.where(pack.mask_kind == W.MASK_CAUSAL, 0.5, 1.0)
+    w = np.where(pack.mask_kind == MASK_CAUSAL, 0.5, 1.0)
     return float(np.sum(w * lens * lens))
 
 
@@ -32,13 +39,13 @@ def stage_fwd_flops(layers, batch) -> Tuple[float, float]:
     """(linear, attention) forward model FLOPs of a stage over a microbatch."""
     lin = attn = 0.0
     for L in layers:
-        if L.kind == W.LAYER_PROJECTOR:
+        if L.kind == LAYER_PROJECTOR:
             lin += 2.0 * batch.img.total_tokens * L.d_model * L.d_out
             continue
-        pack = batch.img if L.kind == W.LAYER_VIT else batch.seq
+        pack = batch.img if L.kind == LAYER_VIT else batch.seq
         T = pack.total_tokens
         nqkv = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim
-        fup = L.d_ff if L.kind == W.LAYER_VIT else 2 * L.d_ff
+        fup = L.d_ff if L.kind == LAYER_VIT else 2 * L.d_ff
         lin += 2.0 * T * L.d_model * (nqkv + L.d_model + fup) + 2.0 * T * L.d_ff * L.d_model
         attn += 4.0 * visible_pairs(pack) * L.n_q_heads * L.head_dim
     return lin, attn
@@ -66,15 +73,15 @@ class StageRunner:
     def _buffers(self, batch):
         t, layers = self.torch, self.layers
         kinds = [l.kind for l in layers]
-        uses_img = kinds[0] in (W.LAYER_VIT, W.LAYER_PROJECTOR)
-        uses_seq = W.LAYER_DECODER in kinds or W.LAYER_PROJECTOR in kinds
+        uses_img = kinds[0] in (LAYER_VIT, LAYER_PROJECTOR)
+        uses_seq = LAYER_DECODER in kinds or LAYER_PROJECTOR in kinds
         x_img = self.randn(batch.img.total_tokens, layers[0].d_model) if uses_img else None
-        d_seq = next((l.d_out if l.kind == W.LAYER_PROJECTOR else l.d_model) for l in layers
-                     if l.kind != W.LAYER_VIT) if uses_seq else 0
+        d_seq = next((l.d_out if l.kind == LAYER_PROJECTOR else l.d_model) for l in layers
+                     if l.kind != LAYER_VIT) if uses_seq else 0
         x_seq = self.randn(batch.seq.total_tokens, d_seq) if uses_seq else None
         last = layers[-1]
-        rows = batch.img.total_tokens if last.kind == W.LAYER_VIT else batch.seq.total_tokens
-        cols = last.d_out if last.kind == W.LAYER_PROJECTOR else last.d_model
+        rows = batch.img.total_tokens if last.kind == LAYER_VIT else batch.seq.total_tokens
+        cols = last.d_out if last.kind == LAYER_PROJECTOR else last.d_model
         dy = self.randn(rows, cols)
         y = t.empty(rows, cols, dtype=t.bfloat16, device=self.dev)
         sb, wb = B.mllm_stage_sizes(self.h, batch)
@@ -126,11 +133,11 @@ class StageRunner:
         B.mllm_stage_destroy(self.h)
 
 
-def profile_encoder(runner: StageRunner, image_counts: Sequence[int]):
+def profile_encoder(runner: StageRunner, image_counts: Sequence[int], make_images: Callable[[int], object]):
     """E_thr over the effective batch size: (x, FLOP/s, ms per step)."""
     thr, ms = [], []
     for b in image_counts:
-        batch = W.batch_from_samples([(int(b), 1)])
+        batch = make_images(int(b))
         lin, attn = stage_fwd_flops(runner.layers, batch)
         t = runner.time(batch)
         ms.append(t)
@@ -138,7 +145,8 @@ def profile_encoder(runner: StageRunner, image_counts: Sequence[int]):
     return np.array(image_counts, dtype=np.float64), np.array(thr), np.array(ms)
 
 
-def profile_llm(runner: StageRunner, seq_lens: Sequence[int], packed_tokens: int = 16384):
+def profile_llm(runner: StageRunner, seq_lens: Sequence[int], make_partition: Callable[[int, int], object],
+                packed_tokens: int = 16384):
     """L_lin_thr and L_attn_thr over the sequence length ("Throughput Profiling": the two are
     measured independently).  Linear operations see only the packed length, so their throughput at
     s comes from one sequence of s tokens (step time minus the attention kernels' time).
@@ -149,14 +157,14 @@ def profile_llm(runner: StageRunner, seq_lens: Sequence[int], packed_tokens: int
     attention, attention ms of the packed partition)."""
     lin_thr, attn_thr, ms, ms_attn, ms_attn_packed = [], [], [], [], []
     for s in seq_lens:
-        lone = W.equal_partition_batch(int(s), 1)
+        lone = make_partition(int(s), 1)
         lin, _ = stage_fwd_flops(runner.layers, lone)
         total, t_attn = runner.time_split(lone)
         ms.append(total)
         ms_attn.append(t_attn)
         lin_thr.append(3.0 * lin / ((total - t_attn) * 1e-3))
         n_seg = max(1, packed_tokens // int(s))
-        packed = W.equal_partition_batch(int(s) * n_seg, n_seg)
+        packed = make_partition(int(s) * n_seg, n_seg)
         _, attn = stage_fwd_flops(runner.layers, packed)
         _, t_attn_p = runner.time_split(packed) if n_seg > 1 else (total, t_attn)
         ms_attn_packed.append(t_attn_p)

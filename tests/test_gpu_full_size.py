@@ -2,10 +2,11 @@
 
 * ViT-L layer and 7B decoder layer: the whole layer, forward and backward, every output and every
   gradient against the fp64 oracle (the oracle finishes these in seconds on the host cores).
-* 8B-GQA decoder layer at 32768 packed tokens: the GPU runs the full microbatch; the oracle runs
-  the shortest, the longest and one middle sample ALONE.  Rows of a sample do not depend on what
-  it is packed with (per-instance attention, row-wise linear maps: Model Profiler, "Throughput
-  Profiling"), so y and dx rows of those samples must match the per-sample oracle.
+* 8B-GQA decoder layer at 32768 packed tokens: the whole layer too, every output and every gradient.
+* A 7-layer full-width stack on the benchmark's 32768-token microbatch: the oracle runs one sample
+  ALONE through all layers.  Rows of a sample do not depend on what it is packed with (per-instance
+  attention, row-wise linear maps: Model Profiler, "Throughput Profiling").  The benchmark's own
+  33-layer stack is covered layer by layer in test_gpu_stack_in_situ.py.
 * The kernels at the full shapes on sampled outputs: GEMM entries (all three layouts of the 8B
   layer, including the weight-gradient contraction over 32768 tokens) against fp64 dot products,
   attention rows of sampled (segment, head) pairs against the oracle run on that pair only.
@@ -117,42 +118,30 @@ def test_internvit_6b_layer_full_width(B):
         st.close()
 
 
-def test_dec8b_layer_sampled_samples(B):
-    wl = W.workload_dec8b(300)                       # 32768 packed tokens, GQA 32/8, SwiGLU 14336
+def test_dec8b_layer_full(B):
+    """The 8B-GQA decoder layer on its whole 32768-token microbatch (seed 300, 32 / 8 heads, SwiGLU
+    14336): y, dx and EVERY parameter gradient (each a contraction over all 32768 tokens) against the
+    fp64 oracle run on the same microbatch (about a minute on 16 host cores)."""
+    wl = W.workload_dec8b(300)
     st = GpuStage(B, wl.layers)
     try:
-        y, _, dx_seq, _ = st.run(wl)
-        y, dx_seq = host_f64(y), host_f64(dx_seq)
+        got = st.run(wl)
     finally:
         st.close()
-    cu = wl.batch.seq.cu_seqlens
-    lens = np.diff(cu)
-    order = np.argsort(lens)
-    picks = sorted({int(order[0]), int(order[len(order) // 2]), int(order[-1])})
-    for s in picks:
-        a, b = int(cu[s]), int(cu[s + 1])
-        one = W.Workload("one", wl.layers, W.Batch(None, W.make_pack([b - a], W.MASK_CAUSAL), None, []),
-                         wl.params, None, wl.x_seq[a:b], wl.dy[a:b])
-        y_ref, caches = O.stage_fwd(one.layers, one.params, one.batch, None, one.x_seq)
-        _, dx_ref, _ = O.stage_bwd(one.layers, one.params, one.batch, caches, one.dy.astype(np.float64))
-        assert nmax_err(y[a:b], y_ref) <= 2e-2, ("y", s, b - a)
-        assert nmax_err(dx_seq[a:b], dx_ref) <= 3e-2, ("dx", s, b - a)
+    errs = compare(st, wl, got, oracle_run(wl))
+    print("8B-GQA layer, 32768 tokens: %s" % ", ".join("%s %.2e" % kv for kv in errs.items()), flush=True)
 
 
-@pytest.mark.parametrize("n_vit,n_dec", [(4, 2), (24, 8)])
+@pytest.mark.parametrize("n_vit,n_dec", [(4, 2)])
 def test_full_width_stack_32k_one_sample_through_all_layers(B, n_vit, n_dec):
-    """The benchmark's microbatch (seed 414, 32768 packed tokens, 43 images) through the benchmark's
-    layers at full width: 4 ViT-L + connector + 2 8B-GQA layers, and the benchmark's own 24 + 1 + 8.
-    The GPU runs the whole microbatch; the oracle runs the shortest image-bearing sample alone
-    through every layer.  Its rows of y, dx_seq and dx_img must match: a sample's rows do not depend
-    on what it is packed with (Model Profiler, "Throughput Profiling").
-
-    Tolerance: the stated 2e-2 / 3e-2 for stacks of up to 8 layers.  Every layer rounds about ten
-    intermediate tensors to bf16 independently of the others, so the error of a deeper stack grows
-    like the square root of its depth: the 33-layer stack is held to sqrt(33 / 8) = 2.03 times the
-    stated tolerances (measured: y 3.1e-2)."""
+    """The benchmark's microbatch (seed 414, 32768 packed tokens, 39 images) through 4 ViT-L layers +
+    connector + 2 8B-GQA layers at full width.  The GPU runs the whole microbatch; the oracle runs the
+    shortest image-bearing sample alone through every layer.  Its rows of y, dx_seq and dx_img must
+    match at the stated tolerances: a sample's rows do not depend on what it is packed with (Model
+    Profiler, "Throughput Profiling")."""
     wl = W.workload_full_stage(414, 32768, "8b", n_vit=n_vit, n_dec=n_dec)
-    scale = max(1.0, np.sqrt(len(wl.layers) / 8.0))
+    scale = 1.0
+    assert len(wl.layers) <= 8
     st = GpuStage(B, wl.layers)
     try:
         y, dx_img, dx_seq, _ = st.run(wl)

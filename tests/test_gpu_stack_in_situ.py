@@ -1,0 +1,228 @@
+"""Every layer of the benchmark's own 33-layer stack, checked where it stands.
+
+The benchmark times 24 ViT-L layers + connector + 8 8B-GQA decoder layers on the 32768-token
+microbatch of seed 414.  Through that depth the bf16 roundings of the layers add up, so the
+end-to-end error of the stack says little about any one layer.  Here each layer is isolated:
+
+* The stack is run once as ONE stage (what the benchmark times) and once as a chain of 33
+  single-layer stages, each fed the previous one's output (forward) or input gradient (backward).
+  Both must agree bit for bit: the chain runs the same kernels on the same shapes, so its
+  per-layer tensors are the stack's own intermediate tensors.
+* For every layer the fp64 oracle's single layer then takes the GPU's OWN layer input (and, in
+  backward, the GPU's own upstream gradient) and must reproduce the GPU's layer output, its
+  residual-branch update y - x, and its input gradient within the stated 2e-2 / 3e-2, unscaled.
+  Rows of a sample depend on no other sample (per-instance attention, row-wise linear maps:
+  Model Profiler, "Throughput Profiling"), so for most layers the oracle runs the rows of a few
+  whole samples (images); the first, a middle and the last encoder layer, the connector and the
+  last decoder layer run on ALL tokens, which also checks every parameter gradient of those
+  layers in place.
+* End to end: the whole 33-layer stack on the smallest of the seeded full-stage microbatches
+  (4096 tokens), every output and every parameter gradient of every layer against the oracle
+  run through all layers; this one carries the accumulated error and is held to sqrt(33 / 8)
+  times the stated tolerances (independent roundings per layer add in quadrature).
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import stage_oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from tests.gpu_util import TOL_GRAD, TOL_OUT, GpuStage, dev_bf16, host_f64, nmax_err, oracle_run, scratch  # noqa: E402
+
+N_VIT, N_DEC = 24, 8
+FULL_TOKEN_LAYERS = (0, 12, 23, 24, 32)     # all tokens: outputs, input gradients and every parameter gradient
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_25120_amd import binding
+    binding.lib()
+    return binding
+
+
+class OneLayer:
+    """A stage of one layer: forward keeps what backward needs."""
+
+    def __init__(self, B, layer, batch):
+        self.B, self.layer, self.batch = B, layer, batch
+        self.h = B.mllm_stage_create([layer])
+        self.infos = [B.mllm_stage_param_info(self.h, i) for i in range(B.mllm_stage_param_count(self.h))]
+        sb, wb = B.mllm_stage_sizes(self.h, batch)
+        self.saved, self.ws = scratch(sb), scratch(wb)
+
+    def fwd(self, params, x_img, x_seq, out_shape):
+        y = torch.zeros(out_shape, dtype=torch.bfloat16, device="cuda")
+        self.B.mllm_stage_fwd(self.h, self.batch, params, x_img, x_seq, y, self.saved, self.ws)
+        return y
+
+    def bwd(self, params, dy, want_img, want_seq):
+        dparams = [torch.full((r, c), float("nan"), dtype=torch.float32, device="cuda") for _, _, r, c in self.infos]
+        dx_img = torch.zeros(want_img, dtype=torch.bfloat16, device="cuda") if want_img else None
+        dx_seq = torch.zeros(want_seq, dtype=torch.bfloat16, device="cuda") if want_seq else None
+        self.B.mllm_stage_bwd(self.h, self.batch, params, dy, self.saved, dx_img, dx_seq, dparams, 0, self.ws)
+        return dx_img, dx_seq, dparams
+
+    def close(self):
+        self.B.mllm_stage_destroy(self.h)
+        self.saved = self.ws = None
+
+
+@pytest.fixture(scope="module")
+def stack(B):
+    """Runs the benchmark stack both ways on the GPU and keeps the chain's per-layer tensors."""
+    wl = W.workload_full_stage(414, 32768, "8b", n_vit=N_VIT, n_dec=N_DEC)
+    layers, batch = wl.layers, wl.batch
+    T_img, T = batch.img.total_tokens, batch.seq.total_tokens
+    st = GpuStage(B, layers)
+    y_full, dxi_full, dxs_full, dp_full = st.run(wl)
+    st.close()
+
+    offs, pi = [], 0
+    for L in layers:
+        offs.append(pi)
+        pi += O.n_params(L)
+    params = [dev_bf16(p) for p in wl.params]
+    x_img0, x_seq0, dy_top = dev_bf16(wl.x_img), dev_bf16(wl.x_seq), dev_bf16(wl.dy)
+    runners, xs, ys = [], [], []
+    cur = x_img0
+    for i, L in enumerate(layers):
+        r = OneLayer(B, L, batch)
+        prm = params[offs[i]:offs[i] + O.n_params(L)]
+        if L.kind == W.LAYER_VIT:
+            y = r.fwd(prm, cur, None, (T_img, L.d_model))
+        elif L.kind == W.LAYER_PROJECTOR:
+            y = r.fwd(prm, cur, x_seq0, (T, L.d_out))
+        else:
+            y = r.fwd(prm, None, cur, (T, L.d_model))
+        runners.append(r)
+        xs.append(cur)
+        ys.append(y)
+        cur = y
+    dys, dxs, dps = [None] * len(layers), [None] * len(layers), [None] * len(layers)
+    dx_seq_text = None
+    g = dy_top
+    for i in range(len(layers) - 1, -1, -1):
+        L, r = layers[i], runners[i]
+        prm = params[offs[i]:offs[i] + O.n_params(L)]
+        dys[i] = g
+        if L.kind == W.LAYER_VIT:
+            dxi, _, dp = r.bwd(prm, g, (T_img, L.d_model), None)
+            g = dxi
+        elif L.kind == W.LAYER_PROJECTOR:
+            dxi, dx_seq_text, dp = r.bwd(prm, g, (T_img, L.d_model), (T, L.d_out))
+            g = dxi
+        else:
+            _, dxs_, dp = r.bwd(prm, g, None, (T, L.d_model))
+            g = dxs_
+        dxs[i], dps[i] = g, dp
+        r.close()
+    torch.cuda.synchronize()
+    return dict(wl=wl, offs=offs, xs=xs, ys=ys, dys=dys, dxs=dxs, dps=dps, x_seq0=x_seq0, dx_seq_text=dx_seq_text,
+                full=(y_full, dxi_full, dxs_full, dp_full))
+
+
+def test_chain_of_single_layer_stages_is_the_stack_bit_for_bit(stack):
+    y_full, dxi_full, dxs_full, dp_full = stack["full"]
+    assert torch.equal(stack["ys"][-1], y_full)
+    assert torch.equal(stack["dxs"][0], dxi_full)
+    assert torch.equal(stack["dx_seq_text"], dxs_full)
+    flat = [g for dp in stack["dps"] for g in dp]
+    assert len(flat) == len(dp_full)
+    for i, (a, b) in enumerate(zip(flat, dp_full)):
+        assert torch.equal(a, b), "parameter gradient %d differs between the chain and the stack" % i
+
+
+def _picked_samples(batch):
+    """The shortest sample, the shortest one with an image and the one of median length."""
+    lens = np.diff(batch.seq.cu_seqlens)
+    order = [int(i) for i in np.argsort(lens, kind="stable")]
+    with_img = [i for i in order if batch.samples[i][0] >= 1]
+    return sorted({order[0], with_img[0], order[len(order) // 2]})
+
+
+def _rows_of(cu, picks):
+    return np.concatenate([np.arange(int(cu[s]), int(cu[s + 1])) for s in picks])
+
+
+@pytest.mark.parametrize("i", range(N_VIT + 1 + N_DEC))
+def test_layer_in_situ(stack, i):
+    wl = stack["wl"]
+    L, batch = wl.layers[i], wl.batch
+    P = wl.params[stack["offs"][i]:stack["offs"][i] + O.n_params(L)]
+    full = i in FULL_TOKEN_LAYERS
+    x, y, dy, dx = stack["xs"][i], stack["ys"][i], stack["dys"][i], stack["dxs"][i]
+    if L.kind == W.LAYER_PROJECTOR:
+        # the connector always runs on all tokens (it is cheap): y = x_seq with the image rows replaced
+        sub = batch
+        x_img, x_seq = host_f64(x), host_f64(stack["x_seq0"])
+        y_g, dy_g, dx_g = host_f64(y), host_f64(dy), host_f64(dx)
+        branch_g = branch_ref = None
+    else:
+        vit = L.kind == W.LAYER_VIT
+        pack = batch.img if vit else batch.seq
+        if full:
+            rows, sub_pack = np.arange(pack.total_tokens), pack
+        elif vit:
+            n_img = pack.n_segments
+            picks = sorted({0, n_img // 2, n_img - 1})
+            rows, sub_pack = _rows_of(pack.cu_seqlens, picks), W.make_pack([W.IMG_TOKENS] * len(picks), W.MASK_BIDIR)
+        else:
+            picks = _picked_samples(batch)
+            lens = [int(pack.cu_seqlens[s + 1] - pack.cu_seqlens[s]) for s in picks]
+            rows, sub_pack = _rows_of(pack.cu_seqlens, picks), W.make_pack(lens, W.MASK_CAUSAL)
+        idx = torch.as_tensor(rows, device="cuda")
+        x_rows = host_f64(x[idx])
+        sub = W.Batch(sub_pack, None, None, []) if vit else W.Batch(None, sub_pack, None, [])
+        x_img, x_seq = (x_rows, None) if vit else (None, x_rows)
+        y_g, dy_g, dx_g = host_f64(y[idx]), host_f64(dy[idx]), host_f64(dx[idx])
+        branch_g = y_g - x_rows
+    y_ref, caches = O.stage_fwd([L], P, sub, x_img, x_seq)
+    dxi_ref, dxs_ref, dp_ref = O.stage_bwd([L], P, sub, caches, dy_g)
+    errs = {"y": nmax_err(y_g, y_ref)}
+    if L.kind == W.LAYER_PROJECTOR:
+        errs["dx"] = nmax_err(dx_g, dxi_ref)
+        errs["dx_seq"] = nmax_err(host_f64(stack["dx_seq_text"]), dxs_ref)
+    else:
+        branch_ref = y_ref - (x_img if x_img is not None else x_seq)
+        errs["branch"] = nmax_err(branch_g, branch_ref)
+        errs["dx"] = nmax_err(dx_g, dxi_ref if dxi_ref is not None else dxs_ref)
+    if full:
+        names = [n for n, _, _ in W.param_specs(L)]
+        for name, g, r in zip(names, stack["dps"][i], dp_ref):
+            errs["d." + name] = nmax_err(host_f64(g), r)
+    print("layer %d (%s rows %d): %s" % (i, "all" if full else "sampled", y_g.shape[0],
+                                          ", ".join("%s %.2e" % kv for kv in errs.items())), flush=True)
+    assert errs["y"] <= TOL_OUT, errs
+    assert errs.get("branch", 0.0) <= TOL_OUT, errs
+    bad = {k: v for k, v in errs.items() if k not in ("y", "branch") and not v <= TOL_GRAD}
+    assert not bad, bad
+
+
+def test_whole_stack_end_to_end_on_the_smallest_seeded_microbatch(B):
+    seed, budget, mix = min(W.full_stage_sweep(), key=lambda c: (c[1], c[0]))
+    assert budget == 4096
+    wl = W.workload_full_stage(seed, budget, mix, n_vit=N_VIT, n_dec=N_DEC)
+    scale = float(np.sqrt(len(wl.layers) / 8.0))
+    st = GpuStage(B, wl.layers)
+    try:
+        y, dx_img, dx_seq, dparams = st.run(wl)
+        infos = st.infos
+    finally:
+        st.close()
+    y_r, dxi_r, dxs_r, dp_r = oracle_run(wl)
+    errs = {"y": nmax_err(host_f64(y), y_r), "dx_img": nmax_err(host_f64(dx_img), dxi_r),
+            "dx_seq": nmax_err(host_f64(dx_seq), dxs_r)}
+    worst = {}
+    for (name, layer, _, _), g, r in zip(infos, dparams, dp_r):
+        e = nmax_err(host_f64(g), r)
+        errs["L%d.%s" % (layer, name)] = e
+        worst[layer] = max(worst.get(layer, 0.0), e)
+    print("end to end, %d tokens (seed %d, mix %s), tolerance scale %.2f: y %.2e dx_img %.2e dx_seq %.2e; "
+          "worst parameter gradient per layer: %s" % (budget, seed, mix, scale, errs["y"], errs["dx_img"], errs["dx_seq"],
+                                                     " ".join("%d:%.1e" % kv for kv in sorted(worst.items()))), flush=True)
+    assert errs["y"] <= TOL_OUT * scale, errs["y"]
+    bad = {k: v for k, v in errs.items() if k != "y" and not v <= TOL_GRAD * scale}
+    assert not bad, bad
