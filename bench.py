@@ -32,6 +32,44 @@ MFMA_BF16_PEAK = 2.5e15   # dense, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
 
 
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_full_stage_32k.md")
+TRAFFIC_KERNELS = {"gemm_fwd": "gemm4_kernel<4, false, true, false>", "gemm_dx": "gemm4_kernel<4, false, false, false>",
+                   "gemm_dw": "gemm4_kernel<4, true, true, true>"}
+
+
+def gemm_source_digest():
+    """First 16 hex digits of the SHA-256 of the GEMM kernel sources."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("gemm.hip", "gemm_common.h"):
+        with open(os.path.join(ROOT, "paper_2603_25120_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(gemm_cls, workload):
+    """L2 <-> fabric bytes per launch of the class's kernel, read from the committed summary of the two
+    `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE) of this command.  The summary names the digest of the
+    kernel sources it was taken with; when the sources have changed since, the figure is withheld (None)."""
+    import re
+    if workload != "full_stage_32k":
+        return None, "counters were collected on the default workload only"
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None, "profiles/hbm_traffic_full_stage_32k.md is missing"
+    m = re.search(r"GEMM kernel sources digest: ([0-9a-f]{16})", text)
+    if not m:
+        return None, "the summary names no kernel source digest"
+    if m.group(1) != gemm_source_digest():
+        return None, "stale: the summary was taken with kernel sources %s, these are %s" % (m.group(1), gemm_source_digest())
+    row = re.search(r"\| `%s` \| \d+ \| (\d+) \| (\d+) \|" % re.escape(TRAFFIC_KERNELS[gemm_cls]), text)
+    if not row:
+        return None, "the summary has no row for %s" % TRAFFIC_KERNELS[gemm_cls]
+    fetch_kib, write_kib = float(row.group(1)), float(row.group(2))
+    return (fetch_kib * 2.0 + write_kib) * 1024.0, "profiles/hbm_traffic_full_stage_32k.md (kernel sources %s)" % m.group(1)
+
+
 def stage_fwd_flops(layers, batch):
     from paper_2603_25120_amd.profiler import stage_fwd_flops as f
     return f(layers, batch)
@@ -532,12 +570,10 @@ def main():
     ragged = any(pk is not None and pk.total_tokens % 64 for pk in (wl.batch.img, wl.batch.seq))
     if ragged:
         kernel_names["gemm_dw"] = "gemm4_ragged_k_kernel<true> (dW = X^T.dY, fp32, 256x256x64 tiles, token count no multiple of 64)"
-    # HBM-side bytes per launch of that kernel on the default workload: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-    # (KiB per dispatch, factors from a copy kernel of known size), see profiles/hbm_traffic_full_stage_32k.md
-    # (per class: launch-weighted mean over its kernels, the fused SwiGLU forms included)
-    traffic_table = {"gemm_fwd": (1122881 * 2.0 + 457873) * 1024, "gemm_dx": (1657537 * 2.0 + 451511) * 1024,
-                     "gemm_dw": (1071560 * 2.0 + 134505) * 1024}
-    traffic = traffic_table[gemm_cls] if args.workload == "full_stage_32k" else None
+    traffic, traffic_note = recorded_traffic(gemm_cls, args.workload)
+    # the large-tile kernels stream, per XCD, the 8 A panels and 4 B panels of an 8 x 4 block of 256 x 256 tiles
+    # through L2 once: 2 M N K (1 / 2048 + 1 / 1024) bytes fetched per launch (bf16 operands)
+    traffic_model = (work / n) * (1.0 / 2048 + 1.0 / 1024) if n else None
     out = {
         "metric": "packed tokens/s per stage fwd+bwd (bf16) + % of MFMA bf16 peak",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -558,7 +594,8 @@ def main():
         "host_wall_ms_per_step": r["wall_ms"] / args.steps,
         "roofline": {"bound": "mfma", "kernel": kernel_names[gemm_cls], "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
-                     "traffic": traffic, "traffic_unit": "bytes per launch (L2 <-> fabric)", "launches": n, "avg_launch_ms": ms / n if n else None,
+                     "traffic": traffic, "traffic_unit": "bytes per launch (L2 <-> fabric), FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB from rocprofv3 --pmc",
+                     "traffic_source": traffic_note, "traffic_model_fetch_bytes": traffic_model, "launches": n, "avg_launch_ms": ms / n if n else None,
                      "all_gemm_tflops": all_gemm_work / (all_gemm_ms * 1e-3) / 1e12 if all_gemm_ms else None},
         "breakdown_ms_per_step": {c: prof[c][1] / args.steps for c in prof},
         "breakdown_rate": {
