@@ -22,7 +22,13 @@
  *     enqueued: on a status other than MLLM_OK and MLLM_ERR_HIP nothing was launched and no
  *     output was touched.  mllm_last_error() returns a thread-local message for the last failure.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
- *     and return without waiting.  Host arrays are consumed before the call returns.
+ *     and return without waiting.  Host arrays are consumed before the call returns: the small
+ *     per-call metadata (attention tile lists, positions, scatter rows) are built in pinned host
+ *     memory owned by the handle (mllm_op_attn_*: by the calling thread) and copied on
+ *     `hip_stream` in front of the kernels.  That staging is a ring of 4 slots: a call waits only
+ *     when the host runs 4 calls ahead of the GPU.  mllm_stage_sizes reserves the slots for the
+ *     microbatch it is asked about; mllm_stage_fwd / mllm_stage_bwd allocate pinned host memory
+ *     only for a microbatch whose metadata exceed every earlier reservation.
  *   - One handle must not be used from two threads at once.  Same inputs give bitwise-identical
  *     outputs (no atomics in any reduction).
  */

@@ -1,16 +1,19 @@
 // C ABI for the single operations (mllm_op_*): argument checks, then the same launchers the
-// stage uses.  The attention entry points build their tile list on the host and copy it into the
-// caller's workspace with a blocking copy (they exist for checking kernels, not for pipelining).
+// stage uses.  The attention entry points build their tile lists on the host in pinned staging
+// memory (a per-thread ring of slots) and copy them into the caller's workspace on the caller's
+// stream, in front of the kernel that reads them.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 #include <string>
 #include <vector>
 
 #include "../../include/mllm_stage.h"
 #include "kernels.h"
+#include "pinned_ring.h"
 
 using namespace mllm;
 
@@ -86,14 +89,29 @@ mllm_status_t check_attn(const mllm_pack_t* pack, int32_t hq, int32_t hkv, int32
     if (e_ != hipSuccess) return op_fail(MLLM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
-mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a) {
+// One ring per host thread (the library keeps no other state between op calls); never freed.
+PinnedRing& op_staging() {
+  thread_local PinnedRing* ring = new PinnedRing();
+  return *ring;
+}
+
+mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a, hipStream_t stream) {
   std::vector<AttnTile> qt, kt;
   build_tiles(*pack, ATTN_FWD_Q_TILE, false, qt);
   build_tiles(*pack, ATTN_BWD_KV_TILE, true, kt);
   char* w = (char*)ws;
   const size_t koff = align_up(sizeof(AttnTile) * qt.size());
-  if (!qt.empty()) OP_TRY(hipMemcpy(w, qt.data(), sizeof(AttnTile) * qt.size(), hipMemcpyHostToDevice));
-  if (!kt.empty()) OP_TRY(hipMemcpy(w + koff, kt.data(), sizeof(AttnTile) * kt.size(), hipMemcpyHostToDevice));
+  const size_t bytes = koff + sizeof(AttnTile) * kt.size();
+  if (bytes) {
+    PinnedRing& ring = op_staging();
+    PinnedRing::Slot* slot = nullptr;
+    OP_TRY(ring.acquire(bytes, &slot));
+    char* h = (char*)slot->p;
+    if (!qt.empty()) memcpy(h, qt.data(), sizeof(AttnTile) * qt.size());
+    if (!kt.empty()) memcpy(h + koff, kt.data(), sizeof(AttnTile) * kt.size());
+    OP_TRY(hipMemcpyAsync(w, h, bytes, hipMemcpyHostToDevice, stream));
+    OP_TRY(ring.commit(slot, stream));
+  }
   a.q_tiles = (const AttnTile*)w;
   a.kv_tiles = (const AttnTile*)(w + koff);
   a.n_q_tiles = (int)qt.size();
@@ -179,7 +197,7 @@ mllm_status_t mllm_op_attn_fwd(const void* q, const void* k, const void* v, void
   a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
   a.q_stride = q_stride; a.kv_stride = kv_stride; a.o_stride = o_stride;
   a.total_tokens = pack->total_tokens; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
-  if ((r = upload_tiles(pack, workspace, a)) != MLLM_OK) return r;
+  if ((r = upload_tiles(pack, workspace, a, (hipStream_t)hip_stream)) != MLLM_OK) return r;
   OP_TRY(launch_attn_fwd(a, (hipStream_t)hip_stream));
   return MLLM_OK;
 }
@@ -198,7 +216,7 @@ mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, cons
   a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta;
   a.q_stride = q_stride; a.kv_stride = kv_stride; a.o_stride = o_stride;
   a.total_tokens = pack->total_tokens; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
-  if ((r = upload_tiles(pack, workspace, a)) != MLLM_OK) return r;
+  if ((r = upload_tiles(pack, workspace, a, (hipStream_t)hip_stream)) != MLLM_OK) return r;
   OP_TRY(launch_attn_bwd(a, (hipStream_t)hip_stream));
   return MLLM_OK;
 }

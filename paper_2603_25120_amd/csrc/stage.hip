@@ -16,6 +16,7 @@
 
 #include "../../include/mllm_stage.h"
 #include "kernels.h"
+#include "pinned_ring.h"
 
 using namespace mllm;
 
@@ -62,11 +63,9 @@ struct mllm_stage {
   std::vector<ParamInfo> params;
   std::vector<int> param_off;  // first parameter index of each layer
   int n_vit = 0, n_dec = 0, proj = -1;
-  // pinned host staging for the per-call metadata upload
-  void* pinned = nullptr;
-  size_t pinned_bytes = 0;
-  hipEvent_t upload_done = nullptr;
-  bool upload_pending = false;
+  // pinned host staging for the per-call metadata upload; sized by mllm_stage_sizes (hence
+  // mutable: that call takes a const handle), so that fwd / bwd neither allocate nor wait
+  mutable PinnedRing staging;
 };
 
 namespace {
@@ -380,19 +379,9 @@ mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, 
                           hipStream_t s) {
   const Meta& M = P.meta;
   if (M.bytes == 0) return MLLM_OK;
-  if (!st->upload_done) HIP_TRY(hipEventCreateWithFlags(&st->upload_done, hipEventDisableTiming));
-  if (st->upload_pending) {  // the previous call's copy must have left the staging buffer
-    HIP_TRY(hipEventSynchronize(st->upload_done));
-    st->upload_pending = false;
-  }
-  if (st->pinned_bytes < M.bytes) {
-    if (st->pinned) HIP_TRY(hipHostFree(st->pinned));
-    st->pinned = nullptr;
-    st->pinned_bytes = 0;
-    HIP_TRY(hipHostMalloc(&st->pinned, M.bytes * 2, hipHostMallocDefault));
-    st->pinned_bytes = M.bytes * 2;
-  }
-  char* h = (char*)st->pinned;
+  PinnedRing::Slot* slot = nullptr;
+  HIP_TRY(st->staging.acquire(M.bytes, &slot));
+  char* h = (char*)slot->p;
   memset(h, 0, M.bytes);
   if (st->n_vit > 0) {
     build_tiles(b->img, ATTN_FWD_Q_TILE, false, (AttnTile*)(h + M.img_q_tiles));
@@ -422,8 +411,7 @@ mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, 
     }
   }
   HIP_TRY(hipMemcpyAsync(workspace, h, M.bytes, hipMemcpyHostToDevice, s));
-  HIP_TRY(hipEventRecord(st->upload_done, s));
-  st->upload_pending = true;
+  HIP_TRY(st->staging.commit(slot, s));
   return MLLM_OK;
 }
 
@@ -729,9 +717,7 @@ mllm_status_t mllm_stage_create(const mllm_stage_desc_t* desc, mllm_stage_t** ou
 
 void mllm_stage_destroy(mllm_stage_t* st) {
   if (!st) return;
-  if (st->upload_pending) (void)hipEventSynchronize(st->upload_done);
-  if (st->upload_done) (void)hipEventDestroy(st->upload_done);
-  if (st->pinned) (void)hipHostFree(st->pinned);
+  st->staging.destroy();
   delete st;
 }
 
@@ -754,6 +740,10 @@ mllm_status_t mllm_stage_sizes(const mllm_stage_t* st, const mllm_batch_t* b, si
   if (r != MLLM_OK) return r;
   Plan P = make_plan(st, b);
   if ((r = check_plan(P)) != MLLM_OK) return r;
+  // The staging ring grows here, where the caller sizes its own buffers, so that fwd / bwd find it
+  // large enough.  Best effort: a failure (no device in this process) is left to fwd / bwd, which
+  // grow the slot they take if they must and report the error then.
+  if (P.meta.bytes && st->staging.reserve(P.meta.bytes) != hipSuccess) (void)hipGetLastError();
   if (saved_bytes) *saved_bytes = P.saved_bytes;
   if (workspace_bytes) *workspace_bytes = P.workspace_bytes;
   return MLLM_OK;
