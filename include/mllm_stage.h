@@ -291,6 +291,19 @@ size_t mllm_op_colsum_partial_bytes(int64_t t, int64_t n);
 mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* partial, int64_t t,
                              int64_t n, void* hip_stream);
 
+/* mllm_op_colsum for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * result bit for bit; the partial sums live in a static device array of the library
+ * (mllm_op_colsum_static_max_bytes() = 8 MiB per GPU, held until the process ends) instead of a
+ * `partial` argument.  The call allocates nothing (the array's device address is looked up once
+ * per device, on the first call there).  MLLM_ERR_WORKSPACE when
+ * mllm_op_colsum_partial_bytes(t, n) exceeds the array (n <= 4096 always fits).  All calls on one
+ * GPU share the array: calls that overlap on one GPU (different streams) race; calls on one
+ * stream are ordered and safe. */
+size_t mllm_op_colsum_static_max_bytes(void);
+mllm_status_t mllm_op_colsum_static(const void* x, float* out, int accumulate, int64_t t, int64_t n,
+                                    void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Online microbatch scheduler (host only, no GPU work; Online Microbatch Scheduler, "Problem
  * Formulation" and "Scheduling Optimization").  Item i of a global batch has an encoder-stage

@@ -24,7 +24,7 @@ EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", 
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
            "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
-           "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_profile_begin",
+           "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_op_colsum_static_max_bytes", "mllm_op_colsum_static", "mllm_profile_begin",
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
            "mllm_find_combs", "mllm_evaluate_parallelism", "mllm_optimize_parallelism"]
 
@@ -115,6 +115,9 @@ def lib() -> C.CDLL:
     L.mllm_op_colsum_partial_bytes.argtypes = [i64, i64]
     L.mllm_op_colsum_partial_bytes.restype = sz
     L.mllm_op_colsum.argtypes = [vp, vp, C.c_int, vp, i64, i64, vp]
+    L.mllm_op_colsum_static_max_bytes.argtypes = []
+    L.mllm_op_colsum_static_max_bytes.restype = sz
+    L.mllm_op_colsum_static.argtypes = [vp, vp, C.c_int, i64, i64, vp]
     L.mllm_profile_begin.argtypes = [i32]
     L.mllm_profile_end.argtypes = [C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
     dp, ip = C.POINTER(C.c_double), C.POINTER(i32)
@@ -330,6 +333,14 @@ def mllm_op_colsum_partial_bytes(t: int, n: int) -> int:
 
 def mllm_op_colsum(x, out, accumulate, partial, t, n, stream=None) -> None:
     _check(lib().mllm_op_colsum(_ptr(x), _ptr(out), int(accumulate), _ptr(partial), t, n, _stream(stream)))
+
+
+def mllm_op_colsum_static_max_bytes() -> int:
+    return int(lib().mllm_op_colsum_static_max_bytes())
+
+
+def mllm_op_colsum_static(x, out, accumulate, t, n, stream=None) -> None:
+    _check(lib().mllm_op_colsum_static(_ptr(x), _ptr(out), int(accumulate), t, n, _stream(stream)))
 
 
 def mllm_profile_begin(max_records: int) -> None:

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -125,6 +126,35 @@ mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a, hipSt
   return MLLM_OK;
 }
 
+}  // namespace
+
+// Scratch of mllm_op_colsum_static, the entry point for callers that cannot allocate: the fp32
+// partial column sums that mllm_op_colsum takes as its `partial` argument live in this array
+// instead.  Every GPU the library runs on holds its own copy until the process ends.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];       // device address of `scratch` on each device, resolved on first use
+std::mutex g_scratch_mutex;
+
+// The array's name is only a host-side handle: its device address on the current device comes
+// from hipGetSymbolAddress, once per device.
+mllm_status_t static_scratch(void** out) {
+  int dev = -1;
+  OP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return op_fail(MLLM_ERR_UNSUPPORTED, "device index %d beyond %d", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    OP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return op_fail(MLLM_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MLLM_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -277,6 +307,23 @@ mllm_status_t mllm_op_colsum(const void* x, float* out, int accumulate, float* p
   if (!x || !out || !partial) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
   if (t < 0 || n <= 0 || n % 8) return op_fail(MLLM_ERR_SHAPE, "n must be a positive multiple of 8");
   OP_TRY(launch_colsum(x, n, out, accumulate, partial, t, n, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+size_t mllm_op_colsum_static_max_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+mllm_status_t mllm_op_colsum_static(const void* x, float* out, int accumulate, int64_t t, int64_t n, void* hip_stream) {
+  if (!x || !out) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (t < 0 || n <= 0 || n % 8) return op_fail(MLLM_ERR_SHAPE, "n must be a positive multiple of 8");
+  const size_t need = mllm_op_colsum_partial_bytes(t, n);
+  if (need > STATIC_SCRATCH_BYTES)
+    return op_fail(MLLM_ERR_WORKSPACE, "a [%lld, %lld] column sum needs %zu bytes of partial sums, the static scratch holds %zu",
+                   (long long)t, (long long)n, need, STATIC_SCRATCH_BYTES);
+  void* partial = nullptr;
+  mllm_status_t r = static_scratch(&partial);
+  if (r != MLLM_OK) return r;
+  // every partial sum the second kernel reads is written by the first: nothing to clear
+  OP_TRY(launch_colsum(x, n, out, accumulate, (float*)partial, t, n, (hipStream_t)hip_stream));
   return MLLM_OK;
 }
 
