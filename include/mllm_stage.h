@@ -257,6 +257,19 @@ mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, cons
                                int64_t kv_stride, int64_t o_stride, void* workspace,
                                size_t workspace_bytes, void* hip_stream);
 
+/* The same with the gradient of the rotary positions folded into the write-out: dq and dk leave
+ * rotated by the negative angle of their row's position inside its segment, i.e. they are the
+ * gradients of the q and k that entered the rotation (what mllm_op_attn_bwd followed by
+ * mllm_op_rope with inverse != 0 computes, with one rounding instead of two).  rope_table: device
+ * fp32 [positions, head_dim] from mllm_op_rope_table, at least max_seqlen positions; NULL: no
+ * rotation (identical to mllm_op_attn_bwd). */
+mllm_status_t mllm_op_attn_bwd_rope(const void* q, const void* k, const void* v, const void* o,
+                                    const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                                    float* delta, const mllm_pack_t* pack, int32_t n_q_heads,
+                                    int32_t n_kv_heads, int32_t head_dim, int64_t q_stride,
+                                    int64_t kv_stride, int64_t o_stride, const float* rope_table,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Row normalisation.  kind 0: LayerNorm (gamma, beta), 1: RMSNorm (gamma).  x, y bf16 [T, d];
  * stats fp32 [2, T]: row 0 = 1/sqrt(var+eps) (or 1/sqrt(mean sq+eps)), row 1 = mean (LayerNorm). */
 mllm_status_t mllm_op_norm_fwd(int kind, const void* x, const void* gamma, const void* beta,
@@ -276,6 +289,24 @@ mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const vo
 mllm_status_t mllm_op_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride,
                            int64_t col0, int32_t n_heads, int32_t head_dim, float rope_base,
                            int inverse, void* hip_stream);
+
+/* Table of rotary factors for the kernels that rotate inside another operation: row p (p <
+ * n_pos) holds cos(p * rope_base^(-2i/head_dim)) for i < head_dim/2, then the sines; device fp32
+ * [n_pos, head_dim].  Angles and their sines are formed in fp64. */
+mllm_status_t mllm_op_rope_table(float* table, int64_t n_pos, int32_t head_dim, float rope_base,
+                                 void* hip_stream);
+
+/* The decoder's QKV projection with the rotary positions in its epilogue (the stage takes this
+ * form whenever it applies): y [M, N] = x [M, K] . w [K, N] (+ bias [N]), all bf16 row-major; the
+ * leading rope_cols columns of y (a multiple of 128) are heads of head_dim (64 or 128) whose
+ * half-split pairs (i, i + head_dim/2) are rotated, on the fp32 accumulators and after the bias, by
+ * the angles of row pos[row] of rope_table (pos: device int32 [M], every entry below the table's
+ * n_pos).  Applies with K a multiple of 64 and at least 200 output tiles of 256 x 256; otherwise
+ * MLLM_ERR_UNSUPPORTED (mllm_op_gemm followed by mllm_op_rope computes the same with one more
+ * rounding). */
+mllm_status_t mllm_op_gemm_rope(const void* x, const void* w, const void* bias, void* y, int64_t m,
+                                int64_t n, int64_t k, const int32_t* pos, const float* rope_table,
+                                int64_t rope_cols, int32_t head_dim, void* hip_stream);
 
 /* Activations.  act GELU_*: a = GELU(h), h [T, f].  act SWIGLU: a = SiLU(g) * u with
  * gu = [g | u] of shape [T, 2f].  Backward writes dh [T, f] or dgu [T, 2f] from da and the

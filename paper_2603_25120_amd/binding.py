@@ -23,7 +23,7 @@ STATUS_NAMES = ["MLLM_OK", "MLLM_ERR_NULL", "MLLM_ERR_DESC", "MLLM_ERR_SHAPE", "
 EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", "mllm_stage_param_info",
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
            "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
-           "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_act_fwd",
+           "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_rope_table", "mllm_op_gemm_rope", "mllm_op_attn_bwd_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_op_colsum_static_max_bytes", "mllm_op_colsum_static", "mllm_profile_begin",
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
            "mllm_find_combs", "mllm_evaluate_parallelism", "mllm_optimize_parallelism"]
@@ -110,6 +110,9 @@ def lib() -> C.CDLL:
     L.mllm_op_norm_bwd_partial_bytes.restype = sz
     L.mllm_op_norm_bwd.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, i64, i64, vp]
     L.mllm_op_rope.argtypes = [vp, vp, i64, i64, i64, i32, i32, C.c_float, C.c_int, vp]
+    L.mllm_op_rope_table.argtypes = [vp, i64, i32, C.c_float, vp]
+    L.mllm_op_gemm_rope.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, i32, vp]
+    L.mllm_op_attn_bwd_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, vp, sz, vp]
     L.mllm_op_act_fwd.argtypes = [C.c_int, vp, vp, i64, i64, vp]
     L.mllm_op_act_bwd.argtypes = [C.c_int, vp, vp, vp, i64, i64, vp]
     L.mllm_op_colsum_partial_bytes.argtypes = [i64, i64]
@@ -317,6 +320,24 @@ def mllm_op_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumul
 def mllm_op_rope(qk, pos, t, row_stride, col0, n_heads, head_dim, rope_base, inverse=0, stream=None) -> None:
     _check(lib().mllm_op_rope(_ptr(qk), _ptr(pos), t, row_stride, col0, n_heads, head_dim, rope_base,
                               int(inverse), _stream(stream)))
+
+
+def mllm_op_rope_table(table, n_pos, head_dim, rope_base, stream=None) -> None:
+    _check(lib().mllm_op_rope_table(_ptr(table), n_pos, head_dim, rope_base, _stream(stream)))
+
+
+def mllm_op_gemm_rope(x, w, bias, y, m, n, k, pos, rope_table, rope_cols, head_dim, stream=None) -> None:
+    _check(lib().mllm_op_gemm_rope(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), m, n, k, _ptr(pos), _ptr(rope_table),
+                                   rope_cols, head_dim, _stream(stream)))
+
+
+def mllm_op_attn_bwd_rope(q, k, v, o, lse, d_o, dq, dk, dv, delta, pack, n_q_heads, n_kv_heads, head_dim, q_stride,
+                          kv_stride, o_stride, rope_table, workspace, stream=None) -> None:
+    pk = _PackKeep(pack)
+    _check(lib().mllm_op_attn_bwd_rope(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk),
+                                       _ptr(dv), _ptr(delta), C.byref(pk.c), n_q_heads, n_kv_heads, head_dim,
+                                       q_stride, kv_stride, o_stride, _ptr(rope_table), _ptr(workspace),
+                                       _nbytes(workspace), _stream(stream)))
 
 
 def mllm_op_act_fwd(act, pre, a, t, f, stream=None) -> None:

@@ -63,7 +63,34 @@ struct AttnParams {
   int32_t T, Hq, Hkv;
   const AttnTile* tiles;
   float scale_log2e, scale;
+  const float* rope_table;   // backward: dq, dk are rotated back by the rotary angle of their row (null: not)
 };
+
+// Gradient of the rotary positions on an accumulator of ND = HD/32 blocks whose lane owns row `pos`
+// of its segment: the pair (c, c + HD/2) sits in blocks (d, d + ND/2) of the same lane.  Forward was
+// y1 = x1 cos - x2 sin, y2 = x2 cos + x1 sin, so dx1 = dy1 cos + dy2 sin, dx2 = dy2 cos - dy1 sin.
+// `scale` multiplies the result.
+template <int HD>
+__device__ __forceinline__ void rope_unrotate(f32x16 (&acc)[HD / 32], const float* table, int pos, int h, float scale) {
+  constexpr int ND = HD / 32, HALF = HD / 2;
+  const float* trow = table + (int64_t)pos * HD;
+#pragma unroll
+  for (int d = 0; d < ND / 2; d++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      const int f0 = 32 * d + 8 * g4 + 4 * h;
+      const float4 c = *reinterpret_cast<const float4*>(trow + f0);
+      const float4 sn = *reinterpret_cast<const float4*>(trow + HALF + f0);
+      const float cs[4] = {c.x * scale, c.y * scale, c.z * scale, c.w * scale};
+      const float ss[4] = {sn.x * scale, sn.y * scale, sn.z * scale, sn.w * scale};
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const float y1 = acc[d][4 * g4 + e], y2 = acc[d + ND / 2][4 * g4 + e];
+        acc[d][4 * g4 + e] = y1 * cs[e] + y2 * ss[e];
+        acc[d + ND / 2][4 * g4 + e] = y2 * cs[e] - y1 * ss[e];
+      }
+    }
+}
 
 // Natural-layout operand: row (r0 + lane%32), contraction values 16c + 8*(lane/32) .. +7.
 template <int HD>
@@ -436,14 +463,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
   }
   __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);   // the last enqueued tile (zeros) has landed
   if (!qok) return;
+  float out_scale = p.scale;
+  if (p.rope_table) {   // the scale rides on the rotation's factors
+    rope_unrotate<HD>(dqacc, p.rope_table, qrow, h, p.scale);
+    out_scale = 1.f;
+  }
   bf16_t* dqp = p.dq + grow * p.q_stride + head * HD;
 #pragma unroll
   for (int d = 0; d < ND; d++)
 #pragma unroll
     for (int g4 = 0; g4 < 4; g4++) {
       uint2 w;
-      w.x = pack_bf16x2(dqacc[d][4 * g4] * p.scale, dqacc[d][4 * g4 + 1] * p.scale);
-      w.y = pack_bf16x2(dqacc[d][4 * g4 + 2] * p.scale, dqacc[d][4 * g4 + 3] * p.scale);
+      w.x = pack_bf16x2(dqacc[d][4 * g4] * out_scale, dqacc[d][4 * g4 + 1] * out_scale);
+      w.y = pack_bf16x2(dqacc[d][4 * g4 + 2] * out_scale, dqacc[d][4 * g4 + 3] * out_scale);
       *reinterpret_cast<uint2*>(dqp + 32 * d + 8 * g4 + 4 * h) = w;
     }
 }
@@ -631,6 +663,11 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
   // can be handed to another one
   __builtin_amdgcn_s_waitcnt(WAIT_VMCNT_0);
   if (!kok) return;
+  float out_scale = p.scale;
+  if (p.rope_table) {
+    rope_unrotate<HD>(dkacc, p.rope_table, krow, h, p.scale);
+    out_scale = 1.f;
+  }
   bf16_t* dkp = p.dk + gkrow * p.kv_stride + kvh * HD;
   bf16_t* dvp = p.dv + gkrow * p.kv_stride + kvh * HD;
 #pragma unroll
@@ -638,8 +675,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
 #pragma unroll
     for (int g4 = 0; g4 < 4; g4++) {
       uint2 w;
-      w.x = pack_bf16x2(dkacc[d][4 * g4] * p.scale, dkacc[d][4 * g4 + 1] * p.scale);
-      w.y = pack_bf16x2(dkacc[d][4 * g4 + 2] * p.scale, dkacc[d][4 * g4 + 3] * p.scale);
+      w.x = pack_bf16x2(dkacc[d][4 * g4] * out_scale, dkacc[d][4 * g4 + 1] * out_scale);
+      w.y = pack_bf16x2(dkacc[d][4 * g4 + 2] * out_scale, dkacc[d][4 * g4 + 3] * out_scale);
       *reinterpret_cast<uint2*>(dkp + 32 * d + 8 * g4 + 4 * h) = w;
       w.x = pack_bf16x2(dvacc[d][4 * g4], dvacc[d][4 * g4 + 1]);
       w.y = pack_bf16x2(dvacc[d][4 * g4 + 2], dvacc[d][4 * g4 + 3]);
@@ -657,6 +694,7 @@ AttnParams make_params(const AttnArgs& a) {
   p.tiles = nullptr;
   p.scale = 1.0f / sqrtf((float)a.head_dim);
   p.scale_log2e = p.scale * LOG2E;
+  p.rope_table = a.rope_table;
   return p;
 }
 

@@ -265,6 +265,22 @@ __global__ void rope_kernel(bf16_t* __restrict__ qk, const int32_t* __restrict__
   }
 }
 
+// Table of the rotary angles for the kernels that rotate in their own epilogue: row `pos` holds
+// cos(pos * base^(-2i/hd)) for i < hd/2, then the sines (fp32; angles and sincos in fp64, as in
+// rope_kernel, so both forms of the rotation use the same factors).
+__global__ void rope_table_kernel(float* __restrict__ table, int64_t n_pos, int hd, double log2_base) {
+  const int half = hd >> 1;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= n_pos * half) return;
+  const int64_t pos = gid / half;
+  const int i = (int)(gid % half);
+  const double inv = exp2(-2.0 * (double)i / (double)hd * log2_base);
+  double sn, cs;
+  sincos((double)pos * inv, &sn, &cs);
+  table[pos * hd + i] = (float)cs;
+  table[pos * hd + half + i] = (float)sn;
+}
+
 // ---------------------------------------------------------------------------------------------
 // activations
 // ---------------------------------------------------------------------------------------------
@@ -607,6 +623,16 @@ hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stri
   ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)t * (double)n_heads * (double)head_dim, s);
   hipLaunchKernelGGL(rope_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, (bf16_t*)qk, pos, t,
                      row_stride, col0, (int)n_heads, (int)head_dim, log2((double)rope_base), inverse);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(float* table, int64_t n_pos, int32_t head_dim, float rope_base, hipStream_t s) {
+  if (n_pos == 0) return hipSuccess;
+  if (head_dim % 16 != 0) return hipErrorInvalidValue;
+  const int64_t n = n_pos * (head_dim / 2);
+  ProfScope prof(PROF_ELEMENTWISE, 4.0 * (double)n_pos * (double)head_dim, s);
+  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, table, n_pos, (int)head_dim,
+                     log2((double)rope_base));
   return hipGetLastError();
 }
 

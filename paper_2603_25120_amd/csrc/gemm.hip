@@ -321,7 +321,8 @@ __device__ __forceinline__ KAdvance k_advance(uint32_t t, uint32_t last_tile, ui
   return {0u, t * kstep};
 }
 
-// EPI: 0 plain epilogue; 1 SwiGLU forward fused; 2 SwiGLU gradient fused.
+// EPI: 0 plain epilogue; 1 SwiGLU forward fused; 2 SwiGLU gradient fused; 3 / 4 rotary positions
+// fused for heads of 128 / 64.
 template <int TM, bool A_T, bool B_T, bool OUT_F32, bool RAGGED_K, int EPI = 0>
 __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   constexpr bool SWIGLU = EPI == 1;
@@ -334,6 +335,7 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   // SWIGLU: C = [gate | up]; the epilogue also writes silu(gate) * up (forward layout only).
   static_assert(!SWIGLU || (TM == 4 && !A_T && B_T && !OUT_F32), "fused SwiGLU: Y = X.W with W stored [K, N], bf16");
   static_assert(EPI != 2 || (TM == 4 && !A_T && !B_T && !OUT_F32), "fused SwiGLU gradient: dA = dY.W^T with W stored [N, K], bf16");
+  static_assert((EPI != 3 && EPI != 4) || (TM == 4 && !A_T && B_T && !OUT_F32), "fused rotary positions: Y = X.W with W stored [K, N], bf16");
   constexpr int BM = 64 * TM, BN = 256, WM = 32 * TM, WN = 128, NT = 256, TN = 4;
   constexpr int NA = 2 * TM;          // A vectors per thread and k-tile (B: 8)
   constexpr int NU = TM + 4;          // fragment units per k-step
@@ -517,9 +519,13 @@ __device__ __forceinline__ void gemm4_tile(GemmParams p) {
   else if constexpr (EPI == 2)
     store_tile_swiglu_bwd<TM>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE, m0 + wm * WM,
                               n0 + wn * WN, lane);
-  else
+  else {
+    if constexpr (EPI == 3 || EPI == 4) {
+      if (rope_rotate_tile<TM, EPI == 3 ? 128 : 64>(p, acc, m0 + wm * WM, n0 + wn * WN, lane)) p.bias = nullptr;
+    }
     store_tile<TM, TN, OUT_F32, true>(p, acc, reinterpret_cast<float*>(Bs) + wave * 32 * ST_STRIDE,
                                       m0 + wm * WM, n0 + wn * WN, lane);
+  }
 }
 
 template <int TM, bool A_T, bool B_T, bool OUT_F32>
@@ -539,6 +545,12 @@ __global__ __launch_bounds__(256) void gemm4_swiglu_kernel(GemmParams p) {
 // dA = dY.W_d^T kept in registers; [d gate | d up] written (the decoder's MLP down-projection, backward).
 __global__ __launch_bounds__(256) void gemm4_swiglu_bwd_kernel(GemmParams p) {
   gemm4_tile<4, false, false, false, false, 2>(p);
+}
+
+// Y = X.W (+ b) with the rotary positions applied to the q and k heads in the epilogue.
+template <int HD>
+__global__ __launch_bounds__(256) void gemm4_rope_kernel(GemmParams p) {
+  gemm4_tile<4, false, true, false, false, HD == 128 ? 3 : 4>(p);
 }
 
 // The four-wavefront kernel takes a problem tiled 256 x 256 when K is a positive multiple of 64,
@@ -573,6 +585,11 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int splits = 1) {
     }
     if (g.swiglu_dpre) {
       hipLaunchKernelGGL(gemm4_swiglu_bwd_kernel, grid, block4, 0, s, p);
+      return hipGetLastError();
+    }
+    if (g.rope_table) {   // launch_gemm has checked gemm_rope_fusable()
+      if (g.rope_head_dim == 128) hipLaunchKernelGGL(gemm4_rope_kernel<128>, grid, block4, 0, s, p);
+      else hipLaunchKernelGGL(gemm4_rope_kernel<64>, grid, block4, 0, s, p);
       return hipGetLastError();
     }
     const bool rows192 = takes_rows192(g, splits);
@@ -681,8 +698,17 @@ bool gemm_swiglu_bwd_fusable(int64_t m, int64_t n, int64_t k) {
   return big_tiles >= 200 && n % 8 == 0 && k >= BK && k % BK == 0;
 }
 
+bool gemm_rope_fusable(int64_t m, int64_t n, int64_t k, int32_t head_dim) {
+  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
+  return big_tiles >= 200 && (head_dim == 64 || head_dim == 128) && n % 8 == 0 && k >= BK && k % BK == 0;
+}
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  if (g.rope_table && (!g.rope_pos || !gemm_rope_fusable(g.m, g.n, g.k, g.rope_head_dim) || g.a_layout != 0 ||
+                       g.b_layout != 0 || g.out_fp32 || g.residual || g.swiglu_act || g.swiglu_dpre || g.ldc != g.n ||
+                       g.rope_cols % 128 != 0 || g.rope_cols > g.n))
+    return hipErrorInvalidValue;
   if ((g.swiglu_dpre || g.swiglu_pre) &&
       (!g.swiglu_dpre || !g.swiglu_pre || g.swiglu_act || !gemm_swiglu_bwd_fusable(g.m, g.n, g.k) || g.a_layout != 0 ||
        g.b_layout != 1 || g.out_fp32 || g.bias || g.residual || g.ldc != 2 * g.n))
@@ -702,7 +728,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
                      g.splitk_ws_bytes >= (size_t)sp.splits * g.m * g.n * 4;
   const bool large = big_tiles >= 200 || (split && sp.big_tile);
   // timing classes: the three layouts of the 256x256 kernel, its 192-row form, and the 128x128 kernel
-  const int cls = !large ? PROF_GEMM_SMALL : (!split && !g.swiglu_act && !g.swiglu_dpre && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
+  const int cls = !large ? PROF_GEMM_SMALL : (!split && !g.swiglu_act && !g.swiglu_dpre && !g.rope_table && takes_rows192(g, 1)) ? PROF_GEMM_ROWS192
                   : g.a_layout ? PROF_GEMM_DW : (g.b_layout ? PROF_GEMM_DX : PROF_GEMM_FWD);
   const double flops = 2.0 * (double)g.m * (double)g.n * (double)g.k;
   // 256x256 tiles (8 wavefronts of 128x64) once they fill the chip; smaller problems keep

@@ -32,6 +32,9 @@ struct GemmParams {
   bf16_t* act;              // fused SwiGLU: silu(gate) * up, [M, N / 2]
   const bf16_t* pre;        // fused SwiGLU gradient: [gate | up], [M, 2 N]
   bf16_t* dpre;             //                        [d gate | d up], [M, 2 N]
+  const float* rope_table;  // fused rotary positions: [positions, head_dim] fp32, cos then sin
+  const int32_t* rope_pos;  //                         position of every row of C
+  int64_t rope_cols;        //                         leading columns of C that are rotated heads
 };
 
 inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
@@ -49,6 +52,9 @@ inline GemmParams make_gemm_params(const GemmArgs& g, int bm, int bn) {
   p.act = (bf16_t*)g.swiglu_act;
   p.pre = (const bf16_t*)g.swiglu_pre;
   p.dpre = (bf16_t*)g.swiglu_dpre;
+  p.rope_table = g.rope_table;
+  p.rope_pos = g.rope_pos;
+  p.rope_cols = g.rope_cols;
   return p;
 }
 
@@ -184,6 +190,60 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
   };
   if (rows_left >= 32 * TM && col0 + WN <= p.N) emit(std::true_type{});
   else emit(std::false_type{});
+}
+
+// Rotary positions on a wavefront's 32*TM x 128 sub-tile while it is still in the accumulators
+// (rows from row0, columns from col0, a multiple of 128, so the sub-tile holds whole heads of HD =
+// 128 or 64).  A lane owns row lane%32 of every band, so the row's position and its angles are the
+// lane's own, and the half-split partner of column c, c + HD/2, lies HD/64 accumulator blocks
+// further in the same lane: the rotation needs no exchange.  With a bias the rotation applies to
+// x.W + b, so the bias is added here (the caller then stores without it).  Sub-tiles past
+// rope_cols (the v columns) are left alone; the branch is wavefront-uniform.
+template <int TM, int HD>
+__device__ __forceinline__ bool rope_rotate_tile(const GemmParams& p, f32x16 (&acc)[TM][4], int64_t row0,
+                                                 int64_t col0, int lane) {
+  static_assert(HD == 128 || HD == 64, "heads of 64 or 128");
+  if (col0 >= p.rope_cols) return false;
+  constexpr int HALF = HD / 2, STEP = HD / 64;      // partner block = block + STEP
+  const int h = lane >> 5, cl = lane & 31;
+  if (p.bias) {
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++) {
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + col0 + 32 * j + 8 * g4 + 4 * h);
+        const float b0 = bf16lo(bb.x), b1 = bf16hi(bb.x), b2 = bf16lo(bb.y), b3 = bf16hi(bb.y);
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          acc[i][j][4 * g4] += b0; acc[i][j][4 * g4 + 1] += b1; acc[i][j][4 * g4 + 2] += b2; acc[i][j][4 * g4 + 3] += b3;
+        }
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int64_t row = row0 + 32 * i + cl;
+    const int pos = row < p.M ? p.rope_pos[row] : 0;
+    const float* trow = p.rope_table + (int64_t)pos * HD;
+#pragma unroll
+    for (int jj = 0; jj < 2; jj++) {
+      // HD = 128: blocks (0, 2) and (1, 3), frequencies 32 jj + ...; HD = 64: blocks (0, 1) and (2, 3), two heads
+      const int j1 = HD == 128 ? jj : 2 * jj, j2 = j1 + STEP;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++) {
+        const int f0 = (HD == 128 ? 32 * jj : 0) + 8 * g4 + 4 * h;
+        const float4 c = *reinterpret_cast<const float4*>(trow + f0);
+        const float4 sn = *reinterpret_cast<const float4*>(trow + HALF + f0);
+        const float cs[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const float x1 = acc[i][j1][4 * g4 + e], x2 = acc[i][j2][4 * g4 + e];
+          acc[i][j1][4 * g4 + e] = x1 * cs[e] - x2 * ss[e];
+          acc[i][j2][4 * g4 + e] = x2 * cs[e] + x1 * ss[e];
+        }
+      }
+    }
+  }
+  return true;
 }
 
 // Epilogue of the fused SwiGLU product.  The wavefront's 32*TM x 128 sub-tile holds 64 gate

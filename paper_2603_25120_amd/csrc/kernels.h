@@ -29,7 +29,18 @@ struct GemmArgs {
   // ([M, 2N] bf16) receives [d gate | d up].  C is unused.  Only where gemm_swiglu_bwd_fusable().
   const void* swiglu_pre = nullptr;
   void* swiglu_dpre = nullptr;
+  // Rotary positions fused into the epilogue of a forward product Y = X.W (+ bias): the leading
+  // rope_cols columns of Y are heads of rope_head_dim (64 or 128) whose half-split pairs are rotated,
+  // on the fp32 accumulators, by the angles of row rope_pos[row] of rope_table (launch_rope_table).
+  // Only where gemm_rope_fusable().
+  const float* rope_table = nullptr;
+  const int32_t* rope_pos = nullptr;   // device int32 [M]
+  int64_t rope_cols = 0;
+  int32_t rope_head_dim = 0;
 };
+// Whether launch_gemm can rotate the q and k columns of a forward product in its epilogue (large-tile
+// kernel, K a multiple of 64, heads of 64 or 128 so that a wavefront's 128 columns hold whole heads).
+bool gemm_rope_fusable(int64_t m, int64_t n, int64_t k, int32_t head_dim);
 bool gemm_swiglu_bwd_fusable(int64_t m, int64_t n, int64_t k);
 // Whether launch_gemm can write the SwiGLU activation of a forward product X[M,K].W[K,N] along
 // with it (large-tile kernel, N/2 a multiple of 128, K a multiple of 64).
@@ -57,6 +68,10 @@ struct AttnArgs {
   int32_t total_tokens, n_q_heads, n_kv_heads, head_dim;
   const AttnTile* q_tiles; int32_t n_q_tiles;     // device
   const AttnTile* kv_tiles; int32_t n_kv_tiles;   // device
+  // backward only: when set (launch_rope_table, head_dim floats per position, positions counted from
+  // the start of each segment), dq and dk leave rotated by the negative rotary angle of their row,
+  // i.e. as gradients of the q and k that entered the rotation
+  const float* rope_table;
   double fwd_flops;                               // algorithmic forward FLOPs of this call (for timing reports)
 };
 constexpr int ATTN_FWD_Q_TILE = 128;   // query rows per workgroup, forward and dQ pass
@@ -76,6 +91,8 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
 hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride, int64_t col0,
                        int32_t n_heads, int32_t head_dim, float rope_base, int inverse,
                        hipStream_t s);
+// table [n_pos, head_dim] fp32: cos then sin of pos * rope_base^(-2i/head_dim), i < head_dim / 2.
+hipError_t launch_rope_table(float* table, int64_t n_pos, int32_t head_dim, float rope_base, hipStream_t s);
 hipError_t launch_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f, hipStream_t s);
 hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t,
                           int64_t f, hipStream_t s);

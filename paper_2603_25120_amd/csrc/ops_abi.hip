@@ -210,6 +210,32 @@ mllm_status_t mllm_op_gemm_swiglu_bwd(const void* dy, const void* w_d, const voi
   return MLLM_OK;
 }
 
+mllm_status_t mllm_op_rope_table(float* table, int64_t n_pos, int32_t head_dim, float rope_base, void* hip_stream) {
+  if (!table) return op_fail(MLLM_ERR_NULL, "table is NULL");
+  if (n_pos < 0 || head_dim <= 0 || head_dim % 16 || !(rope_base > 1.f)) return op_fail(MLLM_ERR_SHAPE, "bad rope table geometry");
+  OP_TRY(launch_rope_table(table, n_pos, head_dim, rope_base, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_gemm_rope(const void* x, const void* w, const void* bias, void* y, int64_t m, int64_t n,
+                                int64_t k, const int32_t* pos, const float* rope_table, int64_t rope_cols,
+                                int32_t head_dim, void* hip_stream) {
+  if (!x || !w || !y || !pos || !rope_table) return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (m < 0 || n <= 0 || k <= 0 || n % 8 || k % 8) return op_fail(MLLM_ERR_SHAPE, "sizes must be positive, n and k multiples of 8");
+  if (rope_cols < 0 || rope_cols > n || rope_cols % 128 || (head_dim != 64 && head_dim != 128))
+    return op_fail(MLLM_ERR_SHAPE, "rope_cols must be a multiple of 128 within n, head_dim 64 or 128");
+  if (!gemm_rope_fusable(m, n, k, head_dim))
+    return op_fail(MLLM_ERR_UNSUPPORTED, "the fused form needs k a multiple of 64 and at least 200 output tiles of 256 x 256");
+  GemmArgs g;
+  g.a = x; g.b = w; g.c = y; g.m = m; g.n = n; g.k = k; g.lda = k; g.ldb = n; g.ldc = n;
+  g.a_layout = 0; g.b_layout = 0; g.out_fp32 = 0; g.accumulate = 0;
+  g.bias = bias; g.residual = nullptr; g.ldres = 0;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
+  g.rope_table = rope_table; g.rope_pos = pos; g.rope_cols = rope_cols; g.rope_head_dim = head_dim;
+  OP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
 size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens) {
   const size_t max_tiles = (size_t)std::max(0, total_tokens) / 128 + (size_t)std::max(0, n_segments) + 1;
   return 2 * align_up(sizeof(AttnTile) * max_tiles);
@@ -238,12 +264,23 @@ mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, cons
                                int32_t n_kv_heads, int32_t head_dim, int64_t q_stride,
                                int64_t kv_stride, int64_t o_stride, void* workspace,
                                size_t workspace_bytes, void* hip_stream) {
+  return mllm_op_attn_bwd_rope(q, k, v, o, lse, d_o, dq, dk, dv, delta, pack, n_q_heads, n_kv_heads, head_dim, q_stride,
+                               kv_stride, o_stride, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+mllm_status_t mllm_op_attn_bwd_rope(const void* q, const void* k, const void* v, const void* o,
+                                    const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                                    float* delta, const mllm_pack_t* pack, int32_t n_q_heads,
+                                    int32_t n_kv_heads, int32_t head_dim, int64_t q_stride,
+                                    int64_t kv_stride, int64_t o_stride, const float* rope_table,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta) return op_fail(MLLM_ERR_NULL, "a tensor pointer is NULL");
   mllm_status_t r = check_attn(pack, n_q_heads, n_kv_heads, head_dim, q_stride, kv_stride, o_stride, workspace, workspace_bytes);
   if (r != MLLM_OK) return r;
   AttnArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
   a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta;
+  a.rope_table = rope_table;
   a.q_stride = q_stride; a.kv_stride = kv_stride; a.o_stride = o_stride;
   a.total_tokens = pack->total_tokens; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
   if ((r = upload_tiles(pack, workspace, a, (hipStream_t)hip_stream)) != MLLM_OK) return r;

@@ -209,6 +209,12 @@ struct Plan {
   size_t w_partial = 0;           // fp32 partial sums of norm / bias gradients
   size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0, w_split = 0;
   size_t w_qkn = 0;               // QK normalisation: gradient of the normalised q, k  [T, nq]
+  // Rotary-angle tables [longest sample, head_dim] fp32, one per distinct (rope_base, head_dim) of the
+  // decoder layers; rope_of[i] = index of layer i's table (-1: the layer has none).
+  struct RopeTable { float base; int32_t head_dim; size_t off; };
+  std::vector<RopeTable> rope_tables;
+  std::vector<int> rope_of;
+  int64_t longest_seq = 0;
   size_t split_bytes = 0;
   size_t workspace_bytes = 0;
   int64_t T_img = 0, T_seq = 0;
@@ -338,6 +344,23 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     split = std::max(split, gemm_splitk_ws_bytes(d, d, T));
     split = std::max(split, gemm_splitk_ws_bytes(d, nq, T));
   }
+  P.rope_of.assign(st->layers.size(), -1);
+  if (st->n_dec > 0) {
+    for (int sgm = 0; sgm < b->seq.n_segments; sgm++)
+      P.longest_seq = std::max<int64_t>(P.longest_seq, b->seq.cu_seqlens_host[sgm + 1] - b->seq.cu_seqlens_host[sgm]);
+    for (size_t i = 0; i < st->layers.size(); i++) {
+      const mllm_layer_desc_t& L = st->layers[i];
+      if (L.kind != MLLM_LAYER_DECODER) continue;
+      int found = -1;
+      for (size_t k = 0; k < P.rope_tables.size(); k++)
+        if (P.rope_tables[k].base == L.rope_base && P.rope_tables[k].head_dim == L.head_dim) found = (int)k;
+      if (found < 0) {
+        found = (int)P.rope_tables.size();
+        P.rope_tables.push_back({L.rope_base, L.head_dim, ws.take((size_t)std::max<int64_t>(P.longest_seq, 1) * L.head_dim * 4)});
+      }
+      P.rope_of[i] = found;
+    }
+  }
   P.split_bytes = split;
   P.w_split = ws.take(split);
   P.w_partial = ws.take(part);
@@ -431,6 +454,18 @@ hipError_t linear_fwd(const void* x, const void* w, void* y, int64_t T, int64_t 
                       const void* bias, const void* res, hipStream_t s) {
   return gemm(x, k, 0, w, n, 0, y, n, T, n, k, 0, 0, bias, res, n, s);
 }
+// Y[T,n] = X[T,k].W[k,n] (+bias) with the leading rope_cols columns (heads of head_dim) rotated by the
+// rotary angle of each row's position
+hipError_t linear_fwd_rope(const void* x, const void* w, void* y, int64_t T, int64_t k, int64_t n, const void* bias,
+                           const float* table, const int32_t* pos, int64_t rope_cols, int32_t head_dim, hipStream_t s) {
+  GemmArgs g;
+  g.splitk_ws = nullptr; g.splitk_ws_bytes = 0;
+  g.a = x; g.b = w; g.c = y; g.m = T; g.n = n; g.k = k; g.lda = k; g.ldb = n; g.ldc = n;
+  g.a_layout = 0; g.b_layout = 0; g.out_fp32 = 0; g.accumulate = 0;
+  g.bias = bias; g.residual = nullptr; g.ldres = 0;
+  g.rope_table = table; g.rope_pos = pos; g.rope_cols = rope_cols; g.rope_head_dim = head_dim;
+  return launch_gemm(g, s);
+}
 // [gate | up][T,2f] = X[T,k].W[k,2f] and act[T,f] = silu(gate) * up in the same pass
 hipError_t linear_fwd_swiglu(const void* x, const void* w, void* pre, void* act, int64_t T, int64_t k,
                              int64_t n, hipStream_t s) {
@@ -497,7 +532,8 @@ AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, con
 // one transformer layer, forward.  x -> y; everything backward needs goes to `saved`.
 // -------------------------------------------------------------------------------------------
 mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, const LayerSaved& S,
-                        char* saved, char* ws, const Plan& P, int64_t T, void* y, hipStream_t s) {
+                        char* saved, char* ws, const Plan& P, int64_t T, void* y, const float* rope_table,
+                        hipStream_t s) {
   const bool vit = L.kind == MLLM_LAYER_VIT;
   const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
   char* x = saved + S.x;
@@ -519,7 +555,14 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
   const int64_t q_cols = (int64_t)L.n_q_heads * L.head_dim, k_cols = (int64_t)L.n_kv_heads * L.head_dim;
 
   K_TRY(launch_norm_fwd(vit ? 0 : 1, x, g1, b1n, n1, (float*)(saved + S.stats1), T, d, d, L.norm_eps, s));
-  K_TRY(linear_fwd(n1, wqkv, qkv, T, d, nq, bqkv, nullptr, s));
+  // Rotary positions ride on the QKV projection's epilogue whenever that product takes the
+  // large-tile kernel and nothing sits between the projection and the rotation.
+  const bool rope_fused = !vit && !L.qk_norm && (q_cols + k_cols) % 128 == 0 && gemm_rope_fusable(T, nq, d, L.head_dim);
+  if (rope_fused)
+    K_TRY(linear_fwd_rope(n1, wqkv, qkv, T, d, nq, bqkv, rope_table, (const int32_t*)(ws + P.meta.pos), q_cols + k_cols,
+                          L.head_dim, s));
+  else
+    K_TRY(linear_fwd(n1, wqkv, qkv, T, d, nq, bqkv, nullptr, s));
   char* qk = qkv;
   if (L.qk_norm) {
     qk = saved + S.qkn;
@@ -527,7 +570,7 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
     K_TRY(launch_norm_fwd(1, qkv + q_cols * 2, prm[n_base + 1], nullptr, qk + q_cols * 2,
                           (float*)(saved + S.statsk), T, k_cols, nq, L.norm_eps, s));
   }
-  if (!vit)
+  if (!vit && !rope_fused)
     K_TRY(launch_rope(qk, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 0, s));
   AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit);
@@ -549,7 +592,8 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
 // dy -> dx (both bf16 [T,d]); parameter gradients into dprm (fp32).
 mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void* const* dprm,
                         int accumulate, const LayerSaved& S, const char* saved, char* ws,
-                        const Plan& P, int64_t T, const void* dy, void* dx, hipStream_t s) {
+                        const Plan& P, int64_t T, const void* dy, void* dx, const float* rope_table,
+                        hipStream_t s) {
   const bool vit = L.kind == MLLM_LAYER_VIT;
   const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
   const char* x = saved + S.x;
@@ -607,10 +651,8 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   a.dk = dqk + q_cols * 2;
   a.dv = we + (q_cols + k_cols) * 2;
   a.delta = (float*)(ws + P.w_delta);
+  a.rope_table = vit ? nullptr : rope_table;   // dq, dk leave the kernels rotated back (the rotation's gradient)
   K_TRY(launch_attn_bwd(a, s));
-  if (!vit)
-    K_TRY(launch_rope(dqk, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
-                      L.head_dim, L.rope_base, 1, s));
   if (L.qk_norm) {
     K_TRY(launch_norm_bwd(1, dqk, qkv, prm[n_base], (const float*)(saved + S.statsq), nullptr, we,
                           (float*)dprm[n_base], nullptr, accumulate, partial, T, q_cols, nq, s));
@@ -767,6 +809,8 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
   char* saved = (char*)saved_v;
   char* ws = (char*)workspace;
   if ((r = upload_meta(st, b, P, workspace, s)) != MLLM_OK) return r;
+  for (const Plan::RopeTable& t : P.rope_tables)
+    K_TRY(launch_rope_table((float*)(ws + t.off), P.longest_seq, t.head_dim, t.base, s));
 
   const int n = (int)st->layers.size();
   for (int i = 0; i < n; i++) {
@@ -803,7 +847,8 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
     const int64_t T = vit ? P.T_img : P.T_seq;
     if (i == 0) K_TRY(launch_copy(vit ? x_img : x_seq, saved + P.saved[i].x, (size_t)T * L.d_model * 2, s));
     void* out = last ? y : (void*)(saved + P.saved[i + 1].x);
-    if ((r = layer_fwd(L, prm, P.saved[i], saved, ws, P, T, out, s)) != MLLM_OK) return r;
+    const float* rope_table = P.rope_of[i] >= 0 ? (const float*)(ws + P.rope_tables[P.rope_of[i]].off) : nullptr;
+    if ((r = layer_fwd(L, prm, P.saved[i], saved, ws, P, T, out, rope_table, s)) != MLLM_OK) return r;
   }
   return MLLM_OK;
 }
@@ -825,6 +870,8 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
   const char* saved = (const char*)saved_v;
   char* ws = (char*)workspace;
   if ((r = upload_meta(st, b, P, workspace, s)) != MLLM_OK) return r;
+  for (const Plan::RopeTable& t : P.rope_tables)
+    K_TRY(launch_rope_table((float*)(ws + t.off), P.longest_seq, t.head_dim, t.base, s));
 
   const int n = (int)st->layers.size();
   const void* cur = dy;  // gradient w.r.t. the output of layer i
@@ -878,7 +925,8 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       void* want = vit ? dx_img : dx_seq;
       if (want) out = want;
     }
-    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, s)) != MLLM_OK) return r;
+    const float* rope_table = P.rope_of[i] >= 0 ? (const float*)(ws + P.rope_tables[P.rope_of[i]].off) : nullptr;
+    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, rope_table, s)) != MLLM_OK) return r;
     cur = out;
     flip ^= 1;
   }

@@ -85,6 +85,21 @@ def test_decoder_layer_with_only_the_gradient_epilogue_fused(B):
         st.close()
 
 
+def test_decoder_layer_rotary_epilogue_heads_of_64_with_qkv_bias(B):
+    """A narrow decoder layer (d = 512, 8 / 2 heads of 64, QKV bias) on 17200 tokens: its QKV projection has
+    204 tiles of 256 x 256 and takes the form with the rotary positions in the epilogue (two heads per
+    wavefront, bias added before the rotation); every output and gradient."""
+    layers = [W.decoder_layer(512, 8, 2, 64, 1024, 10000.0, qkv_bias=1)]
+    batch = W.Batch(None, W.make_pack([3000, 5000, 1, 9199], W.MASK_CAUSAL), None, [])
+    assert batch.seq.total_tokens == 17200
+    wl = W.make_workload("dec_rope64", layers, batch, 917)
+    st = GpuStage(B, layers)
+    try:
+        compare(st, wl, st.run(wl), oracle_run(wl))
+    finally:
+        st.close()
+
+
 def test_dec7b_layer_full(B):
     wl = W.workload_dec7b(200)                       # 8192 packed tokens, d = 4096, MHA, SwiGLU 11008
     st = GpuStage(B, wl.layers)

@@ -349,6 +349,72 @@ def test_rope(B, hd, base):
     assert nmax_err(host_f64(dz)[:, :heads * hd], z[:, :heads * hd].astype(np.float64)) < 2e-2
 
 
+@pytest.mark.parametrize("hd,base,bias", [(128, 500000.0, False), (64, 10000.0, True), (128, 10000.0, True)])
+def test_gemm_with_rotary_epilogue(B, hd, base, bias):
+    """The QKV projection with the rotary positions in its epilogue: 7 q/k heads + value columns, ragged last
+    row tile, positions up to 13000 + 2300, against the fp64 product rotated by the oracle."""
+    lengths = [2300, 1, 700, 1095 + 37]
+    m, k = sum(lengths), 320
+    n_rot = 7 * 128 if hd == 128 else 14 * 64              # rotated heads: a multiple of 128 columns
+    n = n_rot + 256 + 3584                                  # plus value columns: 18 column tiles x 17 row tiles >= 200
+    x = W.draw_tensor(51, m, k)
+    w = W.bf16_round(W.draw_tensor(52, k, n) * np.float32(0.06))
+    b = W.bf16_round(W.draw_tensor(53, 1, n) * np.float32(0.5)) if bias else None
+    pos = (O.segment_positions(W.make_pack(lengths, 1).cu_seqlens) + 13000).astype(np.int32)
+    n_pos = int(pos.max()) + 1
+    table = torch.empty(n_pos, hd, dtype=torch.float32, device="cuda")
+    B.mllm_op_rope_table(table, n_pos, hd, base)
+    cos, sin = O.rope_tables(pos, hd, base)
+    tab = host_f64(table)[pos]
+    assert np.max(np.abs(tab[:, :hd // 2] - cos)) < 1e-6 and np.max(np.abs(tab[:, hd // 2:] - sin)) < 1e-6
+    y64 = x.astype(np.float64) @ w.astype(np.float64) + (b.astype(np.float64) if bias else 0.0)
+    ref = y64.copy()
+    ref[:, :n_rot] = O.rope_apply(y64[:, :n_rot].reshape(m, n_rot // hd, hd), cos, sin).reshape(m, n_rot)
+    y = torch.zeros(m, n, dtype=torch.bfloat16, device="cuda")
+    B.mllm_op_gemm_rope(dev_bf16(x), dev_bf16(w), dev_bf16(b) if bias else None, y, m, n, k,
+                        torch.from_numpy(pos).cuda(), table, n_rot, hd)
+    got = host_f64(y)
+    assert nmax_err(got[:, :n_rot], ref[:, :n_rot]) < 1e-2
+    assert nmax_err(got[:, n_rot:], ref[:, n_rot:]) < 1e-2
+    with pytest.raises(B.MllmError):                         # too few tiles for the large-tile kernel
+        B.mllm_op_gemm_rope(dev_bf16(x), dev_bf16(w), None, y, 256, n, k, torch.from_numpy(pos).cuda(), table, n_rot, hd)
+
+
+@pytest.mark.parametrize("hd,hq,hkv,lengths,kinds", [(128, 4, 1, [300, 1, 77], [1, 1, 1]), (64, 4, 2, [130, 64, 5], [1, 0, 1])])
+def test_attention_bwd_with_rotary_gradient(B, hd, hq, hkv, lengths, kinds):
+    """dq and dk leave the backward kernels rotated back: equal to the oracle's attention gradient followed
+    by the oracle's inverse rotation; dv is untouched."""
+    pack = W.make_pack(lengths, 0)
+    pack.mask_kind[:] = np.asarray(kinds, dtype=np.uint8)
+    T = pack.total_tokens
+    nq = (hq + 2 * hkv) * hd
+    qkv = W.draw_tensor(14, T, nq)
+    do = W.draw_tensor(15, T, hq * hd)
+    q = qkv[:, :hq * hd].reshape(T, hq, hd).astype(np.float64)
+    k = qkv[:, hq * hd:(hq + hkv) * hd].reshape(T, hkv, hd).astype(np.float64)
+    v = qkv[:, (hq + hkv) * hd:].reshape(T, hkv, hd).astype(np.float64)
+    dq_ref, dk_ref, dv_ref = O.attention_bwd(do.reshape(T, hq, hd).astype(np.float64), q, k, v, pack.cu_seqlens, pack.mask_kind)
+    cos, sin = O.rope_tables(O.segment_positions(pack.cu_seqlens), hd, 10000.0)
+    dq_ref, dk_ref = O.rope_apply_inverse(dq_ref, cos, sin), O.rope_apply_inverse(dk_ref, cos, sin)
+    table = torch.empty(max(lengths), hd, dtype=torch.float32, device="cuda")
+    B.mllm_op_rope_table(table, max(lengths), hd, 10000.0)
+    d_qkv = dev_bf16(qkv)
+    o = torch.zeros(T, hq * hd, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    qp, kp, vp = d_qkv.data_ptr(), d_qkv.data_ptr() + hq * hd * 2, d_qkv.data_ptr() + (hq + hkv) * hd * 2
+    B.mllm_op_attn_fwd(qp, kp, vp, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
+    dqkv = torch.zeros(T, nq, dtype=torch.bfloat16, device="cuda")
+    delta = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
+    gp = dqkv.data_ptr()
+    B.mllm_op_attn_bwd_rope(qp, kp, vp, o, lse, dev_bf16(do), gp, gp + hq * hd * 2, gp + (hq + hkv) * hd * 2, delta,
+                            pack, hq, hkv, hd, nq, nq, hq * hd, table, ws)
+    g = host_f64(dqkv)
+    assert nmax_err(g[:, :hq * hd], dq_ref.reshape(T, -1)) < 3e-2
+    assert nmax_err(g[:, hq * hd:(hq + hkv) * hd], dk_ref.reshape(T, -1)) < 3e-2
+    assert nmax_err(g[:, (hq + hkv) * hd:], dv_ref.reshape(T, -1)) < 3e-2
+
+
 @pytest.mark.parametrize("act", [0, 1, 2])
 def test_activations(B, act):
     t, f = 77, 768
