@@ -14,7 +14,7 @@
 // which is fetched from LDS with the transposing read).
 //
 //   forward:  S^T = K.Q^T, online softmax, O^T += V^T.P^T
-//   dQ pass:  S^T, dP^T = V.dO^T, dS^T = P^T*(dP^T - delta), dQ^T += K^T.dS^T
+//   dQ pass:  delta = rowsum(dO*O); S^T, dP^T = V.dO^T, dS^T = P^T*(dP^T - delta), dQ^T += K^T.dS^T
 //   dK/dV:    S = Q.K^T, dP = dO.V^T, dV^T += dO^T.P, dK^T += Q^T.dS, looping the query tiles
 //             and the query heads of the GQA group, so dK/dV need no atomics.
 #include <algorithm>
@@ -317,33 +317,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// delta[h][t] = sum_d dO[t,h,d] * O[t,h,d]
-// ---------------------------------------------------------------------------------------------
-template <int HD>
-__global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
-                                  float* __restrict__ delta, int64_t T, int Hq, int64_t o_stride) {
-  constexpr int G = HD / 8;  // lanes per (token, head)
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t pair = gid / G;
-  const int sub = (int)(gid % G);
-  float s = 0.f;
-  const bool ok = pair < T * Hq;
-  const int64_t tok = ok ? pair / Hq : 0;
-  const int hh = ok ? (int)(pair % Hq) : 0;
-  if (ok) {
-    const int64_t off = tok * o_stride + hh * HD + 8 * sub;
-    uint4 a = *reinterpret_cast<const uint4*>(o + off), b = *reinterpret_cast<const uint4*>(d_o + off);
-    s = bf16lo(a.x) * bf16lo(b.x) + bf16hi(a.x) * bf16hi(b.x) + bf16lo(a.y) * bf16lo(b.y) +
-        bf16hi(a.y) * bf16hi(b.y) + bf16lo(a.z) * bf16lo(b.z) + bf16hi(a.z) * bf16hi(b.z) +
-        bf16lo(a.w) * bf16lo(b.w) + bf16hi(a.w) * bf16hi(b.w);
-  }
-#pragma unroll
-  for (int off = G / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-  if (ok && sub == 0) delta[(int64_t)hh * T + tok] = s;
-}
-
-// ---------------------------------------------------------------------------------------------
-// dQ pass: one workgroup per (query tile of 128, head), looping over key tiles.
+// dQ pass: one workgroup per (query tile of 128, head), looping over key tiles.  It runs first in
+// the backward pass and also produces delta[h][t] = sum_d dO[t,h,d] * O[t,h,d] for the dK/dV pass.
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
@@ -370,7 +345,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
   }
   // Rows beyond the segment get lse = +inf, so their probabilities are exp2(-inf) = 0.
   const float lse2 = qok ? p.lse[(int64_t)head * p.T + grow] * LOG2E : INFINITY;
-  const float delta = qok ? p.delta[(int64_t)head * p.T + grow] : 0.f;
+  // delta = rowsum(dO * O) of the lane's query row: each half-wavefront holds half of the row's
+  // columns (the dO fragments above, O fetched the same way).  The dK/dV pass, which runs after this
+  // kernel, reads it from p.delta.
+  float delta = 0.f;
+  {
+    const bf16_t* op = p.o + grow * p.o_stride + head * HD + 8 * h;
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+      Frag8 fo, fd;
+      fo.v = global_frag(op + 16 * c, qok);
+      fd.v = dof[c];
+#pragma unroll
+      for (int w = 0; w < 4; w++) delta += bf16lo(fo.w[w]) * bf16lo(fd.w[w]) + bf16hi(fo.w[w]) * bf16hi(fd.w[w]);
+    }
+    delta += __shfl_xor(delta, 32, 64);
+    if (qok && h == 0) p.delta[(int64_t)head * p.T + grow] = delta;
+  }
   const int wave_first_q = t.tile0 + 32 * wave;
 
   const bf16_t* kbase = p.k + (int64_t)t.seg_start * p.kv_stride + kvh * HD;
@@ -726,24 +717,20 @@ hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   if (!offsets_fit(a)) return hipErrorInvalidValue;
   ProfScope prof(PROF_ATTN_BWD, 2.0 * a.fwd_flops, s);
   AttnParams p = make_params(a);
-  const int64_t n = (int64_t)a.total_tokens * a.n_q_heads * (a.head_dim / 8);
-  dim3 dgrid((unsigned)((n + 255) / 256)), block(256);
+  const dim3 block(256);
   dim3 qgrid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles);
   dim3 kgrid((unsigned)a.n_kv_heads, (unsigned)a.n_kv_tiles);
+  // dQ first: it writes delta, which the dK/dV pass reads
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL(attn_delta_kernel<128>, dgrid, block, 0, s, (const bf16_t*)a.o,
-                       (const bf16_t*)a.d_o, a.delta, (int64_t)a.total_tokens, a.n_q_heads, a.o_stride);
-    p.tiles = a.kv_tiles;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, kgrid, block, 0, s, p);
     p.tiles = a.q_tiles;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, qgrid, block, 0, s, p);
-  } else if (a.head_dim == 64) {
-    hipLaunchKernelGGL(attn_delta_kernel<64>, dgrid, block, 0, s, (const bf16_t*)a.o,
-                       (const bf16_t*)a.d_o, a.delta, (int64_t)a.total_tokens, a.n_q_heads, a.o_stride);
     p.tiles = a.kv_tiles;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, kgrid, block, 0, s, p);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, kgrid, block, 0, s, p);
+  } else if (a.head_dim == 64) {
     p.tiles = a.q_tiles;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, qgrid, block, 0, s, p);
+    p.tiles = a.kv_tiles;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, kgrid, block, 0, s, p);
   } else {
     return hipErrorInvalidValue;
   }

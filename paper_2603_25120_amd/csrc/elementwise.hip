@@ -304,6 +304,50 @@ __global__ void gelu_bwd_kernel(int act, const bf16_t* __restrict__ da, const bf
   for (int e = 0; e < 8; e++) o[e] = g[e] * gelu_grad_f(act, z[e]);
   reinterpret_cast<uint4*>(dh)[i] = pack8(o);
 }
+// The same with the column sums of dh (the gradient of the bias in front of the activation) formed
+// on the way: workgroup (bx, by) owns columns [512 bx, 512 bx + 512) and rows by*4 + wave + k*4*gridDim.y;
+// a lane keeps eight columns, the four wavefronts' sums are added through LDS in a fixed order and
+// land in row by of `partial` ([gridDim.y, f] fp32), which reduce_partials_kernel then sums.
+// da and dh may be the same buffer (a lane reads its eight values of a row before it writes them).
+__global__ __launch_bounds__(256) void gelu_bwd_colsum_kernel(int act, const bf16_t* da,
+                                                              const bf16_t* __restrict__ h, bf16_t* dh,
+                                                              float* __restrict__ partial, int64_t T, int64_t f) {
+  __shared__ float red[3][64][8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * 8;
+  const bool valid = c < f;
+  const int64_t step = (int64_t)gridDim.y * 4;
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (valid) {
+    int64_t r = (int64_t)blockIdx.y * 4 + wave;
+    uint4 zq, gq;
+    if (r < T) { zq = *reinterpret_cast<const uint4*>(h + r * f + c); gq = *reinterpret_cast<const uint4*>(da + r * f + c); }
+    for (; r < T; r += step) {
+      float z[8], g[8], o[8];
+      unpack8(zq, z);
+      unpack8(gq, g);
+      if (r + step < T) {   // the next row's loads go out before this row's arithmetic
+        zq = *reinterpret_cast<const uint4*>(h + (r + step) * f + c);
+        gq = *reinterpret_cast<const uint4*>(da + (r + step) * f + c);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e++) { o[e] = g[e] * gelu_grad_f(act, z[e]); s[e] += o[e]; }
+      *reinterpret_cast<uint4*>(dh + r * f + c) = pack8(o);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) red[wave - 1][lane][e] = s[e];
+  }
+  __syncthreads();
+  if (wave == 0 && valid) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) s[e] = (s[e] + red[0][lane][e]) + (red[1][lane][e] + red[2][lane][e]);
+    float* p = partial + (int64_t)blockIdx.y * f + c;
+    *reinterpret_cast<float4*>(p) = make_float4(s[0], s[1], s[2], s[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(s[4], s[5], s[6], s[7]);
+  }
+}
 // gu = [g | u], [T, 2f];  a = g * sigmoid(g) * u
 __global__ void swiglu_fwd_kernel(const bf16_t* __restrict__ gu, bf16_t* __restrict__ a, int64_t T, int64_t f) {
   const int64_t vec_per_row = f >> 3;
@@ -662,6 +706,18 @@ hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, 
   else
     hipLaunchKernelGGL(gelu_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, act,
                        (const bf16_t*)da, (const bf16_t*)pre, (bf16_t*)dpre, nvec);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd_colsum(int act, const void* da, const void* pre, void* dpre, float* colsum,
+                                  int accumulate, float* partial, int64_t t, int64_t f, hipStream_t s) {
+  if (f % 8 != 0 || (act != 0 && act != 1)) return hipErrorInvalidValue;
+  const int64_t P = colsum_partial_rows(t);
+  ProfScope prof(PROF_ELEMENTWISE, 6.0 * (double)t * (double)f, s);
+  hipLaunchKernelGGL(gelu_bwd_colsum_kernel, dim3(blocks_for(f, 512), (unsigned)P), dim3(256), 0, s, act,
+                     (const bf16_t*)da, (const bf16_t*)pre, (bf16_t*)dpre, partial, t, f);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(f, RED_COLS)), dim3(256), 0, s, partial, colsum, (int)P,
+                     f, accumulate);
   return hipGetLastError();
 }
 

@@ -96,6 +96,10 @@ hipError_t launch_rope_table(float* table, int64_t n_pos, int32_t head_dim, floa
 hipError_t launch_act_fwd(int act, const void* pre, void* a, int64_t t, int64_t f, hipStream_t s);
 hipError_t launch_act_bwd(int act, const void* da, const void* pre, void* dpre, int64_t t,
                           int64_t f, hipStream_t s);
+// GELU backward that also leaves the column sums of dpre (the gradient of the bias in front of the
+// activation) in colsum [f] fp32 (accumulate != 0: +=).  partial: fp32 scratch of colsum_partial_rows(t) x f.
+hipError_t launch_gelu_bwd_colsum(int act, const void* da, const void* pre, void* dpre, float* colsum,
+                                  int accumulate, float* partial, int64_t t, int64_t f, hipStream_t s);
 int64_t colsum_partial_rows(int64_t t);
 hipError_t launch_colsum(const void* x, int64_t ldx, float* out, int accumulate, float* partial,
                          int64_t t, int64_t n, hipStream_t s);

@@ -625,10 +625,12 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
     K_TRY(linear_dx_swiglu(dy, prm[iwdn], pre, dpre, T, f, d, s));
   } else {
     K_TRY(linear_dx(dy, prm[iwdn], wa, T, f, d, s));
-    K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
+    if (vit)   // the bias gradient (column sums of dpre) comes out of the same pass
+      K_TRY(launch_gelu_bwd_colsum(L.act, wa, pre, dpre, (float*)dprm[ibup], accumulate, partial, T, f, s));
+    else
+      K_TRY(launch_act_bwd(L.act, wa, pre, dpre, T, f, s));
   }
   K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s, split));
-  if (vit) K_TRY(launch_colsum(dpre, fup, (float*)dprm[ibup], accumulate, partial, T, fup, s));
   K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x1, prm[ig2], (const float*)(saved + S.stats2), dy, wd,
                         (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, d, s));
@@ -902,9 +904,8 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
         K_TRY(linear_dw(act, dproj, dprm[2], P.T_con, L.d_ff, L.d_out, accumulate, s, split));
         K_TRY(launch_colsum(dproj, L.d_out, (float*)dprm[3], accumulate, partial, P.T_con, L.d_out, s));
         K_TRY(linear_dx(dproj, prm[2], dh, P.T_con, L.d_ff, L.d_out, s));
-        K_TRY(launch_act_bwd(L.act, dh, pre, dh, P.T_con, L.d_ff, s));
+        K_TRY(launch_gelu_bwd_colsum(L.act, dh, pre, dh, (float*)dprm[1], accumulate, partial, P.T_con, L.d_ff, s));
         K_TRY(linear_dw(xin, dh, dprm[0], P.T_con, d_in, L.d_ff, accumulate, s, split));
-        K_TRY(launch_colsum(dh, L.d_ff, (float*)dprm[1], accumulate, partial, P.T_con, L.d_ff, s));
         K_TRY(linear_dx(dh, prm[0], dxin, P.T_con, d_in, L.d_ff, s));
       } else {
         K_TRY(linear_dw(xin, dproj, dprm[0], P.T_con, d_in, L.d_out, accumulate, s, split));
