@@ -241,13 +241,30 @@ mllm_status_t mllm_op_gemm_swiglu_bwd(const void* dy, const void* w_d, const voi
  *   q [T, n_q, hd], k, v [T, n_kv, hd] bf16 with row strides (in elements) q_stride / kv_stride,
  *   o [T, n_q, hd] bf16 (row stride o_stride), lse fp32 [n_q, T] (natural log-sum-exp of the
  *   scaled scores), scale = 1/sqrt(hd) applied inside.
- *   workspace: device scratch of at least mllm_op_attn_workspace_bytes(n_segments, T) bytes. */
-size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens);
+ *   workspace: device scratch of at least mllm_op_attn_workspace_bytes(n_segments, T, n_q_heads)
+ *   bytes (it receives the kernels' work lists: one item per (segment, tile, head)). */
+size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens, int32_t n_q_heads);
 mllm_status_t mllm_op_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                                const mllm_pack_t* pack, int32_t n_q_heads, int32_t n_kv_heads,
                                int32_t head_dim, int64_t q_stride, int64_t kv_stride,
                                int64_t o_stride, void* workspace, size_t workspace_bytes,
                                void* hip_stream);
+/* The order in which the attention kernels visit a packed token space (host only, no GPU work;
+ * exported so that the order can be checked).  One work item = one workgroup = (segment, tile of
+ * 128 rows, head): query tiles x query heads for the forward and dQ passes (kv_major = 0), key tiles
+ * x kv heads for the dK/dV pass (kv_major != 0).  Forward / dQ: items that read the same K / V rows
+ * (the tiles and query heads of one (segment, kv head), in runs of about one XCD's resident
+ * workgroups) are kept together on one XCD; the runs go to the eight XCDs heaviest first, each to the
+ * least loaded one, and workgroup pid of the launch takes item number pid / 8 of XCD pid % 8.  dK/dV:
+ * one list, heaviest key tile first, the kv heads of a tile adjacent.
+ * out_host (may be NULL to query the size) receives *grid_out entries of 5 int32 words: seg_start,
+ * seg_len, tile0, causal, head; entry pid is workgroup pid's item; seg_len = 0 marks the empty entries
+ * that pad the shorter XCD lists.  *bytes_needed = an upper bound of the bytes written (the size to
+ * allocate); *grid_out = workgroups launched = 8 * the longest XCD list. */
+mllm_status_t mllm_attn_work_list(const mllm_pack_t* pack, int32_t kv_major, int32_t n_q_heads,
+                                  int32_t n_kv_heads, int32_t head_dim, void* out_host,
+                                  size_t out_bytes, size_t* bytes_needed, int32_t* grid_out);
+
 /* Backward of the above from (q, k, v, o, lse, do): dq, dk, dv bf16 with the strides of q / k / v.
  * delta: fp32 scratch [n_q, T] (rowsum(dO * O)), overwritten. */
 mllm_status_t mllm_op_attn_bwd(const void* q, const void* k, const void* v, const void* o,

@@ -22,7 +22,7 @@ STATUS_NAMES = ["MLLM_OK", "MLLM_ERR_NULL", "MLLM_ERR_DESC", "MLLM_ERR_SHAPE", "
 
 EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", "mllm_stage_param_info",
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
-           "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
+           "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_attn_work_list", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
            "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_rope_table", "mllm_op_gemm_rope", "mllm_op_attn_bwd_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_op_colsum_static_max_bytes", "mllm_op_colsum_static", "mllm_profile_begin",
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
@@ -101,8 +101,9 @@ def lib() -> C.CDLL:
     L.mllm_op_gemm.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     L.mllm_op_gemm_swiglu.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
     L.mllm_op_gemm_swiglu_bwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
-    L.mllm_op_attn_workspace_bytes.argtypes = [i32, i32]
+    L.mllm_op_attn_workspace_bytes.argtypes = [i32, i32, i32]
     L.mllm_op_attn_workspace_bytes.restype = sz
+    L.mllm_attn_work_list.argtypes = [C.POINTER(PackC), i32, i32, i32, i32, vp, sz, C.POINTER(sz), C.POINTER(i32)]
     L.mllm_op_attn_fwd.argtypes = [vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, sz, vp]
     L.mllm_op_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(PackC), i32, i32, i32, i64, i64, i64, vp, sz, vp]
     L.mllm_op_norm_fwd.argtypes = [C.c_int, vp, vp, vp, vp, vp, i64, i64, C.c_float, vp]
@@ -280,8 +281,20 @@ def mllm_op_gemm_swiglu_bwd(dy, w_d, pre, dpre, m, f, k, stream=None) -> None:
     _check(lib().mllm_op_gemm_swiglu_bwd(_ptr(dy), _ptr(w_d), _ptr(pre), _ptr(dpre), m, f, k, _stream(stream)))
 
 
-def mllm_op_attn_workspace_bytes(n_segments: int, total_tokens: int) -> int:
-    return int(lib().mllm_op_attn_workspace_bytes(n_segments, total_tokens))
+def mllm_op_attn_workspace_bytes(n_segments: int, total_tokens: int, n_q_heads: int) -> int:
+    return int(lib().mllm_op_attn_workspace_bytes(n_segments, total_tokens, n_q_heads))
+
+
+def mllm_attn_work_list(pack, kv_major: bool, n_q_heads: int, n_kv_heads: int, head_dim: int) -> np.ndarray:
+    """The launch's entries [grid, 5] = seg_start, seg_len, tile0, causal, head (seg_len 0: empty entry)."""
+    pk = _PackKeep(pack)
+    need, grid = C.c_size_t(), C.c_int32()
+    _check(lib().mllm_attn_work_list(C.byref(pk.c), int(kv_major), n_q_heads, n_kv_heads, head_dim, None, 0,
+                                     C.byref(need), C.byref(grid)))
+    buf = np.zeros(max(need.value // 4, 5), dtype=np.int32)
+    _check(lib().mllm_attn_work_list(C.byref(pk.c), int(kv_major), n_q_heads, n_kv_heads, head_dim,
+                                     buf.ctypes.data_as(C.c_void_p), buf.nbytes, C.byref(need), C.byref(grid)))
+    return buf[:5 * grid.value].reshape(-1, 5).copy()
 
 
 def mllm_op_attn_fwd(q, k, v, o, lse, pack, n_q_heads, n_kv_heads, head_dim, q_stride, kv_stride, o_stride,

@@ -4,7 +4,8 @@
 // on its own so that no sample sees another (Model Profiler, "Throughput Profiling"): a packed
 // [T, heads, hd] sequence is cut into segments by cu_seqlens; each segment
 // attends only to itself, bidirectionally (an image inside the ViT) or causally (a sample inside
-// the LLM).  The host turns the segments into a list of tiles, longest first.
+// the LLM).  The host turns the segments into lists of (segment, tile, head) work items, one list
+// per XCD, in which workgroups that share rows sit together (attn_items.h).
 //
 // All three kernels compute score blocks TRANSPOSED so that a lane owns one query (or one key)
 // column of the 32x32 MFMA result: row statistics are then per-lane scalars plus one exchange
@@ -61,7 +62,7 @@ struct AttnParams {
   const bf16_t* d_o; bf16_t* dq; bf16_t* dk; bf16_t* dv; float* delta;
   int64_t q_stride, kv_stride, o_stride;
   int32_t T, Hq, Hkv;
-  const AttnTile* tiles;
+  const AttnItem* list;      // work list, one entry per workgroup
   float scale_log2e, scale;
   const float* rope_table;   // backward: dq, dk are rotated back by the rotary angle of their row (null: not)
 };
@@ -90,6 +91,14 @@ __device__ __forceinline__ void rope_unrotate(f32x16 (&acc)[HD / 32], const floa
         acc[d + ND / 2][4 * g4 + e] = y2 * cs[e] - y1 * ss[e];
       }
     }
+}
+
+// The work item of this workgroup (entry blockIdx.x of the list; the host has arranged the entries so
+// that workgroups sharing rows run on one XCD).  Returns false, for the whole workgroup, on the empty
+// items that pad the shorter XCD lists.
+__device__ __forceinline__ bool work_item(const AttnItem* list, AttnItem& t) {
+  t = list[blockIdx.x];
+  return t.seg_len > 0;
 }
 
 // Natural-layout operand: row (r0 + lane%32), contraction values 16c + 8*(lane/32) .. +7.
@@ -159,8 +168,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(1024))) bf16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vs1[TILE];
-  const AttnTile t = p.tiles[blockIdx.y];
-  const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
+  AttnItem t;
+  if (!work_item(p.list, t)) return;
+  const int head = t.head, kvh = head / (p.Hq / p.Hkv);
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qrow = t.tile0 + 32 * wave + (lane & 31);
@@ -252,7 +262,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnParams p) {
 #pragma unroll
       for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[b][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
-    const float m_new = fmaxf(m, mx);
+    // The reference maximum follows the row maximum lazily: it moves only when a tile exceeds it by
+    // more than 8 (log2 units).  Probabilities then reach 2^8 at most, which fp32 sums and the bf16
+    // operand carry at the same relative precision, and the 64-value rescaling of the output
+    // accumulator below is needed on a few tiles instead of on nearly every one (with 64 query rows
+    // per wavefront some row finds a slightly larger score in almost every tile).
+    const float m_new = mx > m + 8.f ? mx : m;
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = fast_exp2(m - m_use);
     float rs = 0.f;
@@ -328,8 +343,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(1024))) bf16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vs1[TILE];
-  const AttnTile t = p.tiles[blockIdx.y];
-  const int head = blockIdx.x, kvh = head / (p.Hq / p.Hkv);
+  AttnItem t;
+  if (!work_item(p.list, t)) return;
+  const int head = t.head, kvh = head / (p.Hq / p.Hkv);
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qrow = t.tile0 + 32 * wave + (lane & 31);
@@ -492,8 +508,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
   __shared__ __attribute__((aligned(1024))) bf16_t dOs0[TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t dOs1[TILE];
   __shared__ float lse_s0[BQ], lse_s1[BQ], delta_s0[BQ], delta_s1[BQ];
-  const AttnTile t = p.tiles[blockIdx.y];
-  const int kvh = blockIdx.x, grp = p.Hq / p.Hkv;
+  AttnItem t;
+  if (!work_item(p.list, t)) return;
+  const int kvh = t.head, grp = p.Hq / p.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int krow = t.tile0 + 32 * wave + (lane & 31);
@@ -682,7 +699,7 @@ AttnParams make_params(const AttnArgs& a) {
   p.dq = (bf16_t*)a.dq; p.dk = (bf16_t*)a.dk; p.dv = (bf16_t*)a.dv; p.delta = a.delta;
   p.q_stride = a.q_stride; p.kv_stride = a.kv_stride; p.o_stride = a.o_stride;
   p.T = a.total_tokens; p.Hq = a.n_q_heads; p.Hkv = a.n_kv_heads;
-  p.tiles = nullptr;
+  p.list = nullptr;
   p.scale = 1.0f / sqrtf((float)a.head_dim);
   p.scale_log2e = p.scale * LOG2E;
   p.rope_table = a.rope_table;
@@ -700,12 +717,12 @@ static bool offsets_fit(const AttnArgs& a) {
 }
 
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
-  if (a.n_q_tiles == 0) return hipSuccess;
+  if (a.q_grid == 0) return hipSuccess;
   if (!offsets_fit(a)) return hipErrorInvalidValue;
   ProfScope prof(PROF_ATTN_FWD, a.fwd_flops, s);
   AttnParams p = make_params(a);
-  p.tiles = a.q_tiles;
-  dim3 grid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles), block(256);  // heads fastest: heavy tiles first
+  p.list = (const AttnItem*)a.q_list;
+  const dim3 grid((unsigned)a.q_grid), block(256);
   if (a.head_dim == 128) hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, block, 0, s, p);
   else if (a.head_dim == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, block, 0, s, p);
   else return hipErrorInvalidValue;
@@ -713,23 +730,21 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
-  if (a.n_q_tiles == 0) return hipSuccess;
+  if (a.q_grid == 0) return hipSuccess;
   if (!offsets_fit(a)) return hipErrorInvalidValue;
   ProfScope prof(PROF_ATTN_BWD, 2.0 * a.fwd_flops, s);
   AttnParams p = make_params(a);
-  const dim3 block(256);
-  dim3 qgrid((unsigned)a.n_q_heads, (unsigned)a.n_q_tiles);
-  dim3 kgrid((unsigned)a.n_kv_heads, (unsigned)a.n_kv_tiles);
+  const dim3 block(256), qgrid((unsigned)a.q_grid), kgrid((unsigned)a.kv_grid);
   // dQ first: it writes delta, which the dK/dV pass reads
   if (a.head_dim == 128) {
-    p.tiles = a.q_tiles;
+    p.list = (const AttnItem*)a.q_list;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, qgrid, block, 0, s, p);
-    p.tiles = a.kv_tiles;
+    p.list = (const AttnItem*)a.kv_list;
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, kgrid, block, 0, s, p);
   } else if (a.head_dim == 64) {
-    p.tiles = a.q_tiles;
+    p.list = (const AttnItem*)a.q_list;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, qgrid, block, 0, s, p);
-    p.tiles = a.kv_tiles;
+    p.list = (const AttnItem*)a.kv_list;
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, kgrid, block, 0, s, p);
   } else {
     return hipErrorInvalidValue;

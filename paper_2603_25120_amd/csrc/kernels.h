@@ -54,20 +54,22 @@ size_t gemm_splitk_ws_bytes(int64_t m, int64_t n, int64_t k);
 hipError_t launch_splitk_reduce(const float* partial, float* out, int splits, int64_t n, int accumulate,
                                 hipStream_t s);
 
-// One entry per (segment, query tile) or (segment, key tile); built on the host, longest first.
-struct AttnTile {
+// One workgroup of an attention kernel: a tile of a segment and a head (query head for the forward
+// and dQ passes, kv head for the dK/dV pass).  The lists are built on the host (attn_items.h).
+struct AttnItem {
   int32_t seg_start;  // first packed row of the segment
   int32_t seg_len;
   int32_t tile0;      // first row of the tile inside the segment
   int32_t causal;
+  int32_t head;
 };
 struct AttnArgs {
   const void* q; const void* k; const void* v; void* o; float* lse;
   const void* d_o; void* dq; void* dk; void* dv; float* delta;
   int64_t q_stride, kv_stride, o_stride;   // row strides in elements (dq/dk/dv/do share them)
   int32_t total_tokens, n_q_heads, n_kv_heads, head_dim;
-  const AttnTile* q_tiles; int32_t n_q_tiles;     // device
-  const AttnTile* kv_tiles; int32_t n_kv_tiles;   // device
+  const void* q_list; int32_t q_grid;      // device work list of the forward / dQ passes and its grid size
+  const void* kv_list; int32_t kv_grid;    // device work list of the dK/dV pass and its grid size
   // backward only: when set (launch_rope_table, head_dim floats per position, positions counted from
   // the start of each segment), dq and dk leave rotated by the negative rotary angle of their row,
   // i.e. as gradients of the q and k that entered the rotation

@@ -14,6 +14,7 @@
 
 #include "../../include/mllm_stage.h"
 #include "kernels.h"
+#include "attn_items.h"
 #include "pinned_ring.h"
 
 using namespace mllm;
@@ -22,22 +23,6 @@ namespace {
 
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
-
-void build_tiles(const mllm_pack_t& p, int tile, bool kv_major, std::vector<AttnTile>& out) {
-  struct Item { AttnTile t; int64_t work; };
-  std::vector<Item> items;
-  for (int s = 0; s < p.n_segments; s++) {
-    const int start = p.cu_seqlens_host[s], len = p.cu_seqlens_host[s + 1] - start;
-    const int causal = p.mask_kind_host[s] == MLLM_MASK_CAUSAL;
-    for (int t0 = 0; t0 < len; t0 += tile) {
-      int64_t work = !causal ? len : (kv_major ? len - t0 : std::min(len, t0 + tile));
-      items.push_back({{start, len, t0, causal}, work});
-    }
-  }
-  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
-  out.clear();
-  for (auto& it : items) out.push_back(it.t);
-}
 
 }  // namespace
 
@@ -80,7 +65,7 @@ mllm_status_t check_attn(const mllm_pack_t* pack, int32_t hq, int32_t hkv, int32
   if (qs < (int64_t)hq * hd || kvs < (int64_t)hkv * hd || os < (int64_t)hq * hd || qs % 8 || kvs % 8 || os % 8)
     return op_fail(MLLM_ERR_SHAPE, "row strides too small or not multiples of 8");
   if (!ws) return op_fail(MLLM_ERR_NULL, "workspace is NULL");
-  if (ws_bytes < mllm_op_attn_workspace_bytes(pack->n_segments, pack->total_tokens)) return op_fail(MLLM_ERR_WORKSPACE, "attention workspace too small");
+  if (ws_bytes < mllm_op_attn_workspace_bytes(pack->n_segments, pack->total_tokens, hq)) return op_fail(MLLM_ERR_WORKSPACE, "attention workspace too small");
   return MLLM_OK;
 }
 
@@ -97,26 +82,22 @@ PinnedRing& op_staging() {
 }
 
 mllm_status_t upload_tiles(const mllm_pack_t* pack, void* ws, AttnArgs& a, hipStream_t stream) {
-  std::vector<AttnTile> qt, kt;
-  build_tiles(*pack, ATTN_FWD_Q_TILE, false, qt);
-  build_tiles(*pack, ATTN_BWD_KV_TILE, true, kt);
   char* w = (char*)ws;
-  const size_t koff = align_up(sizeof(AttnTile) * qt.size());
-  const size_t bytes = koff + sizeof(AttnTile) * kt.size();
-  if (bytes) {
-    PinnedRing& ring = op_staging();
-    PinnedRing::Slot* slot = nullptr;
-    OP_TRY(ring.acquire(bytes, &slot));
-    char* h = (char*)slot->p;
-    if (!qt.empty()) memcpy(h, qt.data(), sizeof(AttnTile) * qt.size());
-    if (!kt.empty()) memcpy(h + koff, kt.data(), sizeof(AttnTile) * kt.size());
-    OP_TRY(hipMemcpyAsync(w, h, bytes, hipMemcpyHostToDevice, stream));
-    OP_TRY(ring.commit(slot, stream));
-  }
-  a.q_tiles = (const AttnTile*)w;
-  a.kv_tiles = (const AttnTile*)(w + koff);
-  a.n_q_tiles = (int)qt.size();
-  a.n_kv_tiles = (int)kt.size();
+  const size_t qbytes = attn_list_bytes(*pack, ATTN_FWD_Q_TILE, a.n_q_heads);
+  const size_t koff = align_up(qbytes);
+  const size_t bytes = koff + attn_list_bytes(*pack, ATTN_BWD_KV_TILE, a.n_kv_heads);
+  PinnedRing& ring = op_staging();
+  PinnedRing::Slot* slot = nullptr;
+  OP_TRY(ring.acquire(bytes, &slot));
+  char* h = (char*)slot->p;
+  a.q_grid = build_attn_list(*pack, ATTN_FWD_Q_TILE, false, a.n_kv_heads, a.n_q_heads / a.n_kv_heads, 64, h);
+  a.kv_grid = build_attn_list(*pack, ATTN_BWD_KV_TILE, true, a.n_kv_heads, a.n_q_heads / a.n_kv_heads,
+                              a.head_dim == 64 ? 64 : 32, h + koff);
+  if (a.q_grid) OP_TRY(hipMemcpyAsync(w, h, (size_t)a.q_grid * sizeof(AttnItem), hipMemcpyHostToDevice, stream));
+  if (a.kv_grid) OP_TRY(hipMemcpyAsync(w + koff, h + koff, (size_t)a.kv_grid * sizeof(AttnItem), hipMemcpyHostToDevice, stream));
+  OP_TRY(ring.commit(slot, stream));
+  a.q_list = w;
+  a.kv_list = w + koff;
   double pairs = 0;
   for (int s = 0; s < pack->n_segments; s++) {
     const double len = pack->cu_seqlens_host[s + 1] - pack->cu_seqlens_host[s];
@@ -236,9 +217,27 @@ mllm_status_t mllm_op_gemm_rope(const void* x, const void* w, const void* bias, 
   return MLLM_OK;
 }
 
-size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens) {
+mllm_status_t mllm_attn_work_list(const mllm_pack_t* pack, int32_t kv_major, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim, void* out_host, size_t out_bytes, size_t* bytes_needed,
+                                  int32_t* grid_out) {
+  mllm_status_t r = check_pack(pack);
+  if (r != MLLM_OK) return r;
+  if (head_dim != 64 && head_dim != 128) return op_fail(MLLM_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads) return op_fail(MLLM_ERR_SHAPE, "n_q_heads must be a positive multiple of n_kv_heads");
+  const int tile = kv_major ? ATTN_BWD_KV_TILE : ATTN_FWD_Q_TILE;
+  const size_t need = attn_list_bytes(*pack, tile, kv_major ? n_kv_heads : n_q_heads);
+  if (bytes_needed) *bytes_needed = need;
+  if (!out_host) return MLLM_OK;
+  if (out_bytes < need) return op_fail(MLLM_ERR_WORKSPACE, "work list needs %zu bytes, %zu given", need, out_bytes);
+  const int grid = build_attn_list(*pack, tile, kv_major != 0, n_kv_heads, n_q_heads / n_kv_heads,
+                                   kv_major ? (head_dim == 64 ? 64 : 32) : 64, (char*)out_host);
+  if (grid_out) *grid_out = grid;
+  return MLLM_OK;
+}
+
+size_t mllm_op_attn_workspace_bytes(int32_t n_segments, int32_t total_tokens, int32_t n_q_heads) {
   const size_t max_tiles = (size_t)std::max(0, total_tokens) / 128 + (size_t)std::max(0, n_segments) + 1;
-  return 2 * align_up(sizeof(AttnTile) * max_tiles);
+  return 2 * align_up((size_t)ATTN_XCDS * sizeof(AttnItem) * max_tiles * (size_t)std::max(1, n_q_heads));
 }
 
 mllm_status_t mllm_op_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,

@@ -16,6 +16,7 @@
 
 #include "../../include/mllm_stage.h"
 #include "kernels.h"
+#include "attn_items.h"
 #include "pinned_ring.h"
 
 using namespace mllm;
@@ -185,26 +186,27 @@ struct LayerSaved {  // byte offsets into `saved`
   size_t qkn, statsq, statsk;
 };
 
-struct Meta {  // byte offsets into the metadata blob at the head of the workspace
-  size_t img_q_tiles = 0, img_kv_tiles = 0, seq_q_tiles = 0, seq_kv_tiles = 0, pos = 0, i2s = 0;
-  size_t pool_first = 0, pool_count = 0, row_window = 0;   // pooling connector: window tables
-  int n_img_q = 0, n_img_kv = 0, n_seq_q = 0, n_seq_kv = 0;
-  size_t bytes = 0;
+// Attention work lists of one (token space, head counts) combination; layers that agree in these share them.
+struct AttnLists {
+  bool img;
+  int hq, hkv, head_dim;
+  size_t q_off = 0, kv_off = 0;     // byte offsets into the metadata blob
+  int q_grid = 0, kv_grid = 0;      // grid sizes, known once the lists are built (upload_meta)
 };
 
-int count_tiles(const mllm_pack_t& p, int tile) {
-  int n = 0;
-  for (int s = 0; s < p.n_segments; s++) {
-    int len = p.cu_seqlens_host[s + 1] - p.cu_seqlens_host[s];
-    n += (len + tile - 1) / tile;
-  }
-  return n;
-}
+struct Meta {  // byte offsets into the metadata blob at the head of the workspace
+  std::vector<AttnLists> attn;
+  size_t tables = 0;                // where the tables below begin (the attention lists come first)
+  size_t pos = 0, i2s = 0;
+  size_t pool_first = 0, pool_count = 0, row_window = 0;   // pooling connector: window tables
+  size_t bytes = 0;
+};
 
 struct Plan {
   std::vector<LayerSaved> saved;  // per layer
   size_t saved_bytes = 0;
   Meta meta;
+  std::vector<int> attn_of;       // per layer: index into meta.attn (-1: no attention)
   // workspace offsets (after the metadata)
   size_t w_partial = 0;           // fp32 partial sums of norm / bias gradients
   size_t w_a = 0, w_b = 0, w_c = 0, w_d = 0, w_e = 0, w_delta = 0, w_g0 = 0, w_g1 = 0, w_proj = 0, w_split = 0;
@@ -283,19 +285,28 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
 
   Bump ws;
   Meta& M = P.meta;
-  if (st->n_vit > 0) {
-    M.n_img_q = count_tiles(b->img, ATTN_FWD_Q_TILE);
-    M.n_img_kv = count_tiles(b->img, ATTN_BWD_KV_TILE);
-    M.img_q_tiles = ws.take(sizeof(AttnTile) * M.n_img_q);
-    M.img_kv_tiles = ws.take(sizeof(AttnTile) * M.n_img_kv);
+  P.attn_of.assign(st->layers.size(), -1);
+  for (size_t i = 0; i < st->layers.size(); i++) {
+    const mllm_layer_desc_t& L = st->layers[i];
+    if (L.kind == MLLM_LAYER_PROJECTOR) continue;
+    const bool img = L.kind == MLLM_LAYER_VIT;
+    int found = -1;
+    for (size_t k = 0; k < M.attn.size(); k++)
+      if (M.attn[k].img == img && M.attn[k].hq == L.n_q_heads && M.attn[k].hkv == L.n_kv_heads && M.attn[k].head_dim == L.head_dim)
+        found = (int)k;
+    if (found < 0) {
+      AttnLists A;
+      A.img = img; A.hq = L.n_q_heads; A.hkv = L.n_kv_heads; A.head_dim = L.head_dim;
+      const mllm_pack_t& pk = img ? b->img : b->seq;
+      A.q_off = ws.take(attn_list_bytes(pk, ATTN_FWD_Q_TILE, L.n_q_heads));
+      A.kv_off = ws.take(attn_list_bytes(pk, ATTN_BWD_KV_TILE, L.n_kv_heads));
+      found = (int)M.attn.size();
+      M.attn.push_back(A);
+    }
+    P.attn_of[i] = found;
   }
-  if (st->n_dec > 0) {
-    M.n_seq_q = count_tiles(b->seq, ATTN_FWD_Q_TILE);
-    M.n_seq_kv = count_tiles(b->seq, ATTN_BWD_KV_TILE);
-    M.seq_q_tiles = ws.take(sizeof(AttnTile) * M.n_seq_q);
-    M.seq_kv_tiles = ws.take(sizeof(AttnTile) * M.n_seq_kv);
-    M.pos = ws.take(sizeof(int32_t) * P.T_seq);
-  }
+  M.tables = ws.off;
+  if (st->n_dec > 0) M.pos = ws.take(sizeof(int32_t) * P.T_seq);
   if (st->proj >= 0) M.i2s = ws.take(sizeof(int32_t) * P.T_con);
   if (st->proj >= 0 && P.pool > 1) {
     M.pool_first = ws.take(sizeof(int32_t) * P.T_con);
@@ -381,38 +392,24 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
 // -------------------------------------------------------------------------------------------
 // metadata: attention tile lists (heaviest first), positions, scatter rows
 // -------------------------------------------------------------------------------------------
-void build_tiles(const mllm_pack_t& p, int tile, bool kv_major, AttnTile* out) {
-  struct Item { AttnTile t; int64_t work; int idx; };
-  std::vector<Item> items;
-  for (int s = 0; s < p.n_segments; s++) {
-    const int start = p.cu_seqlens_host[s], len = p.cu_seqlens_host[s + 1] - start;
-    const int causal = p.mask_kind_host[s] == MLLM_MASK_CAUSAL;
-    for (int t0 = 0; t0 < len; t0 += tile) {
-      int64_t work;
-      if (!causal) work = len;
-      else work = kv_major ? (len - t0) : std::min(len, t0 + tile);
-      items.push_back({{start, len, t0, causal}, work, (int)items.size()});
-    }
-  }
-  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
-  for (size_t i = 0; i < items.size(); i++) out[i] = items[i].t;
-}
+// Residents per XCD (32 CUs): the forward and dQ kernels keep two workgroups per CU, the dK/dV kernel
+// two for heads of 64 and one for heads of 128.
+int kv_residents(int head_dim) { return head_dim == 64 ? 64 : 32; }
 
-mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, void* workspace,
+mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, Plan& P, void* workspace,
                           hipStream_t s) {
-  const Meta& M = P.meta;
+  Meta& M = P.meta;
   if (M.bytes == 0) return MLLM_OK;
   PinnedRing::Slot* slot = nullptr;
   HIP_TRY(st->staging.acquire(M.bytes, &slot));
   char* h = (char*)slot->p;
-  memset(h, 0, M.bytes);
-  if (st->n_vit > 0) {
-    build_tiles(b->img, ATTN_FWD_Q_TILE, false, (AttnTile*)(h + M.img_q_tiles));
-    build_tiles(b->img, ATTN_BWD_KV_TILE, true, (AttnTile*)(h + M.img_kv_tiles));
+  memset(h + M.tables, 0, M.bytes - M.tables);
+  for (AttnLists& A : M.attn) {
+    const mllm_pack_t& pk = A.img ? b->img : b->seq;
+    A.q_grid = build_attn_list(pk, ATTN_FWD_Q_TILE, false, A.hkv, A.hq / A.hkv, 64, h + A.q_off);
+    A.kv_grid = build_attn_list(pk, ATTN_BWD_KV_TILE, true, A.hkv, A.hq / A.hkv, kv_residents(A.head_dim), h + A.kv_off);
   }
   if (st->n_dec > 0) {
-    build_tiles(b->seq, ATTN_FWD_Q_TILE, false, (AttnTile*)(h + M.seq_q_tiles));
-    build_tiles(b->seq, ATTN_BWD_KV_TILE, true, (AttnTile*)(h + M.seq_kv_tiles));
     int32_t* pos = (int32_t*)(h + M.pos);
     for (int sgm = 0; sgm < b->seq.n_segments; sgm++)
       for (int t = b->seq.cu_seqlens_host[sgm]; t < b->seq.cu_seqlens_host[sgm + 1]; t++)
@@ -433,7 +430,13 @@ mllm_status_t upload_meta(mllm_stage* st, const mllm_batch_t* b, const Plan& P, 
       }
     }
   }
-  HIP_TRY(hipMemcpyAsync(workspace, h, M.bytes, hipMemcpyHostToDevice, s));
+  // the lists are reserved at their upper bound; only the entries of the launch grids are copied
+  char* w = (char*)workspace;
+  for (const AttnLists& A : M.attn) {
+    if (A.q_grid) HIP_TRY(hipMemcpyAsync(w + A.q_off, h + A.q_off, (size_t)A.q_grid * sizeof(AttnItem), hipMemcpyHostToDevice, s));
+    if (A.kv_grid) HIP_TRY(hipMemcpyAsync(w + A.kv_off, h + A.kv_off, (size_t)A.kv_grid * sizeof(AttnItem), hipMemcpyHostToDevice, s));
+  }
+  if (M.bytes > M.tables) HIP_TRY(hipMemcpyAsync(w + M.tables, h + M.tables, M.bytes - M.tables, hipMemcpyHostToDevice, s));
   HIP_TRY(st->staging.commit(slot, s));
   return MLLM_OK;
 }
@@ -501,8 +504,9 @@ hipError_t linear_dw(const void* x, const void* dy, void* dw, int64_t T, int64_t
 
 // qk: the [T, nq] matrix whose q and k columns attention reads; v: the one whose v columns it reads
 // (the same matrix unless the layer normalises q and k).
-AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, const char* ws, const Plan& P, bool img) {
-  const Meta& M = P.meta;
+AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, const char* ws, const Plan& P, bool img,
+                   int list_index) {
+  const AttnLists& A = P.meta.attn[list_index];
   AttnArgs a;
   memset(&a, 0, sizeof a);
   const int64_t nq = nqkv_of(L);
@@ -513,10 +517,10 @@ AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, con
   a.o_stride = L.d_model;
   a.total_tokens = (int32_t)T;
   a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads; a.head_dim = L.head_dim;
-  a.q_tiles = (const AttnTile*)(ws + (img ? M.img_q_tiles : M.seq_q_tiles));
-  a.kv_tiles = (const AttnTile*)(ws + (img ? M.img_kv_tiles : M.seq_kv_tiles));
-  a.n_q_tiles = img ? M.n_img_q : M.n_seq_q;
-  a.n_kv_tiles = img ? M.n_img_kv : M.n_seq_kv;
+  a.q_list = ws + A.q_off;
+  a.kv_list = ws + A.kv_off;
+  a.q_grid = A.q_grid;
+  a.kv_grid = A.kv_grid;
   a.fwd_flops = 4.0 * (img ? P.img_pairs : P.seq_pairs) * L.n_q_heads * L.head_dim;
   return a;
 }
@@ -533,7 +537,7 @@ AttnArgs attn_args(const mllm_layer_desc_t& L, char* qk, char* v, int64_t T, con
 // -------------------------------------------------------------------------------------------
 mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, const LayerSaved& S,
                         char* saved, char* ws, const Plan& P, int64_t T, void* y, const float* rope_table,
-                        hipStream_t s) {
+                        int attn_list, hipStream_t s) {
   const bool vit = L.kind == MLLM_LAYER_VIT;
   const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
   char* x = saved + S.x;
@@ -573,7 +577,7 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
   if (!vit && !rope_fused)
     K_TRY(launch_rope(qk, (const int32_t*)(ws + P.meta.pos), T, nq, 0, L.n_q_heads + L.n_kv_heads,
                       L.head_dim, L.rope_base, 0, s));
-  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit);
+  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit, attn_list);
   a.o = o;
   a.lse = (float*)(saved + S.lse);
   K_TRY(launch_attn_fwd(a, s));
@@ -593,7 +597,7 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
 mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void* const* dprm,
                         int accumulate, const LayerSaved& S, const char* saved, char* ws,
                         const Plan& P, int64_t T, const void* dy, void* dx, const float* rope_table,
-                        hipStream_t s) {
+                        int attn_list, hipStream_t s) {
   const bool vit = L.kind == MLLM_LAYER_VIT;
   const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
   const char* x = saved + S.x;
@@ -645,7 +649,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   const int64_t q_cols = (int64_t)L.n_q_heads * L.head_dim, k_cols = (int64_t)L.n_kv_heads * L.head_dim;
   char* qk = L.qk_norm ? const_cast<char*>(saved + S.qkn) : qkv;
   char* dqk = L.qk_norm ? ws + P.w_qkn : we;
-  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit);
+  AttnArgs a = attn_args(L, qk, qkv, T, ws, P, vit, attn_list);
   a.o = const_cast<char*>(o);
   a.lse = (float*)const_cast<char*>(saved + S.lse);
   a.d_o = wc;
@@ -850,7 +854,7 @@ mllm_status_t mllm_stage_fwd(mllm_stage_t* st, const mllm_batch_t* b, const void
     if (i == 0) K_TRY(launch_copy(vit ? x_img : x_seq, saved + P.saved[i].x, (size_t)T * L.d_model * 2, s));
     void* out = last ? y : (void*)(saved + P.saved[i + 1].x);
     const float* rope_table = P.rope_of[i] >= 0 ? (const float*)(ws + P.rope_tables[P.rope_of[i]].off) : nullptr;
-    if ((r = layer_fwd(L, prm, P.saved[i], saved, ws, P, T, out, rope_table, s)) != MLLM_OK) return r;
+    if ((r = layer_fwd(L, prm, P.saved[i], saved, ws, P, T, out, rope_table, P.attn_of[i], s)) != MLLM_OK) return r;
   }
   return MLLM_OK;
 }
@@ -927,7 +931,7 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       if (want) out = want;
     }
     const float* rope_table = P.rope_of[i] >= 0 ? (const float*)(ws + P.rope_tables[P.rope_of[i]].off) : nullptr;
-    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, rope_table, s)) != MLLM_OK) return r;
+    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, rope_table, P.attn_of[i], s)) != MLLM_OK) return r;
     cur = out;
     flip ^= 1;
   }

@@ -220,7 +220,7 @@ def test_attention_full_shape_sampled(B):
     lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
     delta = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
     dqkv = torch.zeros(T, nq, dtype=torch.bfloat16, device="cuda")
-    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T, hq))
     qp = dq_.data_ptr()
     kp, vp = qp + hq * hd * 2, qp + (hq + hkv) * hd * 2
     gp = dqkv.data_ptr()

@@ -264,7 +264,7 @@ def test_attention_fwd_bwd(B, hd, hq, hkv, lengths, kinds):
     d_qkv = dev_bf16(qkv)
     o = torch.zeros(T, hq * hd, dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
-    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T, hq))
     esz = 2
     qp, kp, vp = d_qkv.data_ptr(), d_qkv.data_ptr() + hq * hd * esz, d_qkv.data_ptr() + (hq + hkv) * hd * esz
     B.mllm_op_attn_fwd(qp, kp, vp, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
@@ -290,7 +290,7 @@ def test_attention_exact_cases(B):
     d = dev_bf16(qkv)
     o = empty_bf16(T, hq * hd)
     lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
-    ws = scratch(B.mllm_op_attn_workspace_bytes(3, T))
+    ws = scratch(B.mllm_op_attn_workspace_bytes(3, T, hq))
     B.mllm_op_attn_fwd(d.data_ptr(), d.data_ptr() + hq * hd * 2, d.data_ptr() + 2 * hq * hd * 2, o, lse, pack,
                        hq, hq, hd, 3 * hq * hd, 3 * hq * hd, hq * hd, ws)
     got = host_f64(o)
@@ -401,7 +401,7 @@ def test_attention_bwd_with_rotary_gradient(B, hd, hq, hkv, lengths, kinds):
     d_qkv = dev_bf16(qkv)
     o = torch.zeros(T, hq * hd, dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros(hq, T, dtype=torch.float32, device="cuda")
-    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T))
+    ws = scratch(B.mllm_op_attn_workspace_bytes(pack.n_segments, T, hq))
     qp, kp, vp = d_qkv.data_ptr(), d_qkv.data_ptr() + hq * hd * 2, d_qkv.data_ptr() + (hq + hkv) * hd * 2
     B.mllm_op_attn_fwd(qp, kp, vp, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
     dqkv = torch.zeros(T, nq, dtype=torch.bfloat16, device="cuda")
@@ -467,7 +467,7 @@ def test_attention_longest_possible_sample(B):
     lse = torch.zeros(hq, L, dtype=torch.float32, device="cuda")
     delta = torch.zeros(hq, L, dtype=torch.float32, device="cuda")
     g = torch.zeros(L, nq, dtype=torch.bfloat16, device="cuda")
-    ws = scratch(B.mllm_op_attn_workspace_bytes(1, L))
+    ws = scratch(B.mllm_op_attn_workspace_bytes(1, L, hq))
     qp = d.data_ptr()
     B.mllm_op_attn_fwd(qp, qp + hq * hd * 2, qp + (hq + hkv) * hd * 2, o, lse, pack, hq, hkv, hd, nq, nq, hq * hd, ws)
     gp = g.data_ptr()
