@@ -180,10 +180,14 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
 // added pairwise (s with s+64, then s with s+32, ...): a fixed association, so the result is
 // bitwise reproducible.
 constexpr int RED_COLS = 8, RED_SLICES = 128;
+// blockIdx.y = 1 (when launched with two rows of workgroups) reduces a second set of partial sums,
+// P * n floats further on, into out1: a norm's two gradients go in one launch.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
                                                               float* __restrict__ out, int P,
-                                                              int64_t n, int accumulate) {
+                                                              int64_t n, int accumulate,
+                                                              float* __restrict__ out1 = nullptr) {
   __shared__ float4 part[RED_SLICES][RED_COLS / 4];
+  if (blockIdx.y == 1) { partial += (int64_t)P * n; out = out1; }
   const int cg = threadIdx.x & 1, slice = threadIdx.x >> 1;
   const int64_t c = ((int64_t)blockIdx.x * (RED_COLS / 4) + cg) * 4;
   const bool valid = c < n;
@@ -650,11 +654,8 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
 #undef CALL
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS)), dim3(256), 0, s, partial,
-                     dgamma, (int)W, d, accumulate);
-  if (kind == 0)
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS)), dim3(256), 0, s,
-                       partial + W * d, dbeta, (int)W, d, accumulate);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS), kind == 0 ? 2 : 1), dim3(256), 0, s, partial,
+                     dgamma, (int)W, d, accumulate, kind == 0 ? dbeta : nullptr);
   return hipGetLastError();
 }
 

@@ -27,9 +27,11 @@ def _both(B, x_np, accumulate, seed_out):
     ref, got = base.clone(), base.clone()
     partial = scratch(B.mllm_op_colsum_partial_bytes(t, n))
     B.mllm_op_colsum(x, ref, accumulate, partial, t, n)
-    before = torch.cuda.memory_allocated()
+    # cumulative count of the allocator's requests: unlike the bytes in use it cannot drop when the
+    # garbage collector frees an earlier test's tensors in the middle of the call
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     B.mllm_op_colsum_static(x, got, accumulate, t, n)
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     torch.cuda.synchronize()
     return host_f64(base), ref, got
 
