@@ -97,7 +97,13 @@ __device__ __forceinline__ void rope_unrotate(f32x16 (&acc)[HD / 32], const floa
 // that workgroups sharing rows run on one XCD).  Returns false, for the whole workgroup, on the empty
 // items that pad the shorter XCD lists.
 __device__ __forceinline__ bool work_item(const AttnItem* list, AttnItem& t) {
-  t = list[blockIdx.x];
+  const AttnItem x = list[blockIdx.x];
+  // the same for every lane: keep the fields in scalar registers
+  t.seg_start = __builtin_amdgcn_readfirstlane(x.seg_start);
+  t.seg_len = __builtin_amdgcn_readfirstlane(x.seg_len);
+  t.tile0 = __builtin_amdgcn_readfirstlane(x.tile0);
+  t.causal = __builtin_amdgcn_readfirstlane(x.causal);
+  t.head = __builtin_amdgcn_readfirstlane(x.head);
   return t.seg_len > 0;
 }
 
@@ -692,6 +698,371 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_kernel(Att
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// dK/dV pass, software-pipelined form.  The work of a block of 32 query rows is a chain: scores and
+// dP (MFMA) -> probabilities and dS (vector ALU, 1/4 of it the exponential) -> dV and dK (MFMA).
+// Run as a chain, with one wavefront per SIMD at head_dim 128, the matrix pipe idles during the
+// vector stage and the vector ALU during the other two.  Here every step works on two blocks: the
+// score MFMAs of block n+1 are issued one per slot and the vector work of block n is cut into as
+// many slices, one behind each MFMA (the matrix pipe runs an MFMA for 32 clocks while the wavefront
+// goes on issuing independent instructions); the dV/dK MFMAs of block n follow, carrying the LDS
+// reads of the next steps.  The Q / dO tiles rotate through NST stages of LDS: a tile is still
+// being read (dV/dK of its second block) after the barrier that opens the next tile, so the tile
+// after that is loaded into a third stage.  The stage base is part of the address registers, which
+// are advanced once per tile; block and operand offsets ride in the instructions' offset fields.
+// ---------------------------------------------------------------------------------------------
+typedef MLLM_LDS const char* lds_cptr;
+__device__ __forceinline__ bf16x8 lds_b128(lds_cptr base, uint32_t off) {
+  return __builtin_bit_cast(bf16x8, *(MLLM_LDS const u32x4_t*)(base + off));
+}
+__device__ __forceinline__ s16x4 lds_tr(lds_cptr base, uint32_t off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)(base + off));
+}
+__device__ __forceinline__ f32x4 lds_f4(lds_cptr base, uint32_t off) { return *(MLLM_LDS const f32x4*)(base + off); }
+template <int V> using Int = std::integral_constant<int, V>;
+// Loads from global memory straight into LDS, written as assembly so that the compiler does not
+// know them for what they are.  Told (through the builtin), it makes LDS reads wait for every such
+// load in flight into the same LDS variable, which turns a queue of several tiles on their way
+// into one tile at a time; it cannot see that the loads go to a stage nobody reads when the stage
+// numbers are run-time values.  The kernel that uses these waits for its loads by count and
+// separates writers from readers with barriers, as it has to anyway.
+// The 64 lanes' 16 (or 4) bytes land side by side from LDS address `lds_addr` (wavefront-uniform).
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t raw_rsrc(const void* base, uint32_t bytes) {   // untyped buffer over [base, base + bytes)
+  const uint64_t b = (uint64_t)base;
+  i32x4_t r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+__device__ __forceinline__ void load_to_lds_b128(i32x4_t rsrc, uint32_t lds_addr, uint32_t byte_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(byte_off), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void load_to_lds_b32(i32x4_t rsrc, uint32_t lds_addr, uint32_t byte_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(byte_off), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(MLLM_LDS const void* p) { return (uint32_t)(size_t)p; }
+// At most N of the loads above still in flight (the compiler does not count them, so neither can its builtin).
+template <int N>
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
+template <int HD>
+__global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkv_pipe_kernel(AttnParams p) {
+  constexpr int NC = HD / 16, ND = HD / 32, TILE = BQ * HD, NST = 4;
+  constexpr int TILE_B = TILE * 2;                          // a stage: the Q tile, then the dO tile
+  constexpr int ROWS32_B = 32 * HD * 2, ROWS16_B = 16 * HD * 2;
+  constexpr int STAGE_B = 2 * TILE_B, STAT_STAGE_B = 2 * BQ * 4;
+  // NST stages of tiles, then NST stages of row statistics (lse of the tile's rows, then delta).  ONE
+  // array on purpose: the compiler tags LDS accesses with the variable they belong to and makes every
+  // read of a variable wait for all loads in flight into the same variable; it cannot tell the stages
+  // of one array apart when their numbers are run-time values.  With a single variable there is
+  // nothing to tag, and the waits below (which know the stages) are the only ones.
+  constexpr int STATS_AT = NST * STAGE_B;
+  __shared__ __attribute__((aligned(1024))) char lds[NST * STAGE_B + NST * STAT_STAGE_B];
+  AttnItem t;
+  if (!work_item(p.list, t)) return;
+  const int kvh = t.head, grp = p.Hq / p.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int krow = t.tile0 + 32 * wave + (lane & 31);
+  const bool kok = krow < t.seg_len;
+  const int64_t gkrow = t.seg_start + (kok ? krow : 0);
+  const bf16_t* kp = p.k + gkrow * p.kv_stride + kvh * HD + 8 * h;
+  const bf16_t* vp = p.v + gkrow * p.kv_stride + kvh * HD + 8 * h;
+  bf16x8 kf[NC], vf[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) {
+    kf[c] = global_frag(kp + 16 * c, kok);
+    vf[c] = global_frag(vp + 16 * c, kok);
+  }
+  // MFMA operands may sit in accumulation registers: park these 64 there for the whole kernel and
+  // leave the vector registers to the values that the vector ALU touches
+#pragma unroll
+  for (int c = 0; c < NC; c++) asm volatile("" : "+a"(kf[c]), "+a"(vf[c]));
+  f32x16 dkacc[ND], dvacc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) { dkacc[d][v] = 0.f; dvacc[d][v] = 0.f; }
+
+  const int q_begin = t.causal ? (t.tile0 / BQ) * BQ : 0;
+  const int wave_first_k = t.tile0 + 32 * wave;
+  const int n_it = grp * ((t.seg_len - q_begin + BQ - 1) / BQ);
+  const float c2 = p.scale_log2e;
+
+  // ---- loads ------------------------------------------------------------------------------------
+  constexpr int CPR = HD / 8, RPI = 64 / CPR, PER_WAVE = BQ / RPI / 4;
+  constexpr int PT = 2 * PER_WAVE + 1;   // load instructions per wavefront and tile
+  uint32_t q_off[PER_WAVE], do_off[PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; i++) {
+    const int r = (wave * PER_WAVE + i) * RPI + lane / CPR, c = (lane % CPR) ^ swz<HD>(r);
+    q_off[i] = (uint32_t)((r * p.q_stride + 8 * c) * 2);
+    do_off[i] = (uint32_t)((r * p.o_stride + 8 * c) * 2);
+  }
+  const uint32_t q_bytes = (uint32_t)(((int64_t)(t.seg_len - 1) * p.q_stride + HD) * 2);
+  const uint32_t do_bytes = (uint32_t)(((int64_t)(t.seg_len - 1) * p.o_stride + HD) * 2);
+  int nj = 0, nq0 = q_begin;          // the tile to be loaded next: query head nj of the group, rows from nq0
+  // Past the last tile the descriptors are empty and the loads write zeros.
+  const uint32_t lds_b = lds_address((MLLM_LDS const void*)lds);
+  // A tile's loads are enqueued in PT parts so that they can be spread over the MFMAs of a stage.
+  i32x4_t rq, rdo, rst;
+  uint32_t qrow, dorow, dst_t, dst_s;
+  auto issue_begin = [&](int stage) {
+    const bool valid = nj < grp;
+    const int head = kvh * grp + (valid ? nj : 0);
+    rq = raw_rsrc(p.q + (int64_t)t.seg_start * p.q_stride + head * HD, valid ? q_bytes : 0u);
+    rdo = raw_rsrc(p.d_o + (int64_t)t.seg_start * p.o_stride + head * HD, valid ? do_bytes : 0u);
+    // lse and delta of the tile's rows, 64 floats each, one instruction each: even wavefronts bring
+    // lse, odd ones delta (twice the same bytes, so that every wavefront counts the same loads).
+    // Rows past the segment read as zero; their dO rows are zero too, so they add nothing.
+    rst = raw_rsrc(((wave & 1) ? p.delta : p.lse) + (int64_t)head * p.T + t.seg_start, valid ? (uint32_t)t.seg_len * 4u : 0u);
+    qrow = (uint32_t)nq0 * (uint32_t)(p.q_stride * 2);
+    dorow = (uint32_t)nq0 * (uint32_t)(p.o_stride * 2);
+    dst_t = lds_b + (uint32_t)(stage * STAGE_B + (wave * PER_WAVE) * 1024);
+    dst_s = lds_b + (uint32_t)(STATS_AT + stage * STAT_STAGE_B + (wave & 1) * BQ * 4);
+  };
+  auto issue_part = [&](int j) {
+    if (j < PER_WAVE) load_to_lds_b128(rq, dst_t + j * 1024, q_off[j] + qrow);
+    else if (j < 2 * PER_WAVE) load_to_lds_b128(rdo, dst_t + TILE_B + (j - PER_WAVE) * 1024, do_off[j - PER_WAVE] + dorow);
+    else load_to_lds_b32(rst, dst_s, (uint32_t)(nq0 + lane) * 4u);
+  };
+  auto issue_end = [&]() {
+    nq0 += BQ;
+    if (nq0 >= t.seg_len) { nq0 = q_begin; nj++; }
+  };
+  auto issue = [&](int stage) {
+    issue_begin(stage);
+#pragma unroll
+    for (int j = 0; j < PT; j++) issue_part(j);
+    issue_end();
+  };
+
+  // ---- lane parts of the LDS offsets, stage included (advanced once per tile); block and operand ride
+  // in the instructions' offset fields ------------------------------------------------------------
+  // natural-layout fragment (frag_rows): tile row lane%32 of a 32-row block, 16-byte chunk 2c + h
+  // transposed fragment (frag_cols_permuted): rows 4h + i16/4 (+8), columns 32d + 16*(lane/16 % 2) + 4*(i16 % 4)
+  uint32_t rows_c[NC], rows_n[NC], cols_c[ND][2];   // _c: stage of the current tile, _n: of the next
+  {
+    const int r = lane & 31, i16 = lane & 15;
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+      rows_c[c] = (uint32_t)(r * HD + 8 * ((2 * c + h) ^ swz<HD>(r))) * 2u;
+      rows_n[c] = rows_c[c] + STAGE_B;
+    }
+#pragma unroll
+    for (int d = 0; d < ND; d++)
+#pragma unroll
+      for (int e = 0; e < 2; e++) {
+        const int k = 4 * h + (i16 >> 2) + 8 * e;
+        const int n = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+        cols_c[d][e] = (uint32_t)(k * HD + 8 * ((n >> 3) ^ swz<HD>(k)) + (n & 7)) * 2u;
+      }
+  }
+  uint32_t sa_c = STATS_AT + 16u * h, sa_n = sa_c + STAT_STAGE_B;
+  int st_c = 0;   // stage of the current tile
+
+  // ---- the two stages of a step ------------------------------------------------------------------
+  const lds_cptr rt = (lds_cptr)lds, rs = (lds_cptr)lds;
+  constexpr int NM = 2 * NC, EPS = 16 / NM, NPV = 2 * ND;
+  constexpr int RD = NM < 8 ? NM / 2 : 8;   // score fragments are read RD slots ahead of their MFMA
+  constexpr int PD = NPV < 8 ? NPV / 2 : 3;   // dV / dK fragments PD pairs ahead
+  constexpr int SP = NPV / 4;               // pairs of the second stage that fetch the next block's statistics
+  // carried from stage to stage
+  bf16x8 pre[RD];            // the first fragments of the next score stage
+  f32x16 s_n, dp_n;          // scores and dP of the block after the current one
+  float xs[16], ts[16];      // current block: exponent (s scale - lse) log2 e, and dP - delta
+  Frag8 pf[2], dsf[2];       // current block: P and dS as MFMA operands
+  Frag8 fdo[NPV], fq[NPV];   // current block: transposed dO and Q fragments
+  // transposing reads of pair i of the dV / dK products: rows 32 BC + 16 cc .. +15 of the current tile, columns 32 d .. +31
+  auto pair_reads = [&](int BC, int i, int part) {   // part 0: the dO fragment, 1: the Q fragment
+    const int cc = i / ND, d = i % ND;
+    const uint32_t o = BC * ROWS32_B + cc * ROWS16_B;
+    if (part == 0) { fdo[i].h[0] = lds_tr(rt, cols_c[d][0] + o + TILE_B); fdo[i].h[1] = lds_tr(rt, cols_c[d][1] + o + TILE_B); }
+    else { fq[i].h[0] = lds_tr(rt, cols_c[d][0] + o); fq[i].h[1] = lds_tr(rt, cols_c[d][1] + o); }
+  };
+  // Score stage: S and dP of block BN of the tile at offsets rows_x, one MFMA per slot; behind each
+  // MFMA a slice of the current block's (BC) vector work, P = exp2(xs), dS = P * ts, packed to bf16.
+  // An MFMA has no side effect the compiler must keep in place: left alone, those whose results are
+  // needed only later all move to the end of the loop body, out of their slots.  Passing each result
+  // through an empty volatile statement ties it between its neighbours.
+  auto sx = [&](auto BCt, auto BNt, const uint32_t (&rows_x)[NC]) {
+    constexpr int BC = decltype(BCt)::value, BN = decltype(BNt)::value;
+    bf16x8 fr[NM];
+#pragma unroll
+    for (int m = 0; m < RD; m++) fr[m] = pre[m];
+    float prv[16], dsv[16];
+    f32x16 zero;
+#pragma unroll
+    for (int v = 0; v < 16; v++) zero[v] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < NM; m++) {
+      if (m + RD < NM) {
+        fr[m + RD] = lds_b128(rt, rows_x[(m + RD) / 2] + ((m + RD) % 2) * TILE_B + BN * ROWS32_B);
+      } else {   // the last 2 PD slots fetch the fragments of the first PD pairs, one fragment per slot
+        const int j = m - (NM - 2 * PD);
+        if (j >= 0) pair_reads(BC, j / 2, j % 2);
+      }
+      if (m % 2 == 0) {
+        s_n = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m], kf[m / 2], m == 0 ? zero : s_n, 0, 0, 0);
+        asm volatile("" : "+a"(s_n));
+      } else {
+        dp_n = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m], vf[m / 2], m == 1 ? zero : dp_n, 0, 0, 0);
+        asm volatile("" : "+a"(dp_n));
+      }
+#pragma unroll
+      for (int e = 0; e < EPS; e++) {
+        const int v = m * EPS + e;
+        prv[v] = fast_exp2(xs[v]);
+        dsv[v] = prv[v] * ts[v];
+        if (v & 1) {
+          pf[v >> 3].w[(v >> 1) & 3] = pack_bf16x2(prv[v - 1], prv[v]);
+          dsf[v >> 3].w[(v >> 1) & 3] = pack_bf16x2(dsv[v - 1], dsv[v]);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // dV / dK stage of block BC: dV += dO^T.P, dK += Q^T.dS, a pair of MFMAs at a time.  Each pair
+  // follows the transposing reads of the pair PD further on; the last pairs carry the first reads
+  // of the next score stage instead (from rows_x, block BT).  The first pairs fetch the statistics of
+  // the next block (offset sa_x, block BN), the later ones turn them and the fresh scores into xs, ts;
+  // with ISSUE, the parts of a tile's loads ride along as well.
+  auto dx = [&](auto BCt, auto BNt, auto BTt, auto ISSUEt, const uint32_t (&rows_x)[NC], uint32_t sa_x) {
+    constexpr int BC = decltype(BCt)::value, BN = decltype(BNt)::value, BT = decltype(BTt)::value;
+    constexpr bool ISSUE = decltype(ISSUEt)::value != 0;
+    f32x4 st[8];   // lse of row groups 0..3, delta of row groups 0..3
+#pragma unroll
+    for (int i = 0; i < NPV; i++) {
+      const int cc = i / ND, d = i % ND;
+      if (i + PD < NPV) {
+        pair_reads(BC, i + PD, 0);
+        pair_reads(BC, i + PD, 1);
+      } else {
+        constexpr int PER = (RD + PD - 1) / PD;
+        const int j0 = (i - (NPV - PD)) * PER;
+#pragma unroll
+        for (int m = j0; m < j0 + PER && m < RD; m++) pre[m] = lds_b128(rt, rows_x[m / 2] + (m % 2) * TILE_B + BT * ROWS32_B);
+      }
+      if (i < SP) {
+#pragma unroll
+        for (int g = i * 8 / SP; g < (i + 1) * 8 / SP; g++)
+          st[g] = lds_f4(rs, sa_x + (g >= 4 ? BQ * 4 : 0) + (32 * BN + 8 * (g & 3)) * 4);
+      } else {
+#pragma unroll
+        for (int v = (i - SP) * 16 / (NPV - SP); v < (i - SP + 1) * 16 / (NPV - SP); v++) {
+          xs[v] = fmaf(s_n[v], c2, -(st[v >> 2][v & 3] * LOG2E));
+          ts[v] = dp_n[v] - st[4 + (v >> 2)][v & 3];
+        }
+      }
+      if (ISSUE) {
+#pragma unroll
+        for (int j = i * PT / NPV; j < (i + 1) * PT / NPV; j++) issue_part(j);
+      }
+      dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo[i].v, pf[cc].v, dvacc[d], 0, 0, 0);
+      asm volatile("" : "+a"(dvacc[d]));
+      dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[i].v, dsf[cc].v, dkacc[d], 0, 0, 0);
+      asm volatile("" : "+a"(dkacc[d]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Causal blocks on or above the diagonal: masked pairs get exponent -inf, i.e. probability zero.
+  auto mask_diag = [&](int q0b) {
+    if (t.causal && q0b <= wave_first_k + 31) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) xs[v] = (krow <= q0b + acc_row(v, h)) ? xs[v] : -INFINITY;
+    }
+  };
+
+  int q0 = q_begin;
+  // ---- prologue: tile 0 lands, its first block's scores are formed on their own ----------------
+#pragma unroll
+  for (int st = 0; st < NST - 1; st++) issue(st);
+  wait_loads<(NST - 2) * PT>();
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
+  {
+#pragma unroll
+    for (int v = 0; v < 16; v++) { s_n[v] = 0.f; dp_n[v] = 0.f; }
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+      s_n = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(rt, rows_c[c]), kf[c], s_n, 0, 0, 0);
+      dp_n = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(rt, rows_c[c] + TILE_B), vf[c], dp_n, 0, 0, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const f32x4 x = lds_f4(rs, sa_c + 8 * g * 4), y = lds_f4(rs, sa_c + BQ * 4 + 8 * g * 4);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        xs[4 * g + e] = fmaf(s_n[4 * g + e], c2, -(x[e] * LOG2E));
+        ts[4 * g + e] = dp_n[4 * g + e] - y[e];
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < RD; m++) pre[m] = lds_b128(rt, rows_c[m / 2] + (m % 2) * TILE_B + ROWS32_B);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // One tile per iteration.  Block 0: P, dS against the scores of block 1; then tile it+1 must have
+  // landed (the NST-3 tiles enqueued after it may still be on their way) and every wavefront must have
+  // left tile it-1, whose stage takes tile it+NST-1, enqueued under dV, dK of block 0.  Block 1: P, dS
+  // against the scores of block 0 of tile it+1, then its dV, dK.
+  for (int it = 0; it < n_it; it++) {
+    mask_diag(q0);
+    sx(Int<0>{}, Int<1>{}, rows_c);
+    wait_loads<(NST - 3) * PT>();
+    __syncthreads();
+    issue_begin(st_c == 0 ? NST - 1 : st_c - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    dx(Int<0>{}, Int<1>{}, Int<0>{}, Int<1>{}, rows_n, sa_c);
+    issue_end();
+    mask_diag(q0 + 32);
+    sx(Int<1>{}, Int<0>{}, rows_n);
+    dx(Int<1>{}, Int<0>{}, Int<1>{}, Int<0>{}, rows_n, sa_n);
+    // rotate the stages
+    q0 += BQ;
+    if (q0 >= t.seg_len) q0 = q_begin;
+    const int st_n = st_c + 1 == NST ? 0 : st_c + 1, st_nn = st_n + 1 == NST ? 0 : st_n + 1;
+    const uint32_t dc = st_n == 0 ? (uint32_t)(-(NST - 1) * STAGE_B) : (uint32_t)STAGE_B;
+    const uint32_t dn = st_nn == 0 ? (uint32_t)(-(NST - 1) * STAGE_B) : (uint32_t)STAGE_B;
+#pragma unroll
+    for (int c = 0; c < NC; c++) { rows_c[c] += dc; rows_n[c] += dn; }
+#pragma unroll
+    for (int d = 0; d < ND; d++) { cols_c[d][0] += dc; cols_c[d][1] += dc; }
+    sa_c += st_n == 0 ? (uint32_t)(-(NST - 1) * STAT_STAGE_B) : (uint32_t)STAT_STAGE_B;
+    sa_n += st_nn == 0 ? (uint32_t)(-(NST - 1) * STAT_STAGE_B) : (uint32_t)STAT_STAGE_B;
+    st_c = st_n;
+  }
+  // the loads enqueued last (tiles past the end: zeros) must have landed before this workgroup's LDS
+  // can be handed to another one
+  wait_loads<0>();
+  if (!kok) return;
+  float out_scale = p.scale;
+  if (p.rope_table) {
+    rope_unrotate<HD>(dkacc, p.rope_table, krow, h, p.scale);
+    out_scale = 1.f;
+  }
+  bf16_t* dkp = p.dk + gkrow * p.kv_stride + kvh * HD;
+  bf16_t* dvp = p.dv + gkrow * p.kv_stride + kvh * HD;
+#pragma unroll
+  for (int d = 0; d < ND; d++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      uint2 w;
+      w.x = pack_bf16x2(dkacc[d][4 * g4] * out_scale, dkacc[d][4 * g4 + 1] * out_scale);
+      w.y = pack_bf16x2(dkacc[d][4 * g4 + 2] * out_scale, dkacc[d][4 * g4 + 3] * out_scale);
+      *reinterpret_cast<uint2*>(dkp + 32 * d + 8 * g4 + 4 * h) = w;
+      w.x = pack_bf16x2(dvacc[d][4 * g4], dvacc[d][4 * g4 + 1]);
+      w.y = pack_bf16x2(dvacc[d][4 * g4 + 2], dvacc[d][4 * g4 + 3]);
+      *reinterpret_cast<uint2*>(dvp + 32 * d + 8 * g4 + 4 * h) = w;
+    }
+}
+
 AttnParams make_params(const AttnArgs& a) {
   AttnParams p;
   p.q = (const bf16_t*)a.q; p.k = (const bf16_t*)a.k; p.v = (const bf16_t*)a.v;
@@ -740,7 +1111,7 @@ hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
     p.list = (const AttnItem*)a.q_list;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, qgrid, block, 0, s, p);
     p.list = (const AttnItem*)a.kv_list;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, kgrid, block, 0, s, p);
+    hipLaunchKernelGGL(attn_bwd_dkv_pipe_kernel<128>, kgrid, block, 0, s, p);
   } else if (a.head_dim == 64) {
     p.list = (const AttnItem*)a.q_list;
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, qgrid, block, 0, s, p);
