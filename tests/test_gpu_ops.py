@@ -32,12 +32,19 @@ def B():
 @pytest.mark.parametrize("m,n,k", [(263, 576, 192), (128, 128, 64), (300, 256, 1024), (1, 64, 64), (517, 192, 263 * 8)])
 @pytest.mark.parametrize("a_layout,b_layout", [(0, 0), (0, 1), (1, 0), (1, 1)])
 def test_gemm_layouts(B, m, n, k, a_layout, b_layout):
-    if (a_layout and m % 8) or (b_layout and k % 8) or (not a_layout and k % 8):
-        pytest.skip("contiguous dimension not a multiple of 8")
     a = W.draw_tensor(1, m, k)
     b = W.draw_tensor(2, k, n) * np.float32(0.125)
     a_st = np.ascontiguousarray(a.T) if a_layout else a
     b_st = np.ascontiguousarray(b.T) if b_layout else b
+    if (a_layout and m % 8) or (b_layout and k % 8) or (not a_layout and k % 8):
+        # an operand whose contiguous dimension is no multiple of 8 is outside the API: refused, nothing written
+        c = torch.full((m, n), 3.0, dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(B.MllmError) as e:
+            B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout)
+        assert e.value.status == 3 and "multiples of 8" in str(e.value)
+        torch.cuda.synchronize()
+        assert bool((c == 3.0).all())
+        return
     ref = a.astype(np.float64) @ b.astype(np.float64)
     c = empty_bf16(m, n)
     B.mllm_op_gemm(dev_bf16(a_st), dev_bf16(b_st), c, m, n, k, a_layout, b_layout)
