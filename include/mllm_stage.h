@@ -299,6 +299,15 @@ mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const vo
                                const float* stats, const void* dres, void* dx, float* dgamma,
                                float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
                                void* hip_stream);
+/* The same, and the column sums of dx (fp32 [d], accumulate != 0: +=), taken from the values of dx
+ * before they are rounded to bf16, in the same pass.  dx is the output gradient of the linear map in
+ * front of the residual stream (an encoder layer's output projection, or the second MLP matrix of the
+ * encoder layer below), so these sums are that map's bias gradient (Model Profiler, "Throughput
+ * Profiling": the encoder's linear operations).  Only for d <= 1024 (MLLM_ERR_SHAPE beyond). */
+mllm_status_t mllm_op_norm_bwd_colsum(int kind, const void* dy, const void* x, const void* gamma,
+                                      const float* stats, const void* dres, void* dx, float* dgamma,
+                                      float* dbeta, float* dx_colsum, int accumulate, float* partial,
+                                      int64_t t, int64_t d, void* hip_stream);
 
 /* Rotary positions applied in place to the q and k column blocks of a packed [T, row_stride]
  * bf16 buffer (n_heads heads of head_dim starting at column col0).  pos: device int32 [T];

@@ -23,7 +23,7 @@ STATUS_NAMES = ["MLLM_OK", "MLLM_ERR_NULL", "MLLM_ERR_DESC", "MLLM_ERR_SHAPE", "
 EXPORTS = ["mllm_stage_create", "mllm_stage_destroy", "mllm_stage_param_count", "mllm_stage_param_info",
            "mllm_stage_sizes", "mllm_stage_fwd", "mllm_stage_bwd", "mllm_last_error", "mllm_op_gemm",
            "mllm_op_gemm_swiglu", "mllm_op_gemm_swiglu_bwd", "mllm_op_attn_workspace_bytes", "mllm_attn_work_list", "mllm_op_attn_fwd", "mllm_op_attn_bwd", "mllm_op_norm_fwd",
-           "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_rope", "mllm_op_rope_table", "mllm_op_gemm_rope", "mllm_op_attn_bwd_rope", "mllm_op_act_fwd",
+           "mllm_op_norm_bwd_partial_bytes", "mllm_op_norm_bwd", "mllm_op_norm_bwd_colsum", "mllm_op_rope", "mllm_op_rope_table", "mllm_op_gemm_rope", "mllm_op_attn_bwd_rope", "mllm_op_act_fwd",
            "mllm_op_act_bwd", "mllm_op_colsum_partial_bytes", "mllm_op_colsum", "mllm_op_colsum_static_max_bytes", "mllm_op_colsum_static", "mllm_profile_begin",
            "mllm_profile_end", "mllm_schedule_lpt", "mllm_schedule", "mllm_interp", "mllm_item_durations",
            "mllm_find_combs", "mllm_evaluate_parallelism", "mllm_optimize_parallelism"]
@@ -110,6 +110,7 @@ def lib() -> C.CDLL:
     L.mllm_op_norm_bwd_partial_bytes.argtypes = [i64, i64]
     L.mllm_op_norm_bwd_partial_bytes.restype = sz
     L.mllm_op_norm_bwd.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, i64, i64, vp]
+    L.mllm_op_norm_bwd_colsum.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, i64, i64, vp]
     L.mllm_op_rope.argtypes = [vp, vp, i64, i64, i64, i32, i32, C.c_float, C.c_int, vp]
     L.mllm_op_rope_table.argtypes = [vp, i64, i32, C.c_float, vp]
     L.mllm_op_gemm_rope.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, i32, vp]
@@ -321,6 +322,13 @@ def mllm_op_norm_fwd(kind, x, gamma, beta, y, stats, t, d, eps, stream=None) -> 
 
 def mllm_op_norm_bwd_partial_bytes(t: int, d: int) -> int:
     return int(lib().mllm_op_norm_bwd_partial_bytes(t, d))
+
+
+def mllm_op_norm_bwd_colsum(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, dx_colsum, accumulate, partial, t, d,
+                            stream=None) -> None:
+    _check(lib().mllm_op_norm_bwd_colsum(kind, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(stats), _ptr(dres), _ptr(dx),
+                                         _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum), int(accumulate), _ptr(partial), t, d,
+                                         _stream(stream)))
 
 
 def mllm_op_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d,

@@ -727,6 +727,8 @@ template <int V> using Int = std::integral_constant<int, V>;
 // numbers are run-time values.  The kernel that uses these waits for its loads by count and
 // separates writers from readers with barriers, as it has to anyway.
 // The 64 lanes' 16 (or 4) bytes land side by side from LDS address `lds_addr` (wavefront-uniform).
+// The statements set M0 themselves; M0 is a reserved register that the compiler holds no value in and
+// sets anew in front of each of its own uses, so overwriting it here disturbs nothing.
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ i32x4_t raw_rsrc(const void* base, uint32_t bytes) {   // untyped buffer over [base, base + bytes)
   const uint64_t b = (uint64_t)base;

@@ -180,14 +180,18 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
 // added pairwise (s with s+64, then s with s+32, ...): a fixed association, so the result is
 // bitwise reproducible.
 constexpr int RED_COLS = 8, RED_SLICES = 128;
-// blockIdx.y = 1 (when launched with two rows of workgroups) reduces a second set of partial sums,
-// P * n floats further on, into out1: a norm's two gradients go in one launch.
+// blockIdx.y = 1, 2 (when launched with two or three rows of workgroups) reduce a second and third
+// set of partial sums, P * n and 2 P * n floats further on, into out1 and out2: a norm's gradients go
+// in one launch.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial,
                                                               float* __restrict__ out, int P,
                                                               int64_t n, int accumulate,
-                                                              float* __restrict__ out1 = nullptr) {
+                                                              float* __restrict__ out1 = nullptr,
+                                                              float* __restrict__ out2 = nullptr) {
   __shared__ float4 part[RED_SLICES][RED_COLS / 4];
   if (blockIdx.y == 1) { partial += (int64_t)P * n; out = out1; }
+  if (blockIdx.y == 2) { partial += 2 * (int64_t)P * n; out = out2; }
+  if (!out) return;   // a set that this launch does not carry
   const int cg = threadIdx.x & 1, slice = threadIdx.x >> 1;
   const int64_t c = ((int64_t)blockIdx.x * (RED_COLS / 4) + cg) * 4;
   const bool valid = c < n;
@@ -534,22 +538,28 @@ hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const voi
 
 // Narrow rows (d <= 1024): a wavefront owns a row, so there is no barrier per row and all 256
 // threads have data; the four wavefronts' column sums are added through LDS once at the end.
-template <int KIND, int NV>
+// CS: the column sums of dx (as computed, before rounding to bf16) come out as a third set of
+// partial sums: dx is the gradient of a linear map's output whenever the layer below or the
+// attention block above the norm ends in one, and those sums are that map's bias gradient.
+template <int KIND, int NV, bool CS>
 __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
     const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
     float* __restrict__ partial, int64_t T, int d, int64_t ld) {
-  __shared__ float red[2][4][1024];  // [d gamma | d beta][wavefront][column]
+  __shared__ float red[CS ? 3 : 2][4][1024];  // [d gamma | d beta | column sums of dx][wavefront][column]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int B = gridDim.x, b = blockIdx.x;
   const int nvec = d >> 3;
-  float g[NV][8], dg[NV][8], db[NV][8];
+  float g[NV][8], dg[NV][8], db[NV][8], dc[CS ? NV : 1][8];
 #pragma unroll
   for (int j = 0; j < NV; j++) {
     const int c = lane + 64 * j;
     if (c < nvec) unpack8(*reinterpret_cast<const uint4*>(gamma + 8 * c), g[j]);
 #pragma unroll
-    for (int e = 0; e < 8; e++) { dg[j][e] = 0.f; db[j][e] = 0.f; if (c >= nvec) g[j][e] = 0.f; }
+    for (int e = 0; e < 8; e++) {
+      dg[j][e] = 0.f; db[j][e] = 0.f; if (c >= nvec) g[j][e] = 0.f;
+      if (CS) dc[j][e] = 0.f;
+    }
   }
   // The next row's loads are issued before this row's arithmetic: two rows in flight per wavefront.
   uint4 nx[NV], ndy[NV], nres[NV];
@@ -601,7 +611,10 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
       if (c < nvec) {
         float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd + r[j][e];
+        for (int e = 0; e < 8; e++) {
+          o[e] = (dxh[j][e] - m1 - xh[j][e] * m2) * rstd + r[j][e];
+          if (CS) dc[j][e] += o[e];
+        }
         *reinterpret_cast<uint4*>(dx + row * ld + 8 * c) = pack8(o);
       }
     }
@@ -611,7 +624,11 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
     const int c = lane + 64 * j;
     if (c < nvec) {
 #pragma unroll
-      for (int e = 0; e < 8; e++) { red[0][wave][8 * c + e] = dg[j][e]; red[1][wave][8 * c + e] = db[j][e]; }
+      for (int e = 0; e < 8; e++) {
+        red[0][wave][8 * c + e] = dg[j][e];
+        red[1][wave][8 * c + e] = db[j][e];
+        if (CS) red[2][wave][8 * c + e] = dc[j][e];
+      }
     }
   }
   __syncthreads();
@@ -619,8 +636,12 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
     partial[(int64_t)b * d + col] = (red[0][0][col] + red[0][1][col]) + (red[0][2][col] + red[0][3][col]);
     if (KIND == 0)
       partial[(int64_t)(B + b) * d + col] = (red[1][0][col] + red[1][1][col]) + (red[1][2][col] + red[1][3][col]);
+    if (CS)
+      partial[(int64_t)(2 * B + b) * d + col] = (red[2][0][col] + red[2][1][col]) + (red[2][2][col] + red[2][3][col]);
   }
 }
+
+bool norm_bwd_colsum_fusable(int64_t d) { return d % 8 == 0 && d / 8 <= 128; }
 
 int64_t norm_bwd_partial_rows(int64_t t) {
   return t < 1 ? 1 : (t > 1024 ? 1024 : t);
@@ -629,8 +650,9 @@ int64_t norm_bwd_partial_rows(int64_t t) {
 hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
                            const float* stats, const void* dres, void* dx, float* dgamma,
                            float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
-                           int64_t ld, hipStream_t s) {
+                           int64_t ld, hipStream_t s, float* dx_colsum) {
   if (d % 8 != 0 || d > 8192 || ld < d || ld % 8 != 0) return hipErrorInvalidValue;
+  if (dx_colsum && !norm_bwd_colsum_fusable(d)) return hipErrorInvalidValue;
   const int64_t nvec = d / 8;
   // Workgroups (= rows of partial sums).  The wavefront-per-row kernel with two vectors per lane
   // keeps three workgroups per CU resident: a grid of 768 runs in one round.
@@ -643,19 +665,21 @@ hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* 
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
   else hipLaunchKernelGGL((norm_bwd_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld);
-#define CALL_WAVE(NV)                                                                                   \
-  if (kind == 0) hipLaunchKernelGGL((norm_bwd_wave_kernel<0, NV>), grid, block, 0, s, (const bf16_t*)dy, \
-      (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld); \
-  else hipLaunchKernelGGL((norm_bwd_wave_kernel<1, NV>), grid, block, 0, s, (const bf16_t*)dy,           \
+#define CALL_WAVE_CS(KIND, NV, CS)                                                                          \
+  hipLaunchKernelGGL((norm_bwd_wave_kernel<KIND, NV, CS>), grid, block, 0, s, (const bf16_t*)dy,             \
       (const bf16_t*)x, (const bf16_t*)gamma, stats, (const bf16_t*)dres, (bf16_t*)dx, partial, t, (int)d, ld);
+#define CALL_WAVE(NV)                                                                       \
+  if (kind == 0) { if (dx_colsum) { CALL_WAVE_CS(0, NV, true) } else { CALL_WAVE_CS(0, NV, false) } } \
+  else { if (dx_colsum) { CALL_WAVE_CS(1, NV, true) } else { CALL_WAVE_CS(1, NV, false) } }
   if (nvec <= 64) { CALL_WAVE(1) } else if (nvec <= 128) { CALL_WAVE(2) }
   else if (nvec <= 256) { CALL(1) } else if (nvec <= 512) { CALL(2) } else { CALL(4) }
 #undef CALL_WAVE
+#undef CALL_WAVE_CS
 #undef CALL
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS), kind == 0 ? 2 : 1), dim3(256), 0, s, partial,
-                     dgamma, (int)W, d, accumulate, kind == 0 ? dbeta : nullptr);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(d, RED_COLS), dx_colsum ? 3 : (kind == 0 ? 2 : 1)), dim3(256), 0, s,
+                     partial, dgamma, (int)W, d, accumulate, kind == 0 ? dbeta : nullptr, dx_colsum);
   return hipGetLastError();
 }
 

@@ -89,7 +89,10 @@ int64_t norm_bwd_partial_rows(int64_t t);
 hipError_t launch_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
                            const float* stats, const void* dres, void* dx, float* dgamma,
                            float* dbeta, int accumulate, float* partial, int64_t t, int64_t d,
-                           int64_t ld, hipStream_t s);
+                           int64_t ld, hipStream_t s, float* dx_colsum = nullptr);
+// dx_colsum (optional, fp32 [d]): the column sums of dx, formed in the same pass; only for rows of at
+// most 1024 elements (norm_bwd_colsum_fusable).  `partial` then holds three sets of sums.
+bool norm_bwd_colsum_fusable(int64_t d);
 hipError_t launch_rope(void* qk, const int32_t* pos, int64_t t, int64_t row_stride, int64_t col0,
                        int32_t n_heads, int32_t head_dim, float rope_base, int inverse,
                        hipStream_t s);

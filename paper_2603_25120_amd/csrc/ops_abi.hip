@@ -298,7 +298,7 @@ mllm_status_t mllm_op_norm_fwd(int kind, const void* x, const void* gamma, const
 }
 
 size_t mllm_op_norm_bwd_partial_bytes(int64_t t, int64_t d) {
-  return (size_t)norm_bwd_partial_rows(t) * (size_t)d * 4 * 2;
+  return (size_t)norm_bwd_partial_rows(t) * (size_t)d * 4 * 3;
 }
 
 mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const void* gamma,
@@ -309,6 +309,20 @@ mllm_status_t mllm_op_norm_bwd(int kind, const void* dy, const void* x, const vo
   if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
   if (t < 0 || d <= 0 || d % 8 || d > 8192) return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 8192");
   OP_TRY(launch_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d, d, (hipStream_t)hip_stream));
+  return MLLM_OK;
+}
+
+mllm_status_t mllm_op_norm_bwd_colsum(int kind, const void* dy, const void* x, const void* gamma,
+                                      const float* stats, const void* dres, void* dx, float* dgamma,
+                                      float* dbeta, float* dx_colsum, int accumulate, float* partial,
+                                      int64_t t, int64_t d, void* hip_stream) {
+  if (!dy || !x || !gamma || !stats || !dx || !dgamma || !dx_colsum || !partial || (kind == 0 && !dbeta))
+    return op_fail(MLLM_ERR_NULL, "a pointer is NULL");
+  if (kind != 0 && kind != 1) return op_fail(MLLM_ERR_SHAPE, "kind must be 0 or 1");
+  if (t < 0 || d <= 0 || d % 8 || !norm_bwd_colsum_fusable(d))
+    return op_fail(MLLM_ERR_SHAPE, "d must be a multiple of 8, at most 1024");
+  OP_TRY(launch_norm_bwd(kind, dy, x, gamma, stats, dres, dx, dgamma, dbeta, accumulate, partial, t, d, d,
+                         (hipStream_t)hip_stream, dx_colsum));
   return MLLM_OK;
 }
 

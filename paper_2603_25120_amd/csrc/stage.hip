@@ -340,7 +340,7 @@ Plan make_plan(const mllm_stage* st, const mllm_batch_t* b) {
     P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)(T * widest * 2));
     // the attention kernels' 32-bit row offsets may run 256 rows past the last token
     P.largest_operand_bytes = std::max<int64_t>(P.largest_operand_bytes, (int64_t)((T + 256) * std::max(nq, d) * 2));
-    part = std::max(part, (size_t)norm_bwd_partial_rows(T) * d * 4 * 2);
+    part = std::max(part, (size_t)norm_bwd_partial_rows(T) * d * 4 * 3);
     part = std::max(part, (size_t)colsum_partial_rows(T) * widest * 4);
     a = std::max(a, T * f * 2);
     bb = std::max(bb, L.kind == MLLM_LAYER_DECODER ? T * 2 * f * 2 : 0);
@@ -597,7 +597,9 @@ mllm_status_t layer_fwd(const mllm_layer_desc_t& L, const void* const* prm, cons
 mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void* const* dprm,
                         int accumulate, const LayerSaved& S, const char* saved, char* ws,
                         const Plan& P, int64_t T, const void* dy, void* dx, const float* rope_table,
-                        int attn_list, hipStream_t s) {
+                        int attn_list, hipStream_t s, bool dy_colsum_done, float* dx_colsum) {
+  // dy_colsum_done: the layer above has already formed the column sums of dy (this layer's b_2
+  // gradient) while writing dy; dx_colsum: where to leave the column sums of dx for the layer below.
   const bool vit = L.kind == MLLM_LAYER_VIT;
   const int64_t d = L.d_model, f = L.d_ff, nq = nqkv_of(L);
   const char* x = saved + S.x;
@@ -623,7 +625,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
 
   // MLP
   K_TRY(linear_dw(act, dy, dprm[iwdn], T, f, d, accumulate, s, split));
-  if (vit) K_TRY(launch_colsum(dy, d, (float*)dprm[ibdn], accumulate, partial, T, d, s));
+  if (vit && !dy_colsum_done) K_TRY(launch_colsum(dy, d, (float*)dprm[ibdn], accumulate, partial, T, d, s));
   char* dpre = vit ? wa : wb;
   if (!vit && gemm_swiglu_bwd_fusable(T, f, d)) {
     K_TRY(linear_dx_swiglu(dy, prm[iwdn], pre, dpre, T, f, d, s));
@@ -636,11 +638,15 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   }
   K_TRY(linear_dw(n2, dpre, dprm[iwup], T, d, fup, accumulate, s, split));
   K_TRY(linear_dx(dpre, prm[iwup], wc, T, d, fup, s));
+  // the gradient that leaves this norm is that of the output projection's output: its column sums are
+  // the projection's bias gradient, formed in the same pass where the row width allows
+  const bool bo_fused = vit && norm_bwd_colsum_fusable(d);
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x1, prm[ig2], (const float*)(saved + S.stats2), dy, wd,
-                        (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, d, s));
+                        (float*)dprm[ig2], vit ? (float*)dprm[ib2n] : nullptr, accumulate, partial, T, d, d, s,
+                        bo_fused ? (float*)dprm[ibo] : nullptr));
   // attention block
   K_TRY(linear_dw(o, wd, dprm[iwo], T, d, d, accumulate, s, split));
-  if (vit) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
+  if (vit && !bo_fused) K_TRY(launch_colsum(wd, d, (float*)dprm[ibo], accumulate, partial, T, d, s));
   K_TRY(linear_dx(wd, prm[iwo], wc, T, d, d, s));
   // With QK normalisation the gradient of the normalised q, k goes to a matrix of its own (same
   // columns as in d qkv); the norm's backward then writes the gradient of the projection's q, k
@@ -670,7 +676,7 @@ mllm_status_t layer_bwd(const mllm_layer_desc_t& L, const void* const* prm, void
   if (ibqkv >= 0) K_TRY(launch_colsum(we, nq, (float*)dprm[ibqkv], accumulate, partial, T, nq, s));
   K_TRY(linear_dx(we, prm[iwqkv], wc, T, d, nq, s));
   K_TRY(launch_norm_bwd(vit ? 0 : 1, wc, x, prm[ig1], (const float*)(saved + S.stats1), wd, dx,
-                        (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, d, s));
+                        (float*)dprm[ig1], vit ? (float*)dprm[ib1n] : nullptr, accumulate, partial, T, d, d, s, dx_colsum));
   return MLLM_OK;
 }
 
@@ -883,6 +889,7 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
   const void* cur = dy;  // gradient w.r.t. the output of layer i
   char* pp[2] = {ws + P.w_g0, ws + P.w_g1};
   int flip = 0;
+  bool colsum_done = false;   // the column sums of `cur` are already in the bias gradient they belong to
   for (int i = n - 1; i >= 0; i--) {
     const mllm_layer_desc_t& L = st->layers[i];
     const void* const* prm = params + st->param_off[i];
@@ -921,6 +928,7 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
                                  (const int32_t*)(ws + P.meta.pool_count), P.T_img, L.d_model, s));
       cur = out;
       flip ^= 1;
+      colsum_done = false;
       continue;
     }
     const bool vit = L.kind == MLLM_LAYER_VIT;
@@ -931,7 +939,16 @@ mllm_status_t mllm_stage_bwd(mllm_stage_t* st, const mllm_batch_t* b, const void
       if (want) out = want;
     }
     const float* rope_table = P.rope_of[i] >= 0 ? (const float*)(ws + P.rope_tables[P.rope_of[i]].off) : nullptr;
-    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, rope_table, P.attn_of[i], s)) != MLLM_OK) return r;
+    // An encoder layer's input gradient is the output gradient of the encoder layer below it, whose last
+    // linear map has a bias (index 11 of its parameters): its gradient, the column sums of that tensor, is
+    // formed while this layer's last norm writes the tensor.
+    float* below = nullptr;
+    if (vit && i > 0 && st->layers[i - 1].kind == MLLM_LAYER_VIT && st->layers[i - 1].d_model == L.d_model &&
+        norm_bwd_colsum_fusable(L.d_model))
+      below = (float*)(dparams + st->param_off[i - 1])[11];
+    if ((r = layer_bwd(L, prm, dprm, accumulate, P.saved[i], saved, ws, P, T, cur, out, rope_table, P.attn_of[i], s,
+                       colsum_done, below)) != MLLM_OK) return r;
+    colsum_done = below != nullptr;
     cur = out;
     flip ^= 1;
   }

@@ -251,6 +251,7 @@ ATTN_CASES = [
     (128, 4, 2, [300, 5, 127, 128, 129], [1, 0, 1, 0, 1]),
     (128, 8, 2, [700], [1]),
     (64, 2, 2, [576, 576], [0, 0]),
+    (128, 2, 1, [0, 1, 64, 65, 191, 260], [1, 0, 1, 0, 1, 1]),   # empty, one-row and just-over-a-tile samples, one kv head
 ]
 
 
@@ -335,6 +336,21 @@ def test_norm_fwd_bwd(B, kind, t, d):
     assert nmax_err(host_f64(dgam), dg_ref[0] + 1.0) < 2e-3
     if kind == 0:
         assert nmax_err(host_f64(dbet), db_ref[0] + 1.0) < 2e-3
+    if d > 1024:
+        with pytest.raises(B.MllmError):
+            B.mllm_op_norm_bwd_colsum(kind, dev_bf16(dy), dx_, dg_, stats, dev_bf16(dres), dx, dgam, dbet, dgam, 0, part, t, d)
+        return
+    # the same pass also sums the columns of dx (before rounding): dx itself and the other sums must not change
+    dx2 = empty_bf16(t, d)
+    dgam2 = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    dbet2 = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    dcol = torch.full((d,), -2.0, dtype=torch.float32, device="cuda")
+    B.mllm_op_norm_bwd_colsum(kind, dev_bf16(dy), dx_, dg_, stats, dev_bf16(dres), dx2, dgam2, dbet2, dcol, 1, part, t, d)
+    assert torch.equal(dx2, dx)
+    assert nmax_err(host_f64(dgam2), dg_ref[0] + 1.0) < 2e-3
+    if kind == 0:
+        assert nmax_err(host_f64(dbet2), db_ref[0] + 1.0) < 2e-3
+    assert nmax_err(host_f64(dcol), dx_ref.sum(axis=0) - 2.0) < 2e-3
 
 
 @pytest.mark.parametrize("hd,base", [(64, 10000.0), (128, 500000.0)])
