@@ -7,7 +7,11 @@ end-to-end error of the stack says little about any one layer.  Here each layer 
 * The stack is run once as ONE stage (what the benchmark times) and once as a chain of 33
   single-layer stages, each fed the previous one's output (forward) or input gradient (backward).
   Both must agree bit for bit: the chain runs the same kernels on the same shapes, so its
-  per-layer tensors are the stack's own intermediate tensors.
+  per-layer tensors are the stack's own intermediate tensors.  One exception: inside a stack the
+  gradient of an encoder layer's last bias (b_2: the column sums of the layer's output gradient) is
+  formed by the layer ABOVE while it writes that output gradient, from the values before they are
+  rounded to bf16; a lone layer sums the rounded tensor.  Those gradients must agree to 5e-3 (the
+  rounding of the summands), and the in-place check below takes the stack's own value for them.
 * For every layer the fp64 oracle's single layer then takes the GPU's OWN layer input (and, in
   backward, the GPU's own upstream gradient) and must reproduce the GPU's layer output and its
   input gradient within the stated 2e-2 / 3e-2, unscaled.  The layer's own contribution, the
@@ -140,8 +144,12 @@ def test_chain_of_single_layer_stages_is_the_stack_bit_for_bit(stack):
     assert torch.equal(stack["dx_seq_text"], dxs_full)
     flat = [g for dp in stack["dps"] for g in dp]
     assert len(flat) == len(dp_full)
+    formed_above = {stack["offs"][l] + 11 for l in range(N_VIT - 1)}   # b_2 of an encoder layer below an encoder layer
     for i, (a, b) in enumerate(zip(flat, dp_full)):
-        assert torch.equal(a, b), "parameter gradient %d differs between the chain and the stack" % i
+        if i in formed_above:
+            assert nmax_err(host_f64(a), host_f64(b)) < 5e-3, "b_2 gradient %d: chain and stack apart" % i
+        else:
+            assert torch.equal(a, b), "parameter gradient %d differs between the chain and the stack" % i
 
 
 def _picked_samples(batch):
@@ -205,6 +213,8 @@ def test_layer_in_situ(stack, i):
         names = [n for n, _, _ in W.param_specs(L)]
         for name, g, r in zip(names, stack["dps"][i], dp_ref):
             errs["d." + name] = nmax_err(host_f64(g), r)
+        if L.kind == W.LAYER_VIT and i < N_VIT - 1:   # the stack's own b_2 gradient (formed by the layer above)
+            errs["d.b_2 (stack)"] = nmax_err(host_f64(stack["full"][3][stack["offs"][i] + 11]), dp_ref[11])
     print("layer %d (%s rows %d): %s" % (i, "all" if full else "sampled", y_g.shape[0],
                                           ", ".join("%s %.2e" % kv for kv in errs.items())), flush=True)
     assert errs["y"] <= TOL_OUT, errs
