@@ -46,23 +46,41 @@ __device__ __forceinline__ s16x4 lds_read_tr4(const bf16_t* tile, int stride, in
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLLM_LDS s16x4*)p);
 }
 
+// erf to 1.5e-7 absolute (Abramowitz and Stegun 7.1.26: 1 - (a1 t + ... + a5 t^5) exp(-x^2) with
+// t = 1 / (1 + p |x|), odd in x), with the hardware reciprocal and exp2: a dozen instructions where
+// the library routine takes several times as many, which made the GELU kernels ALU-bound.  The
+// results are rounded to bf16 (2^-9 relative), far above this error.
+__device__ __forceinline__ float fast_erf(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
+  return copysignf(fmaf(-p * t, e, 1.f), x);
+}
 // GELU (act 0: exact erf form, 1: tanh form) and its derivative.
+// tanh through the hardware exp2 and reciprocal: 1 - 2 / (1 + e^(2u)); exact at both ends (e = inf or 0).
+__device__ __forceinline__ float fast_tanh(float u) {
+  return fmaf(-2.f, __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(2.8853900817779268f * u)), 1.f);
+}
 __device__ __forceinline__ float gelu_f(int act, float z) {
   if (act == 1) {
     float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    return 0.5f * z * (1.f + tanhf(u));
+    return 0.5f * z * (1.f + fast_tanh(u));
   }
-  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
+  return 0.5f * z * (1.f + fast_erf(z * 0.7071067811865476f));
 }
 __device__ __forceinline__ float gelu_grad_f(int act, float z) {
   if (act == 1) {
     float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    float t = tanhf(u);
+    float t = fast_tanh(u);
     return 0.5f * (1.f + t) +
            0.5f * z * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * z * z);
   }
-  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) +
-         z * expf(-0.5f * z * z) * 0.3989422804014327f;
+  return 0.5f * (1.f + fast_erf(z * 0.7071067811865476f)) +
+         z * __builtin_amdgcn_exp2f(-0.7213475204444817f * z * z) * 0.3989422804014327f;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

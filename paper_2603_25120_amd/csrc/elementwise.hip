@@ -542,7 +542,7 @@ hipError_t launch_norm_fwd(int kind, const void* x, const void* gamma, const voi
 // partial sums: dx is the gradient of a linear map's output whenever the layer below or the
 // attention block above the norm ends in one, and those sums are that map's bias gradient.
 template <int KIND, int NV, bool CS>
-__global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
+__global__ __launch_bounds__(256, 3) void norm_bwd_wave_kernel(
     const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const float* __restrict__ stats, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
     float* __restrict__ partial, int64_t T, int d, int64_t ld) {
