@@ -493,8 +493,7 @@ __global__ void splitk_reduce_kernel(const float4* __restrict__ partial, float4*
                                      int splits, int64_t nvec, int accumulate) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= nvec) return;
-  // the parts are added in their order, four loads in flight at a time (one after the other, each
-  // waited for, the kernel ran at half the memory rate)
+  // the parts are added in their order; four of their loads are in flight at a time
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   if (accumulate) o = out[i];
   float4 t = partial[i];
